@@ -1,0 +1,143 @@
+/*
+ * kitty.h — C ABI of libkitty: page quantizer and decode attention over Kitty's page-centric
+ * 2-bit KV cache (arXiv 2511.18643) for AMD MI355X (gfx950).
+ *
+ * Conventions shared by every entry point
+ *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are ordinary
+ *     host memory.  The library never allocates, frees or retains device memory.
+ *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = default stream) and
+ *     the call returns without synchronising.  Structs are read during the call only.
+ *   - Return value: KITTY_OK, or a negative KITTY_ERR_* code; when an error is returned nothing has
+ *     been enqueued.  No exceptions cross the boundary.
+ *   - Tensors are bf16 (1-8-7 bit patterns) with the channel index contiguous; cache metadata is
+ *     IEEE fp16.  Inputs holding NaN/Inf or |x| > 65504 are outside the contract (fp16 metadata
+ *     would saturate); this is not checked.
+ *   - head_dim D = 128 and page_size G = 128 are the only supported sizes (the paper's models,
+ *     Sec. 4.1 and Fig. 1 caption, use both).
+ */
+#ifndef KITTY_H_
+#define KITTY_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define KITTY_OK 0
+#define KITTY_ERR_INVALID_ARG (-1) /* null pointer, bad alignment, inconsistent sizes          */
+#define KITTY_ERR_UNSUPPORTED (-2) /* a size outside the supported set (D, G, R, GQA group)     */
+#define KITTY_ERR_WORKSPACE (-3)   /* workspace smaller than kitty_decode_workspace_bytes()     */
+#define KITTY_ERR_HIP (-4)         /* the HIP runtime rejected a launch                         */
+
+/* Problem statement knobs (Fig. 1 caption: G, R; Sec. 3.2: boost fraction; Sec. 2.1: grouping). */
+typedef struct kitty_layout {
+  int32_t head_dim;        /* D: channels per head; must be 128                                          */
+  int32_t page_size;       /* G: Key quantization group = tokens per page (Sec. 4.1); must be 128        */
+  int32_t v_group;         /* Value quantization group along D (per-token, Sec. 2.1); must equal D       */
+  int32_t n_boost;         /* boosted Key channels per page = boost fraction * D (Sec. 3.2): 0,16,32,64,128 */
+  int32_t residual_window; /* R: full-precision tokens kept before a page forms (Sec. 4.3): 128, or 0    */
+  int32_t n_q_heads;       /* query heads                                                                */
+  int32_t n_kv_heads;      /* KV heads; n_q_heads / n_kv_heads must be 1, 2, 4 or 8                      */
+  int32_t rank_metric;     /* channel ranking: 0 = mean |x| over the page (Eq. 2), 1 = max - min         */
+} kitty_layout;
+
+/* One batch's cache.  All pointers are device pointers.
+ * The record of (physical page id p, kv-head h) starts at page_pool + (p*n_kv_heads + h)*kitty_page_bytes(). */
+typedef struct kitty_cache {
+  void*    page_pool;    /* n_pool_pages * n_kv_heads records, 128-byte aligned                          */
+  int32_t* page_table;   /* [batch][max_pages] physical page ids in token order                          */
+  int32_t* n_pages;      /* [batch] packed pages of each sequence, 0..max_pages                          */
+  void*    resid_k;      /* bf16 [batch][n_kv_heads][R][D] newest tokens not yet in a page; NULL if R=0  */
+  void*    resid_v;      /* same for Values                                                              */
+  int32_t* n_resid;      /* [batch] valid rows of the window, 0..R; NULL if R=0                          */
+  int32_t  batch;
+  int32_t  max_pages;    /* row length of page_table                                                     */
+  int32_t  n_pool_pages;
+} kitty_cache;
+
+/* Size in bytes of one (page, kv-head) record: a multiple of 128.  0 if the layout is unsupported.
+ * Record contents (Sec. 4.1): dense 2-bit plane with the low bits of every Key channel, compact
+ * 2-bit plane with the high bits of the boosted channels, fp16 scale and zero-point per channel,
+ * ascending list of boosted channels, 2-bit Value plane, fp16 scale and zero-point per token. */
+size_t kitty_page_bytes(const kitty_layout* layout /*host*/);
+
+/* Bytes of a record the method has to move (record minus alignment padding).  0 if unsupported. */
+size_t kitty_page_payload_bytes(const kitty_layout* layout /*host*/);
+
+/* Split plan used by the decode calls.  n_splits_req = 0 picks a plan from the sizes and the
+ * GPU's compute-unit count.  On return *n_splits is the number of page ranges per (sequence,
+ * kv-head) and *pages_per_split the length of each range.  Host pointers. */
+int kitty_decode_plan(const kitty_layout* layout, int32_t batch, int32_t max_pages,
+                      int32_t n_splits_req, int32_t* n_splits, int32_t* pages_per_split);
+
+/* Device workspace needed by the decode calls for the plan kitty_decode_plan() returns for the
+ * same arguments.  0 if the arguments are invalid. */
+size_t kitty_decode_workspace_bytes(const kitty_layout* layout, int32_t batch, int32_t max_pages,
+                                    int32_t n_splits_req);
+
+/* Page quantizer (Sec. 4.3 step 3; Sec. 3.2; Sec. 4.1): quantize and pack n_pages pages of
+ * G tokens for every kv-head.
+ *   k_src, v_src   device bf16.  Element (page i, head h, token t, channel c) is at
+ *                  src + off_i + h*head_stride + t*token_stride + c   (all in elements), where
+ *                  off_i = src_page_offsets[i] if that pointer is non-NULL, else i*page_stride.
+ *                  Every row must be 16-byte aligned (strides and offsets multiples of 8).
+ *   src_page_offsets device int64 [n_pages] or NULL.
+ *   dst_page_ids   device int32 [n_pages]: physical page written by source page i; ids outside
+ *                  [0, n_pool_pages) are skipped.
+ *   page_pool      device, as in kitty_cache.
+ * Per page and head: per-channel min/max of K over the G tokens, channel score, the n_boost
+ * best channels (score descending, index ascending) get 4-bit codes and the rest 2-bit codes;
+ * V gets 2-bit codes per token.  scale = fp16((max-min)/qmax), zero = fp16(min),
+ * code = clamp(rint((x-zero)/scale), 0, qmax) in fp32 against the stored fp16 values. */
+int kitty_quantize_pages(const kitty_layout* layout, const void* k_src, const void* v_src,
+                         int64_t page_stride, int64_t head_stride, int64_t token_stride,
+                         const int64_t* src_page_offsets, const int32_t* dst_page_ids,
+                         int32_t n_pages, void* page_pool, int32_t n_pool_pages, void* hip_stream);
+
+/* Insert one new token per sequence (Sec. 4.3 steps 1 and 3, seen from the following step).
+ *   k_new, v_new     device bf16 [batch][n_kv_heads][D].
+ *   fresh_page_ids   device int32 [batch]; entry b is consumed only if sequence b flushes.
+ * For each sequence b: if n_resid[b] == R the window is first quantized into page
+ * fresh_page_ids[b], that id is appended to the page table, and the window restarts empty; then the
+ * new token is stored in the window.  Attention therefore always sees the newest token in full
+ * precision, and a sequence flushes once every G appends.  If a flush is due but the page table
+ * is full or the fresh id is outside the pool, that sequence is left unchanged.
+ * Requires residual_window == page_size. */
+int kitty_append_token(const kitty_layout* layout, const kitty_cache* cache, const void* k_new,
+                       const void* v_new, const int32_t* fresh_page_ids, void* hip_stream);
+
+/* Decode attention for one new query token per sequence (Sec. 4.3 step 2; Eq. 1), read directly
+ * from the packed records and the bf16 window:
+ *   out[b][hq] = softmax(sm_scale * q[b][hq] . K^T) V   over pages in page-table order, then the
+ * window rows 0..n_resid-1, with kv-head = hq / (n_q_heads/n_kv_heads).
+ *   q          device bf16 [batch][n_q_heads][D], 16-byte aligned.
+ *   out        device, same shape; bf16 if out_dtype == 0, fp32 if out_dtype == 1.
+ *   n_splits   0 = automatic; otherwise page ranges per (sequence, kv-head).
+ *   workspace  device scratch of at least kitty_decode_workspace_bytes(..., n_splits) bytes,
+ *              16-byte aligned; contents are overwritten.
+ * A sequence with no tokens yields zeros.  Equivalent to kitty_decode_split + kitty_decode_merge. */
+int kitty_decode_attention(const kitty_layout* layout, const kitty_cache* cache, const void* q,
+                           void* out, float sm_scale, int32_t n_splits, int32_t out_dtype,
+                           void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* First half of kitty_decode_attention: every page range (and the window) of every (sequence,
+ * kv-head) is reduced to a partial (running max, sum of weights, weighted Value sum) in the
+ * workspace.  This is the kernel that streams the cache. */
+int kitty_decode_split(const kitty_layout* layout, const kitty_cache* cache, const void* q,
+                       float sm_scale, int32_t n_splits, void* workspace, size_t workspace_bytes,
+                       void* hip_stream);
+
+/* Second half: log-sum-exp merge of the partials and the store of `out`. */
+int kitty_decode_merge(const kitty_layout* layout, const kitty_cache* cache, void* out,
+                       int32_t n_splits, int32_t out_dtype, const void* workspace,
+                       size_t workspace_bytes, void* hip_stream);
+
+/* Static description of an error code. */
+const char* kitty_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KITTY_H_ */

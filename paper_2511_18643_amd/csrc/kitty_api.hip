@@ -1,0 +1,280 @@
+// Host side of libkitty: argument validation, split planning and kernel launches (gfx950).
+#include "../../include/kitty.h"
+
+#include <type_traits>
+
+#include "kitty_decode.h"
+#include "kitty_quant.h"
+
+namespace {
+
+using namespace kitty;
+
+int check_layout(const kitty_layout* L) {
+  if (!L) return KITTY_ERR_INVALID_ARG;
+  if (L->n_q_heads <= 0 || L->n_kv_heads <= 0 || L->n_q_heads % L->n_kv_heads != 0) return KITTY_ERR_INVALID_ARG;
+  if (L->n_boost < 0 || L->n_boost > L->head_dim || L->n_boost % 16 != 0) return KITTY_ERR_INVALID_ARG;
+  if (L->rank_metric != 0 && L->rank_metric != 1) return KITTY_ERR_INVALID_ARG;
+  if (L->head_dim != D || L->page_size != G || L->v_group != D) return KITTY_ERR_UNSUPPORTED;
+  if (L->residual_window != 0 && L->residual_window != G) return KITTY_ERR_UNSUPPORTED;
+  const int nb16 = L->n_boost / 16;
+  if (nb16 != 0 && nb16 != 1 && nb16 != 2 && nb16 != 4 && nb16 != 8) return KITTY_ERR_UNSUPPORTED;
+  const int g = L->n_q_heads / L->n_kv_heads;
+  if (g != 1 && g != 2 && g != 4 && g != 8) return KITTY_ERR_UNSUPPORTED;
+  return KITTY_OK;
+}
+
+int check_cache(const kitty_layout* L, const kitty_cache* C) {
+  if (!C) return KITTY_ERR_INVALID_ARG;
+  if (C->batch <= 0 || C->max_pages < 0 || C->n_pool_pages < 0) return KITTY_ERR_INVALID_ARG;
+  if (!C->n_pages) return KITTY_ERR_INVALID_ARG;
+  if (C->max_pages > 0 && (!C->page_pool || !C->page_table)) return KITTY_ERR_INVALID_ARG;
+  if (reinterpret_cast<uintptr_t>(C->page_pool) % 128 != 0) return KITTY_ERR_INVALID_ARG;
+  if (L->residual_window > 0) {
+    if (!C->resid_k || !C->resid_v || !C->n_resid) return KITTY_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(C->resid_k) % 16 != 0 || reinterpret_cast<uintptr_t>(C->resid_v) % 16 != 0)
+      return KITTY_ERR_INVALID_ARG;
+  }
+  return KITTY_OK;
+}
+
+int num_compute_units() {
+  static int cus = 0;   // read once; the value never changes for a device
+  if (cus == 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+      cus = n;
+    else
+      cus = 256;
+  }
+  return cus;
+}
+
+void plan_splits(const kitty_layout* L, int32_t batch, int32_t max_pages, int32_t req, int32_t* n_splits, int32_t* pps) {
+  if (max_pages <= 0) { *n_splits = 0; *pps = 1; return; }
+  int32_t per;
+  if (req > 0) {
+    per = (max_pages + req - 1) / req;
+  } else {
+    // aim at several workgroups per compute unit; a wavefront should see at least two pages
+    const int64_t pairs = (int64_t)batch * L->n_kv_heads;
+    const int64_t target = (int64_t)num_compute_units() * 8;
+    int64_t want = (target + pairs - 1) / pairs;          // splits per pair
+    if (want < 1) want = 1;
+    per = (int32_t)((max_pages + want - 1) / want);
+    if (per < 8) per = 8;
+  }
+  if (per < 1) per = 1;
+  if (per > max_pages) per = max_pages;
+  *pps = per;
+  *n_splits = (max_pages + per - 1) / per;
+}
+
+template <typename F>
+int dispatch_nb16(int nb16, F&& f) {
+  switch (nb16) {
+    case 0: return f(std::integral_constant<int, 0>{});
+    case 1: return f(std::integral_constant<int, 1>{});
+    case 2: return f(std::integral_constant<int, 2>{});
+    case 4: return f(std::integral_constant<int, 4>{});
+    case 8: return f(std::integral_constant<int, 8>{});
+  }
+  return KITTY_ERR_UNSUPPORTED;
+}
+
+int launch_status() { return hipGetLastError() == hipSuccess ? KITTY_OK : KITTY_ERR_HIP; }
+
+int fill_decode_params(const kitty_layout* L, const kitty_cache* C, int32_t n_splits_req, const void* ws,
+                       size_t ws_bytes, DecodeParams* P) {
+  int rc = check_layout(L);
+  if (rc) return rc;
+  rc = check_cache(L, C);
+  if (rc) return rc;
+  if (n_splits_req < 0) return KITTY_ERR_INVALID_ARG;
+  if (!ws || reinterpret_cast<uintptr_t>(ws) % 16 != 0) return KITTY_ERR_INVALID_ARG;
+  int32_t ns, pps;
+  plan_splits(L, C->batch, C->max_pages, n_splits_req, &ns, &pps);
+  const size_t need = kitty_decode_workspace_bytes(L, C->batch, C->max_pages, n_splits_req);
+  if (ws_bytes < need) return KITTY_ERR_WORKSPACE;
+  P->pool = static_cast<const uint8_t*>(C->page_pool);
+  P->page_table = C->page_table;
+  P->n_pages = C->n_pages;
+  P->resid_k = static_cast<const uint16_t*>(C->resid_k);
+  P->resid_v = static_cast<const uint16_t*>(C->resid_v);
+  P->n_resid = C->n_resid;
+  P->q = nullptr;
+  P->ws = const_cast<float*>(static_cast<const float*>(ws));
+  P->out = nullptr;
+  P->qk_scale_log2 = 0.f;
+  P->batch = C->batch;
+  P->max_pages = C->max_pages;
+  P->n_q_heads = L->n_q_heads;
+  P->n_kv_heads = L->n_kv_heads;
+  P->gqa = L->n_q_heads / L->n_kv_heads;
+  P->n_splits = ns;
+  P->pages_per_split = pps;
+  P->has_window = L->residual_window > 0 ? 1 : 0;
+  P->out_dtype = 0;
+  return KITTY_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t kitty_page_bytes(const kitty_layout* L) {
+  if (check_layout(L) != KITTY_OK) return 0;
+  return (size_t)record_bytes(L->n_boost / 16);
+}
+
+size_t kitty_page_payload_bytes(const kitty_layout* L) {
+  if (check_layout(L) != KITTY_OK) return 0;
+  return (size_t)record_bytes(L->n_boost / 16) - (size_t)(128 - L->n_boost);
+}
+
+int kitty_decode_plan(const kitty_layout* L, int32_t batch, int32_t max_pages, int32_t n_splits_req,
+                      int32_t* n_splits, int32_t* pages_per_split) {
+  int rc = check_layout(L);
+  if (rc) return rc;
+  if (!n_splits || !pages_per_split || batch <= 0 || max_pages < 0 || n_splits_req < 0) return KITTY_ERR_INVALID_ARG;
+  plan_splits(L, batch, max_pages, n_splits_req, n_splits, pages_per_split);
+  return KITTY_OK;
+}
+
+size_t kitty_decode_workspace_bytes(const kitty_layout* L, int32_t batch, int32_t max_pages, int32_t n_splits_req) {
+  if (check_layout(L) != KITTY_OK || batch <= 0 || max_pages < 0 || n_splits_req < 0) return 0;
+  int32_t ns, pps;
+  plan_splits(L, batch, max_pages, n_splits_req, &ns, &pps);
+  const size_t slots = (size_t)ns + (L->residual_window > 0 ? 1 : 0);
+  const size_t bytes = (size_t)batch * L->n_q_heads * slots * WS_STRIDE * sizeof(float);
+  return bytes ? bytes : 16;
+}
+
+int kitty_quantize_pages(const kitty_layout* L, const void* k_src, const void* v_src, int64_t page_stride,
+                         int64_t head_stride, int64_t token_stride, const int64_t* src_page_offsets,
+                         const int32_t* dst_page_ids, int32_t n_pages, void* page_pool, int32_t n_pool_pages,
+                         void* hip_stream) {
+  int rc = check_layout(L);
+  if (rc) return rc;
+  if (n_pages < 0 || n_pool_pages < 0) return KITTY_ERR_INVALID_ARG;
+  if (n_pages == 0) return KITTY_OK;
+  if (!k_src || !v_src || !dst_page_ids || !page_pool) return KITTY_ERR_INVALID_ARG;
+  if (reinterpret_cast<uintptr_t>(k_src) % 16 || reinterpret_cast<uintptr_t>(v_src) % 16 ||
+      reinterpret_cast<uintptr_t>(page_pool) % 128)
+    return KITTY_ERR_INVALID_ARG;
+  if (token_stride < D || token_stride % 8 || head_stride % 8 || (!src_page_offsets && page_stride % 8))
+    return KITTY_ERR_INVALID_ARG;
+  if (L->n_kv_heads > 65535) return KITTY_ERR_UNSUPPORTED;
+  QuantPagesParams P;
+  P.k_src = static_cast<const uint16_t*>(k_src);
+  P.v_src = static_cast<const uint16_t*>(v_src);
+  P.page_stride = page_stride;
+  P.head_stride = head_stride;
+  P.token_stride = token_stride;
+  P.src_page_offsets = src_page_offsets;
+  P.dst_page_ids = dst_page_ids;
+  P.pool = static_cast<uint8_t*>(page_pool);
+  P.n_kv_heads = L->n_kv_heads;
+  P.n_pool_pages = n_pool_pages;
+  P.rank_metric = L->rank_metric;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  return dispatch_nb16(L->n_boost / 16, [&](auto nb) {
+    constexpr int NB = decltype(nb)::value;
+    hipLaunchKernelGGL(quantize_pages_kernel<NB>, dim3(n_pages, L->n_kv_heads), dim3(256), 0, st, P);
+    return launch_status();
+  });
+}
+
+int kitty_append_token(const kitty_layout* L, const kitty_cache* C, const void* k_new, const void* v_new,
+                       const int32_t* fresh_page_ids, void* hip_stream) {
+  int rc = check_layout(L);
+  if (rc) return rc;
+  rc = check_cache(L, C);
+  if (rc) return rc;
+  if (L->residual_window != G) return KITTY_ERR_UNSUPPORTED;
+  if (!k_new || !v_new || !fresh_page_ids || !C->page_pool || !C->page_table) return KITTY_ERR_INVALID_ARG;
+  if (reinterpret_cast<uintptr_t>(k_new) % 16 || reinterpret_cast<uintptr_t>(v_new) % 16) return KITTY_ERR_INVALID_ARG;
+  if (L->n_kv_heads > 65535 || C->batch > 65535) return KITTY_ERR_UNSUPPORTED;
+  AppendParams P;
+  P.pool = static_cast<uint8_t*>(C->page_pool);
+  P.page_table = C->page_table;
+  P.n_pages = C->n_pages;
+  P.resid_k = static_cast<uint16_t*>(C->resid_k);
+  P.resid_v = static_cast<uint16_t*>(C->resid_v);
+  P.n_resid = C->n_resid;
+  P.k_new = static_cast<const uint16_t*>(k_new);
+  P.v_new = static_cast<const uint16_t*>(v_new);
+  P.fresh_page_ids = fresh_page_ids;
+  P.batch = C->batch;
+  P.max_pages = C->max_pages;
+  P.n_pool_pages = C->n_pool_pages;
+  P.n_kv_heads = L->n_kv_heads;
+  P.rank_metric = L->rank_metric;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  return dispatch_nb16(L->n_boost / 16, [&](auto nb) {
+    constexpr int NB = decltype(nb)::value;
+    hipLaunchKernelGGL(append_token_kernel<NB>, dim3(L->n_kv_heads, C->batch), dim3(256), 0, st, P);
+    if (hipGetLastError() != hipSuccess) return KITTY_ERR_HIP;
+    hipLaunchKernelGGL(append_state_kernel, dim3((C->batch + 255) / 256), dim3(256), 0, st, P);
+    return launch_status();
+  });
+}
+
+int kitty_decode_split(const kitty_layout* L, const kitty_cache* C, const void* q, float sm_scale, int32_t n_splits,
+                       void* workspace, size_t workspace_bytes, void* hip_stream) {
+  DecodeParams P;
+  int rc = fill_decode_params(L, C, n_splits, workspace, workspace_bytes, &P);
+  if (rc) return rc;
+  if (!q || reinterpret_cast<uintptr_t>(q) % 16) return KITTY_ERR_INVALID_ARG;
+  if (L->n_kv_heads > 65535 || C->batch > 65535) return KITTY_ERR_UNSUPPORTED;
+  P.q = static_cast<const uint16_t*>(q);
+  P.qk_scale_log2 = sm_scale * 1.44269504088896340736f;
+  const int n_slots = P.n_splits + P.has_window;
+  if (n_slots == 0) return KITTY_OK;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const dim3 grid(n_slots, L->n_kv_heads, C->batch);
+  const bool wide = P.gqa == 8;
+  return dispatch_nb16(L->n_boost / 16, [&](auto nb) {
+    constexpr int NB = decltype(nb)::value;
+    if (wide) hipLaunchKernelGGL((decode_split_kernel<NB, 2>), grid, dim3(256), 0, st, P);
+    else hipLaunchKernelGGL((decode_split_kernel<NB, 1>), grid, dim3(256), 0, st, P);
+    return launch_status();
+  });
+}
+
+int kitty_decode_merge(const kitty_layout* L, const kitty_cache* C, void* out, int32_t n_splits, int32_t out_dtype,
+                       const void* workspace, size_t workspace_bytes, void* hip_stream) {
+  DecodeParams P;
+  int rc = fill_decode_params(L, C, n_splits, workspace, workspace_bytes, &P);
+  if (rc) return rc;
+  if (!out || (out_dtype != 0 && out_dtype != 1)) return KITTY_ERR_INVALID_ARG;
+  if (L->n_q_heads > 65535 * 8 || C->batch > 65535) return KITTY_ERR_UNSUPPORTED;
+  P.out = out;
+  P.out_dtype = out_dtype;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  hipLaunchKernelGGL(decode_merge_kernel, dim3(L->n_q_heads, C->batch), dim3(128), 0, st, P);
+  return launch_status();
+}
+
+int kitty_decode_attention(const kitty_layout* L, const kitty_cache* C, const void* q, void* out, float sm_scale,
+                           int32_t n_splits, int32_t out_dtype, void* workspace, size_t workspace_bytes,
+                           void* hip_stream) {
+  if (!out || (out_dtype != 0 && out_dtype != 1)) return KITTY_ERR_INVALID_ARG;
+  int rc = kitty_decode_split(L, C, q, sm_scale, n_splits, workspace, workspace_bytes, hip_stream);
+  if (rc) return rc;
+  return kitty_decode_merge(L, C, out, n_splits, out_dtype, workspace, workspace_bytes, hip_stream);
+}
+
+const char* kitty_strerror(int code) {
+  switch (code) {
+    case KITTY_OK: return "ok";
+    case KITTY_ERR_INVALID_ARG: return "invalid argument (null pointer, bad alignment or inconsistent sizes)";
+    case KITTY_ERR_UNSUPPORTED: return "unsupported size (head_dim, page_size, residual window, boost count or GQA group)";
+    case KITTY_ERR_WORKSPACE: return "workspace too small";
+    case KITTY_ERR_HIP: return "HIP launch failed";
+  }
+  return "unknown error";
+}
+
+}  // extern "C"

@@ -1,0 +1,523 @@
+// Split-K decode attention read directly from packed records (Sec. 4.3 step 2; Alg. 1; Eq. 1).
+//
+// One wavefront owns one page at a time and never synchronises with the others inside the loop.
+// Dequantization is folded out of the inner products (Alg. 1: K = X*scale + zero):
+//     q . K_t      = sum_c (q_c s_c) X[t][c] + sum_c q_c z_c
+//     sum_t p_t V_t = sum_t (p_t s_t) X[t][:] + sum_t p_t z_t
+// so the 2-bit codes X go to the int8 matrix cores unchanged (mask/shift into bytes), while the
+// small vectors q*s and p*s are turned into 2 or 3 signed-byte terms (n = t0 + 256 t1 + 65536 t2)
+// occupying separate matrix rows; the integer dot products are exact and are recombined by shifts.
+// The high bits of boosted channels are one more short contraction against the same q*s values
+// gathered through the channel list (the only gather, and it is of q, never of cache bytes).
+#pragma once
+#include <cstddef>
+
+#include "kitty_common.h"
+
+namespace kitty {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+
+constexpr int WS_STRIDE = D + 2;   // floats per partial: acc[128], running max (log2 domain), weight sum
+
+struct DecodeParams {
+  const uint8_t* pool;
+  const int32_t* page_table;
+  const int32_t* n_pages;
+  const uint16_t* resid_k;
+  const uint16_t* resid_v;
+  const int32_t* n_resid;
+  const uint16_t* q;
+  float* ws;
+  void* out;
+  float qk_scale_log2;   // sm_scale * log2(e)
+  int32_t batch, max_pages, n_q_heads, n_kv_heads, gqa;
+  int32_t n_splits, pages_per_split, has_window, out_dtype;
+};
+
+template <int NB16>
+struct PageRegs {
+  uint4 kd[4];
+  uint2 kb[NB16 ? NB16 : 1];
+  uint4 ksc, kzr;
+  uint32_t chv[NB16 ? NB16 : 1];
+  uint4 vd[4];
+  uint4 vsc, vzr;
+};
+
+template <int NB16>
+__device__ __forceinline__ void load_page(PageRegs<NB16>& r, const uint8_t* __restrict__ rec, int l) {
+  using R = Rec<NB16>;
+  const int j = l & 15;
+  const uint4* kd = reinterpret_cast<const uint4*>(rec + R::kd) + l;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) r.kd[i] = kd[64 * i];
+#pragma unroll
+  for (int s = 0; s < NB16; ++s) {
+    r.kb[s] = *reinterpret_cast<const uint2*>(rec + R::kb + 512 * s + 8 * l);
+    r.chv[s] = rec[R::ch + 16 * s + j];
+  }
+  r.ksc = *reinterpret_cast<const uint4*>(rec + R::ks + 16 * j);
+  r.kzr = *reinterpret_cast<const uint4*>(rec + R::kz + 16 * j);
+  const uint4* vd = reinterpret_cast<const uint4*>(rec + R::vd) + l;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) r.vd[i] = vd[64 * i];
+  r.vsc = *reinterpret_cast<const uint4*>(rec + R::vs + 16 * j);
+  r.vzr = *reinterpret_cast<const uint4*>(rec + R::vz + 16 * j);
+}
+
+// sixteen 2-bit elements -> four registers of four int8 each (elements 4v..4v+3 in register v)
+__device__ __forceinline__ v4i unpack16(uint32_t w) {
+  v4i r;
+  r.x = (int)(w & 0x03030303u);
+  r.y = (int)((w >> 2) & 0x03030303u);
+  r.z = (int)((w >> 4) & 0x03030303u);
+  r.w = (int)((w >> 6) & 0x03030303u);
+  return r;
+}
+// same, each element multiplied by 4 (the weight of the high bits of a 4-bit code)
+__device__ __forceinline__ v4i unpack16_x4(uint32_t w) {
+  v4i r;
+  r.x = (int)((w << 2) & 0x0c0c0c0cu);
+  r.y = (int)(w & 0x0c0c0c0cu);
+  r.z = (int)((w >> 2) & 0x0c0c0c0cu);
+  r.w = (int)((w >> 4) & 0x0c0c0c0cu);
+  return r;
+}
+
+// byte K of a, b, c, d -> one word (a in byte 0)
+template <int K>
+__device__ __forceinline__ uint32_t gather_byte(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
+  constexpr uint32_t sel = 0x0c0c0000u | ((4u + K) << 8) | (uint32_t)K;
+  const uint32_t lo = __builtin_amdgcn_perm(b, a, sel);
+  const uint32_t hi = __builtin_amdgcn_perm(d, c, sel);
+  return __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+}
+
+// eight integers -> TR planes of eight signed bytes: n = t0 + 256 t1 (+ 65536 t2), each t in [-128,127]
+template <int TR>
+__device__ __forceinline__ void split_terms(const int (&n)[8], uint2 (&w)[TR]) {
+  uint32_t u[8], t1[8], t2[8];
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    u[k] = (uint32_t)n[k];
+    t1[k] = u[k] + 0x80u;
+    t2[k] = u[k] + 0x8080u;
+  }
+  w[0].x = gather_byte<0>(u[0], u[1], u[2], u[3]);
+  w[0].y = gather_byte<0>(u[4], u[5], u[6], u[7]);
+  w[1].x = gather_byte<1>(t1[0], t1[1], t1[2], t1[3]);
+  w[1].y = gather_byte<1>(t1[4], t1[5], t1[6], t1[7]);
+  if constexpr (TR == 3) {
+    w[2].x = gather_byte<2>(t2[0], t2[1], t2[2], t2[3]);
+    w[2].y = gather_byte<2>(t2[4], t2[5], t2[6], t2[7]);
+  }
+}
+
+// round to nearest for |x| < 2^22: adding 1.5*2^23 leaves the integer in the low mantissa bits
+__device__ __forceinline__ int round_to_int(float x) {
+  return (int)(__float_as_uint(x + 12582912.0f) - 0x4b400000u);
+}
+
+__device__ __forceinline__ void f16x8_to_f32(const uint4& v, float (&f)[8]) {
+  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    f[2 * k] = f16_bits_to_f32((uint16_t)(w[k] & 0xffffu));
+    f[2 * k + 1] = f16_bits_to_f32((uint16_t)(w[k] >> 16));
+  }
+}
+
+__device__ __forceinline__ void wave_lds_fence() {
+  // LDS traffic of one wavefront is processed in order; this only stops the compiler from moving
+  // a lane's read above another lane's write.
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Per-wave LDS scratch.  Rows of the int8 operand matrices are 144 bytes apart so that the
+// 16-byte reads of the sixteen rows fall into different banks.
+template <int NB16, int HPL>
+struct WaveScratch {
+  int32_t nbuf[4 * HPL][D];                      // integer q*s per (head, channel), for the boost gather
+  uint8_t abuf[16][144];                         // rows (head, term) x channel
+  uint8_t bbuf[16][16 * (NB16 ? NB16 : 1) + 16];  // rows (head, term) x boost slot
+  uint8_t pbuf[16][144];                         // rows (head, term) x position
+  float pw[32][8];                               // window path: softmax weights [token][head]
+  uint8_t zero[16];
+};
+
+template <int HPL>
+struct MergeScratch {
+  float acc[4][4 * HPL][D];
+  float m[4][4 * HPL];
+  float l[4][4 * HPL];
+};
+
+template <int NB16, int HPL>
+union __attribute__((aligned(16))) DecodeSmem {
+  WaveScratch<NB16, HPL> w[4];
+  MergeScratch<HPL> mg;
+};
+
+// HPL = query heads per lane: 1 for GQA groups of 1, 2, 4 (three byte terms), 2 for groups of 8
+// (two byte terms).  Grid: x = split slot (n_splits page ranges, then the window), y = kv-head,
+// z = sequence.  Block = 4 wavefronts.
+template <int NB16, int HPL>
+__global__ __launch_bounds__(256, 2) void decode_split_kernel(DecodeParams p) {
+  using R = Rec<NB16>;
+  constexpr int TR = HPL == 1 ? 3 : 2;     // byte terms
+  constexpr int RPH = 4 / HPL;             // matrix rows per head
+  constexpr int NH = 4 * HPL;              // heads handled by the block
+  constexpr float NLIM = TR == 3 ? 1048000.0f : 32000.0f;   // bound of the integer images
+
+  __shared__ DecodeSmem<NB16, HPL> smem;
+
+  const int slot = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int tid = threadIdx.x;
+  const int w = tid >> 6, l = tid & 63, j = l & 15, gi = l >> 4;
+  const int g = p.gqa;
+  const int n_slots = p.n_splits + p.has_window;
+
+  const bool is_window = slot >= p.n_splits;
+  int p0 = 0, p1 = 0, r = 0;
+  if (!is_window) {
+    const int np = min(p.n_pages[b], p.max_pages);
+    p0 = slot * p.pages_per_split;
+    p1 = min(p0 + p.pages_per_split, np);
+    if (p0 >= p1) return;
+  } else {
+    r = min(p.n_resid[b], G);
+    if (r <= 0) return;
+  }
+
+  // running state of this wavefront, per head handled by the lane (head = gi*HPL + e)
+  float m_run[HPL], l_run[HPL], z_run[HPL];
+  float acc[HPL][8];        // page path: channel 16*Td + j ; window path: see below
+#pragma unroll
+  for (int e = 0; e < HPL; ++e) {
+    m_run[e] = -INFINITY; l_run[e] = 0.f; z_run[e] = 0.f;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) acc[e][k] = 0.f;
+  }
+  float accw[NH][2];        // window path: channels 2l, 2l+1 of every head
+#pragma unroll
+  for (int hh = 0; hh < NH; ++hh) accw[hh][0] = accw[hh][1] = 0.f;
+
+  WaveScratch<NB16, HPL>& ws = smem.w[w];
+  const size_t qrow = ((size_t)b * p.n_q_heads + (size_t)h * g);
+
+  if (!is_window) {
+    // ---- zero the operand matrices once (rows of absent heads and the unused term row stay zero)
+    {
+      uint32_t* z32 = reinterpret_cast<uint32_t*>(&ws.abuf[0][0]);
+      using WSc = WaveScratch<NB16, HPL>;
+      constexpr int nwords = (int)(offsetof(WSc, pw) - offsetof(WSc, abuf)) / 4;   // abuf, bbuf, pbuf are contiguous
+      for (int i = l; i < nwords; i += 64) z32[i] = 0u;
+      if (l < 4) reinterpret_cast<uint32_t*>(ws.zero)[l] = 0u;
+    }
+    // ---- q in "compact" layout: lane (gi, j) holds channels 8j..8j+7 of heads gi*HPL + e, pre-scaled
+    float qv[HPL][8];
+#pragma unroll
+    for (int e = 0; e < HPL; ++e) {
+      const int hd = gi * HPL + e;
+      if (hd < g) {
+        const uint4 raw = *reinterpret_cast<const uint4*>(p.q + (qrow + hd) * D + 8 * j);
+        const uint32_t rw[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          qv[e][2 * k] = __uint_as_float(rw[k] << 16) * p.qk_scale_log2;
+          qv[e][2 * k + 1] = __uint_as_float(rw[k] & 0xffff0000u) * p.qk_scale_log2;
+        }
+      } else {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) qv[e][k] = 0.f;
+      }
+    }
+    // LDS addresses of the A operands: lane (row i = j, k-block gi)
+    const uint8_t* a_ptr = &ws.abuf[j][16 * gi];
+    const uint8_t* p_ptr = &ws.pbuf[j][16 * gi];
+    wave_lds_fence();
+
+    const int32_t* pt = p.page_table + (size_t)b * p.max_pages;
+    const size_t rec_stride = (size_t)p.n_kv_heads * R::bytes;
+    const uint8_t* pool_h = p.pool + (size_t)h * R::bytes;
+
+    PageRegs<NB16> cur{}, nxt{};
+    int idx = p0 + w;
+    if (idx < p1) load_page<NB16>(cur, pool_h + (size_t)pt[idx] * rec_stride, l);
+
+    for (; idx < p1; idx += 4) {
+      if (idx + 4 < p1) load_page<NB16>(nxt, pool_h + (size_t)pt[idx + 4] * rec_stride, l);
+
+      // ================= A: integer image of q*s, bias q.z =================
+      float ks[8], kz[8];
+      f16x8_to_f32(cur.ksc, ks);
+      f16x8_to_f32(cur.kzr, kz);
+      float inv_alpha[HPL], bias[HPL];
+#pragma unroll
+      for (int e = 0; e < HPL; ++e) {
+        float qs[8], amax = 0.f, bsum = 0.f;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          qs[k] = qv[e][k] * ks[k];
+          amax = fmaxf(amax, fabsf(qs[k]));
+          bsum = fmaf(qv[e][k], kz[k], bsum);
+        }
+        amax = fmaxf(row_max(amax), 1e-30f);
+        bias[e] = row_sum(bsum);
+        const float alpha = NLIM / amax;
+        inv_alpha[e] = amax * (1.0f / NLIM);
+        int n[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) n[k] = round_to_int(qs[k] * alpha);
+        uint2 tw[TR];
+        split_terms<TR>(n, tw);
+        const int hd = gi * HPL + e;
+#pragma unroll
+        for (int t = 0; t < TR; ++t) *reinterpret_cast<uint2*>(&ws.abuf[hd * RPH + t][8 * j]) = tw[t];
+        if constexpr (NB16 > 0) {
+          *reinterpret_cast<int4*>(&ws.nbuf[hd][8 * j]) = make_int4(n[0], n[1], n[2], n[3]);
+          *reinterpret_cast<int4*>(&ws.nbuf[hd][8 * j + 4]) = make_int4(n[4], n[5], n[6], n[7]);
+        }
+      }
+      wave_lds_fence();
+      // ================= B: same integers gathered through the boosted-channel list =================
+      if constexpr (NB16 > 0) {
+#pragma unroll
+        for (int s = 0; s < NB16; ++s) {
+#pragma unroll
+          for (int e = 0; e < HPL; ++e) {
+            const int hd = gi * HPL + e;
+            const uint32_t nn = (uint32_t)ws.nbuf[hd][cur.chv[s]];
+            ws.bbuf[hd * RPH + 0][16 * s + j] = (uint8_t)nn;
+            ws.bbuf[hd * RPH + 1][16 * s + j] = (uint8_t)((nn + 0x80u) >> 8);
+            if constexpr (TR == 3) ws.bbuf[hd * RPH + 2][16 * s + j] = (uint8_t)((nn + 0x8080u) >> 16);
+          }
+        }
+        wave_lds_fence();
+      }
+      // ================= C: logits for 128 tokens x heads on the int8 matrix cores =================
+      const v4i a0 = *reinterpret_cast<const v4i*>(a_ptr);
+      const v4i a1 = *reinterpret_cast<const v4i*>(a_ptr + 64);
+      v4i dq[8];
+#pragma unroll
+      for (int T = 0; T < 8; ++T) {
+        const uint4 ld = cur.kd[T >> 1];
+        const uint32_t w0 = (T & 1) ? ld.z : ld.x, w1 = (T & 1) ? ld.w : ld.y;
+        v4i c = {0, 0, 0, 0};
+        c = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0, unpack16(w0), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1, unpack16(w1), c, 0, 0, 0);
+        dq[T] = c;
+      }
+      if constexpr (NB16 > 0) {
+#pragma unroll
+        for (int s = 0; s < NB16; ++s) {
+          // tile 4u+kb of the boost plane lives in the lanes of k-block kb: feed A only to that block
+          v4i ab[4];
+#pragma unroll
+          for (int kb = 0; kb < 4; ++kb) {
+            const uint8_t* src = (gi == kb) ? &ws.bbuf[j][16 * s] : ws.zero;
+            ab[kb] = *reinterpret_cast<const v4i*>(src);
+          }
+#pragma unroll
+          for (int u = 0; u < 2; ++u) {
+            const v4i bb = unpack16_x4(u ? cur.kb[s].y : cur.kb[s].x);
+#pragma unroll
+            for (int kb = 0; kb < 4; ++kb)
+              dq[4 * u + kb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ab[kb], bb, dq[4 * u + kb], 0, 0, 0);
+          }
+        }
+      }
+      // ================= D: online softmax; lane (j, gi) owns token 16T + j of heads gi*HPL + e ==========
+      float vs[8], vz[8];
+      f16x8_to_f32(cur.vsc, vs);
+      f16x8_to_f32(cur.vzr, vz);
+      float corr[HPL], inv_beta[HPL];
+#pragma unroll
+      for (int e = 0; e < HPL; ++e) {
+        float x[8], mx = -INFINITY;
+#pragma unroll
+        for (int T = 0; T < 8; ++T) {
+          int nl;
+          if constexpr (TR == 3) nl = dq[T][0] + dq[T][1] * 256 + dq[T][2] * 65536;
+          else nl = dq[T][2 * e] + dq[T][2 * e + 1] * 256;
+          x[T] = fmaf((float)nl, inv_alpha[e], bias[e]);
+          mx = fmaxf(mx, x[T]);
+        }
+        mx = row_max(mx);
+        const float m_new = fmaxf(m_run[e], mx);
+        corr[e] = __builtin_amdgcn_exp2f(m_run[e] - m_new);
+        m_run[e] = m_new;
+        float ps[8], psum = 0.f, zsum = 0.f, pmax = 0.f;
+#pragma unroll
+        for (int T = 0; T < 8; ++T) {
+          const float pT = __builtin_amdgcn_exp2f(x[T] - m_new);
+          psum += pT;
+          zsum = fmaf(pT, vz[T], zsum);
+          ps[T] = pT * vs[T];
+          pmax = fmaxf(pmax, ps[T]);
+        }
+        l_run[e] = fmaf(l_run[e], corr[e], psum);
+        z_run[e] = fmaf(z_run[e], corr[e], zsum);
+        pmax = fmaxf(row_max(pmax), 1e-30f);
+        const float beta = NLIM / pmax;
+        inv_beta[e] = pmax * (1.0f / NLIM);
+        int n[8];
+#pragma unroll
+        for (int T = 0; T < 8; ++T) n[T] = (int)fmaf(ps[T], beta, 0.5f);   // ps >= 0: round half up
+        uint2 tw[TR];
+        split_terms<TR>(n, tw);
+        const int hd = gi * HPL + e;
+#pragma unroll
+        for (int t = 0; t < TR; ++t) *reinterpret_cast<uint2*>(&ws.pbuf[hd * RPH + t][8 * j]) = tw[t];
+      }
+      wave_lds_fence();
+      // ================= E: weighted Value sum on the int8 matrix cores =================
+      const v4i pa0 = *reinterpret_cast<const v4i*>(p_ptr);
+      const v4i pa1 = *reinterpret_cast<const v4i*>(p_ptr + 64);
+#pragma unroll
+      for (int Td = 0; Td < 8; ++Td) {
+        const uint4 ld = cur.vd[Td >> 1];
+        const uint32_t w0 = (Td & 1) ? ld.z : ld.x, w1 = (Td & 1) ? ld.w : ld.y;
+        v4i c = {0, 0, 0, 0};
+        c = __builtin_amdgcn_mfma_i32_16x16x64_i8(pa0, unpack16(w0), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_i32_16x16x64_i8(pa1, unpack16(w1), c, 0, 0, 0);
+#pragma unroll
+        for (int e = 0; e < HPL; ++e) {
+          int ne;
+          if constexpr (TR == 3) ne = c[0] + c[1] * 256 + c[2] * 65536;
+          else ne = c[2 * e] + c[2 * e + 1] * 256;
+          acc[e][Td] = fmaf(acc[e][Td], corr[e], (float)ne * inv_beta[e]);
+        }
+      }
+      wave_lds_fence();   // the next page overwrites abuf/pbuf
+      cur = nxt;
+    }
+  } else {
+    // ================= residual window: bf16 rows, 32 tokens per wavefront =================
+    const int t0 = 32 * w;
+    if (t0 < r) {
+      const uint16_t* wk = p.resid_k + ((size_t)b * p.n_kv_heads + h) * (size_t)(G * D);
+      const uint16_t* wv = p.resid_v + ((size_t)b * p.n_kv_heads + h) * (size_t)(G * D);
+      // A operand: query rows; row hd*RPH carries head hd, the other rows are zero
+      const int arow_head = j / RPH;
+      const bool arow_live = (j % RPH) == 0 && arow_head < g;
+      v8bf aq[4];
+#pragma unroll
+      for (int mm = 0; mm < 4; ++mm) {
+        uint4 raw = make_uint4(0, 0, 0, 0);
+        if (arow_live) raw = *reinterpret_cast<const uint4*>(p.q + (qrow + arow_head) * D + 32 * mm + 8 * gi);
+        aq[mm] = __builtin_bit_cast(v8bf, raw);
+      }
+      float x[HPL][2];
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt) {
+        const int t = t0 + 16 * tt + j;
+        v4f c = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int mm = 0; mm < 4; ++mm) {
+          const uint4 raw = *reinterpret_cast<const uint4*>(wk + (size_t)t * D + 32 * mm + 8 * gi);
+          c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aq[mm], __builtin_bit_cast(v8bf, raw), c, 0, 0, 0);
+        }
+#pragma unroll
+        for (int e = 0; e < HPL; ++e) x[e][tt] = t < r ? c[e * RPH] * p.qk_scale_log2 : -INFINITY;
+      }
+#pragma unroll
+      for (int e = 0; e < HPL; ++e) {
+        const float mx = row_max(fmaxf(x[e][0], x[e][1]));
+        m_run[e] = mx;
+        const float pa = __builtin_amdgcn_exp2f(x[e][0] - mx), pb = __builtin_amdgcn_exp2f(x[e][1] - mx);
+        l_run[e] = pa + pb;
+        ws.pw[j][gi * HPL + e] = pa;
+        ws.pw[16 + j][gi * HPL + e] = pb;
+      }
+      wave_lds_fence();
+      const int nt = min(32, r - t0);
+      for (int t = 0; t < nt; ++t) {
+        const uint32_t two = *reinterpret_cast<const uint32_t*>(wv + (size_t)(t0 + t) * D + 2 * l);
+        const float v0 = __uint_as_float(two << 16), v1 = __uint_as_float(two & 0xffff0000u);
+#pragma unroll
+        for (int hh = 0; hh < NH; ++hh) {
+          const float ph = ws.pw[t][hh];
+          accw[hh][0] = fmaf(ph, v0, accw[hh][0]);
+          accw[hh][1] = fmaf(ph, v1, accw[hh][1]);
+        }
+      }
+    }
+  }
+
+  // ================= merge the four wavefronts, write the partial =================
+  float lsum[HPL], zsum[HPL];
+#pragma unroll
+  for (int e = 0; e < HPL; ++e) { lsum[e] = row_sum(l_run[e]); zsum[e] = row_sum(z_run[e]); }
+  __syncthreads();   // every wavefront is done with its scratch
+  MergeScratch<HPL>& mg = smem.mg;
+  if (!is_window) {
+#pragma unroll
+    for (int e = 0; e < HPL; ++e) {
+      const int hd = gi * HPL + e;
+#pragma unroll
+      for (int Td = 0; Td < 8; ++Td) mg.acc[w][hd][16 * Td + j] = acc[e][Td] + zsum[e];
+      if (j == 0) { mg.m[w][hd] = m_run[e]; mg.l[w][hd] = lsum[e]; }
+    }
+  } else {
+#pragma unroll
+    for (int hh = 0; hh < NH; ++hh) {
+      mg.acc[w][hh][2 * l] = accw[hh][0];
+      mg.acc[w][hh][2 * l + 1] = accw[hh][1];
+    }
+#pragma unroll
+    for (int e = 0; e < HPL; ++e)
+      if (j == 0) { mg.m[w][gi * HPL + e] = m_run[e]; mg.l[w][gi * HPL + e] = lsum[e]; }
+  }
+  __syncthreads();
+  float* out = p.ws + (((size_t)b * p.n_kv_heads + h) * n_slots + slot) * (size_t)g * WS_STRIDE;
+  for (int o = tid; o < g * D; o += 256) {
+    const int hd = o >> 7, d = o & 127;
+    float M = fmaxf(fmaxf(mg.m[0][hd], mg.m[1][hd]), fmaxf(mg.m[2][hd], mg.m[3][hd]));
+    float a = 0.f, L = 0.f;
+#pragma unroll
+    for (int ww = 0; ww < 4; ++ww) {
+      const float f = __builtin_amdgcn_exp2f(mg.m[ww][hd] - M);   // exp2(-inf) = 0 for idle wavefronts
+      a = fmaf(mg.acc[ww][hd][d], f, a);
+      L = fmaf(mg.l[ww][hd], f, L);
+    }
+    out[hd * WS_STRIDE + d] = a;
+    if (d == 0) { out[hd * WS_STRIDE + D] = M; out[hd * WS_STRIDE + D + 1] = L; }
+  }
+}
+
+// Log-sum-exp merge of the partials of one (sequence, query head); grid (n_q_heads, batch), 128 threads.
+__global__ __launch_bounds__(128) void decode_merge_kernel(DecodeParams p) {
+  const int hq = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
+  const int g = p.gqa, h = hq / g, hd = hq % g;
+  const int n_slots = p.n_splits + p.has_window;
+  const int np = min(p.n_pages[b], p.max_pages);
+  const int r = p.has_window ? p.n_resid[b] : 0;
+  const float* base = p.ws + (((size_t)b * p.n_kv_heads + h) * n_slots) * (size_t)g * WS_STRIDE + (size_t)hd * WS_STRIDE;
+  const size_t slot_stride = (size_t)g * WS_STRIDE;
+  float M = -INFINITY;
+  for (int s = 0; s < n_slots; ++s) {
+    const bool valid = s < p.n_splits ? (s * p.pages_per_split < np) : (r > 0);
+    if (valid) M = fmaxf(M, base[s * slot_stride + D]);
+  }
+  float a = 0.f, L = 0.f;
+  for (int s = 0; s < n_slots; ++s) {
+    const bool valid = s < p.n_splits ? (s * p.pages_per_split < np) : (r > 0);
+    if (valid) {
+      const float f = __builtin_amdgcn_exp2f(base[s * slot_stride + D] - M);
+      a = fmaf(base[s * slot_stride + d], f, a);
+      L = fmaf(base[s * slot_stride + D + 1], f, L);
+    }
+  }
+  const float o = L > 0.f ? a / L : 0.f;
+  const size_t oi = ((size_t)b * p.n_q_heads + hq) * D + d;
+  if (p.out_dtype == 0) reinterpret_cast<uint16_t*>(p.out)[oi] = f32_to_bf16_rne(o);
+  else reinterpret_cast<float*>(p.out)[oi] = o;
+}
+
+}  // namespace kitty

@@ -1,0 +1,263 @@
+// Page quantizer: one workgroup of 256 threads turns G=128 tokens of one kv-head into a record.
+// Sec. 2.1 (per-channel K / per-token V asymmetric quantization), Sec. 3.2 Eq. (2) (channel
+// score and top-K boost), Sec. 4.1 (dense low-bit plane + compact high-bit plane + index list).
+#pragma once
+#include "kitty_common.h"
+
+namespace kitty {
+
+struct QuantSmem {
+  uint32_t tile[G * 65];   // 128 rows of 128 bf16, row stride 65 dwords (bank-conflict-free rows and columns)
+  double sum[2][D];
+  double score[D];
+  float mn[2][D];
+  float mx[2][D];
+  float sc[D];             // scale as float(fp16), per channel (K phase) or per token (V phase)
+  float zr[D];
+  float qm[D];
+  unsigned long long ballot0;
+  uint8_t chl[D];
+};
+
+__device__ __forceinline__ float tile_elem(const QuantSmem& s, int t, int c) {
+  return bf16_to_f32(reinterpret_cast<const uint16_t*>(s.tile)[t * 130 + c]);
+}
+
+// code = clamp(rint((x - zero)/scale), 0, qmax) with IEEE fp32 subtract and divide; 0 if scale == 0.
+__device__ __forceinline__ uint32_t qcode(float x, float s, float z, float qmax) {
+  float r = rintf(__fdiv_rn(__fsub_rn(x, z), s));
+  r = fminf(fmaxf(r, 0.0f), qmax);
+  return s > 0.0f ? (uint32_t)r : 0u;
+}
+
+__device__ __forceinline__ int elem_shift(int a) { return 8 * (a & 3) + 2 * (a >> 2); }
+
+// src: bf16 rows of 128 channels, row t at src + t*token_stride (elements), 16-byte aligned.
+__device__ __forceinline__ void load_tile(QuantSmem& s, const uint16_t* __restrict__ src, int64_t token_stride, int tid) {
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    int chunk = tid + 256 * i;
+    int t = chunk >> 4, part = chunk & 15;
+    uint4 v = *reinterpret_cast<const uint4*>(src + (int64_t)t * token_stride + part * 8);
+    uint32_t* d = &s.tile[t * 65 + part * 4];
+    d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
+  }
+}
+
+template <int NB16>
+__device__ void quantize_page(QuantSmem& s, const uint16_t* __restrict__ ksrc, const uint16_t* __restrict__ vsrc,
+                              int64_t token_stride, uint8_t* __restrict__ rec, int rank_metric) {
+  using R = Rec<NB16>;
+  const int tid = threadIdx.x;
+  const int c = tid & 127, half = tid >> 7;
+
+  // ---------------- Key page ----------------
+  load_tile(s, ksrc, token_stride, tid);
+  __syncthreads();
+  {  // per-channel min, max, sum |x| over half of the tokens
+    float mn = INFINITY, mx = -INFINITY;
+    double sum = 0.0;
+    for (int t = half * 64; t < half * 64 + 64; ++t) {
+      float x = tile_elem(s, t, c);
+      mn = fminf(mn, x);
+      mx = fmaxf(mx, x);
+      sum += (double)fabsf(x);   // exact for bf16 inputs: the order of the additions does not matter
+    }
+    s.mn[half][c] = mn; s.mx[half][c] = mx; s.sum[half][c] = sum;
+  }
+  __syncthreads();
+  float mn = 0.f, mx = 0.f;
+  if (tid < 128) {
+    mn = fminf(s.mn[0][c], s.mn[1][c]);
+    mx = fmaxf(s.mx[0][c], s.mx[1][c]);
+    s.score[c] = rank_metric == 0 ? s.sum[0][c] + s.sum[1][c] : (double)__fsub_rn(mx, mn);
+  }
+  __syncthreads();
+  bool boosted = false;
+  if (tid < 128) {  // rank under (score descending, channel ascending)
+    const double my = s.score[c];
+    int rank = 0;
+    for (int o = 0; o < 128; ++o) {
+      double so = s.score[o];
+      rank += (so > my) || (so == my && o < c);
+    }
+    boosted = rank < 16 * NB16;
+  }
+  unsigned long long bal = __ballot(boosted);
+  if (tid == 0) s.ballot0 = bal;
+  __syncthreads();
+  if (tid < 128) {
+    const int lane = tid & 63;
+    int slot = __popcll(bal & ((1ull << lane) - 1ull)) + (tid >= 64 ? __popcll(s.ballot0) : 0);
+    const float qmax = boosted ? 15.0f : 3.0f;
+    const uint16_t sh = f32_to_f16_bits(__fdiv_rn(__fsub_rn(mx, mn), qmax));
+    const uint16_t zh = f32_to_f16_bits(mn);
+    s.sc[c] = f16_bits_to_f32(sh);
+    s.zr[c] = f16_bits_to_f32(zh);
+    s.qm[c] = qmax;
+    reinterpret_cast<uint16_t*>(rec + R::ks)[c] = sh;
+    reinterpret_cast<uint16_t*>(rec + R::kz)[c] = zh;
+    if (boosted) { s.chl[slot] = (uint8_t)c; rec[R::ch + slot] = (uint8_t)c; }
+    if (c >= 16 * NB16) rec[R::ch + c] = 0;   // pad bytes of the channel list
+  }
+  __syncthreads();
+  {  // dense plane: thread (q, lane) builds the 16 bytes that lane reads back in the decode kernel
+    const int q = tid >> 6, lane = tid & 63;
+    uint32_t w[4];
+#pragma unroll
+    for (int wi = 0; wi < 4; ++wi) {
+      const int t = 32 * q + 16 * (wi >> 1) + (lane & 15);
+      const int cb = 4 * (wi & 1) + (lane >> 4);
+      uint32_t word = 0;
+#pragma unroll
+      for (int a = 0; a < 16; ++a) {
+        const int ch = 16 * cb + a;
+        word |= (qcode(tile_elem(s, t, ch), s.sc[ch], s.zr[ch], s.qm[ch]) & 3u) << elem_shift(a);
+      }
+      w[wi] = word;
+    }
+    reinterpret_cast<uint4*>(rec + R::kd)[64 * q + lane] = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+  if constexpr (NB16 > 0) {  // boost plane: high two bits of the boosted channels, slot order
+    for (int idx = tid; idx < 128 * NB16; idx += 256) {
+      const int sblk = idx >> 7, u = (idx >> 6) & 1, lane = idx & 63;
+      const int t = 16 * (4 * u + (lane >> 4)) + (lane & 15);
+      uint32_t word = 0;
+#pragma unroll
+      for (int a = 0; a < 16; ++a) {
+        const int ch = s.chl[16 * sblk + a];
+        word |= (qcode(tile_elem(s, t, ch), s.sc[ch], s.zr[ch], 15.0f) >> 2) << elem_shift(a);
+      }
+      *reinterpret_cast<uint32_t*>(rec + R::kb + 512 * sblk + 8 * lane + 4 * u) = word;
+    }
+  }
+  __syncthreads();
+
+  // ---------------- Value page ----------------
+  load_tile(s, vsrc, token_stride, tid);
+  __syncthreads();
+  {  // per-token min, max over half of the channels
+    const int t = c;
+    float mn2 = INFINITY, mx2 = -INFINITY;
+    for (int k = 0; k < 32; ++k) {
+      uint32_t two = s.tile[t * 65 + half * 32 + k];
+      float a = __uint_as_float(two << 16), b = __uint_as_float(two & 0xffff0000u);
+      mn2 = fminf(mn2, fminf(a, b));
+      mx2 = fmaxf(mx2, fmaxf(a, b));
+    }
+    s.mn[half][t] = mn2; s.mx[half][t] = mx2;
+  }
+  __syncthreads();
+  if (tid < 128) {
+    const int t = c;
+    const float mnv = fminf(s.mn[0][t], s.mn[1][t]);
+    const float mxv = fmaxf(s.mx[0][t], s.mx[1][t]);
+    const uint16_t sh = f32_to_f16_bits(__fdiv_rn(__fsub_rn(mxv, mnv), 3.0f));
+    const uint16_t zh = f32_to_f16_bits(mnv);
+    s.sc[t] = f16_bits_to_f32(sh);
+    s.zr[t] = f16_bits_to_f32(zh);
+    const int p = 8 * (t & 15) + (t >> 4);
+    reinterpret_cast<uint16_t*>(rec + R::vs)[p] = sh;
+    reinterpret_cast<uint16_t*>(rec + R::vz)[p] = zh;
+  }
+  __syncthreads();
+  {
+    const int q = tid >> 6, lane = tid & 63;
+    uint32_t w[4];
+#pragma unroll
+    for (int wi = 0; wi < 4; ++wi) {
+      const int d = 32 * q + 16 * (wi >> 1) + (lane & 15);
+      const int wv = 4 * (wi & 1) + (lane >> 4);
+      uint32_t word = 0;
+#pragma unroll
+      for (int a = 0; a < 16; ++a) {
+        const int p = 16 * wv + a;
+        const int t = 16 * (p & 7) + (p >> 3);
+        word |= qcode(tile_elem(s, t, d), s.sc[t], s.zr[t], 3.0f) << elem_shift(a);
+      }
+      w[wi] = word;
+    }
+    reinterpret_cast<uint4*>(rec + R::vd)[64 * q + lane] = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+  __syncthreads();   // the tile and the window rows may be overwritten by the caller after this
+}
+
+struct QuantPagesParams {
+  const uint16_t* k_src;
+  const uint16_t* v_src;
+  int64_t page_stride, head_stride, token_stride;
+  const int64_t* src_page_offsets;
+  const int32_t* dst_page_ids;
+  uint8_t* pool;
+  int32_t n_kv_heads, n_pool_pages, rank_metric;
+};
+
+template <int NB16>
+__global__ __launch_bounds__(256) void quantize_pages_kernel(QuantPagesParams p) {
+  __shared__ QuantSmem smem;
+  const int i = blockIdx.x, h = blockIdx.y;
+  const int32_t pid = p.dst_page_ids[i];
+  if (pid < 0 || pid >= p.n_pool_pages) return;
+  const int64_t off = (p.src_page_offsets ? p.src_page_offsets[i] : (int64_t)i * p.page_stride) + (int64_t)h * p.head_stride;
+  uint8_t* rec = p.pool + ((size_t)pid * p.n_kv_heads + h) * (size_t)Rec<NB16>::bytes;
+  quantize_page<NB16>(smem, p.k_src + off, p.v_src + off, p.token_stride, rec, p.rank_metric);
+}
+
+struct AppendParams {
+  uint8_t* pool;
+  int32_t* page_table;
+  int32_t* n_pages;
+  uint16_t* resid_k;
+  uint16_t* resid_v;
+  int32_t* n_resid;
+  const uint16_t* k_new;
+  const uint16_t* v_new;
+  const int32_t* fresh_page_ids;
+  int32_t batch, max_pages, n_pool_pages, n_kv_heads, rank_metric;
+};
+
+// Grid (n_kv_heads, batch).  Reads the sequence state, flushes a full window into a page, stores the
+// new token.  The state itself is advanced by append_state_kernel after every head has read it.
+template <int NB16>
+__global__ __launch_bounds__(256) void append_token_kernel(AppendParams p) {
+  __shared__ QuantSmem smem;
+  const int h = blockIdx.x, b = blockIdx.y;
+  const int nr = p.n_resid[b];
+  uint16_t* wk = p.resid_k + ((size_t)b * p.n_kv_heads + h) * (size_t)(G * D);
+  uint16_t* wv = p.resid_v + ((size_t)b * p.n_kv_heads + h) * (size_t)(G * D);
+  if (nr < 0) return;
+  int slot = nr;
+  if (nr >= G) {
+    const int32_t pid = p.fresh_page_ids[b];
+    if (p.n_pages[b] >= p.max_pages || pid < 0 || pid >= p.n_pool_pages) return;   // cannot flush: leave unchanged
+    uint8_t* rec = p.pool + ((size_t)pid * p.n_kv_heads + h) * (size_t)Rec<NB16>::bytes;
+    quantize_page<NB16>(smem, wk, wv, D, rec, p.rank_metric);
+    slot = 0;
+  }
+  const int tid = threadIdx.x;
+  if (tid < 32) {
+    const int part = tid & 15;
+    const uint16_t* src = (tid < 16 ? p.k_new : p.v_new) + ((size_t)b * p.n_kv_heads + h) * D + part * 8;
+    uint16_t* dst = (tid < 16 ? wk : wv) + (size_t)slot * D + part * 8;
+    *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
+  }
+}
+
+__global__ void append_state_kernel(AppendParams p) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= p.batch) return;
+  const int nr = p.n_resid[b];
+  if (nr < 0) return;
+  if (nr >= G) {
+    const int32_t pid = p.fresh_page_ids[b];
+    const int np = p.n_pages[b];
+    if (np >= p.max_pages || pid < 0 || pid >= p.n_pool_pages) return;
+    p.page_table[(size_t)b * p.max_pages + np] = pid;
+    p.n_pages[b] = np + 1;
+    p.n_resid[b] = 1;
+  } else {
+    p.n_resid[b] = nr + 1;
+  }
+}
+
+}  // namespace kitty

@@ -1,0 +1,87 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every declared
+symbol, sizes follow the closed forms, and invalid arguments are rejected before any launch."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2511_18643_amd import kitty
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "kitty.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(kitty_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = kitty.lib()
+    names = declared_symbols()
+    assert set(names) == set(kitty.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_record_sizes():
+    for nb, want in ((0, 9344), (16, 9856), (32, 10368), (64, 11392), (128, 13440)):
+        lay = kitty.make_layout(32, 8, nb)
+        assert kitty.kitty_page_bytes(lay) == want
+        assert kitty.kitty_page_payload_bytes(lay) == want - (128 - nb)
+        assert want % 128 == 0
+    assert kitty.kitty_page_payload_bytes(kitty.make_layout(32, 8, 16)) == 9744
+    assert kitty.kitty_page_payload_bytes(kitty.make_layout(32, 8, 32)) == 10272
+
+
+def test_unsupported_layouts_are_rejected():
+    assert kitty.kitty_page_bytes(kitty.make_layout(32, 8, 16, head_dim=64)) == 0
+    assert kitty.kitty_page_bytes(kitty.make_layout(32, 8, 16, page_size=64)) == 0
+    assert kitty.kitty_page_bytes(kitty.make_layout(32, 8, 16, v_group=32)) == 0
+    assert kitty.kitty_page_bytes(kitty.make_layout(32, 8, 24)) == 0           # not a multiple of 16
+    assert kitty.kitty_page_bytes(kitty.make_layout(32, 8, 48)) == 0           # unsupported count
+    assert kitty.kitty_page_bytes(kitty.make_layout(32, 8, 16, residual_window=64)) == 0
+    assert kitty.kitty_page_bytes(kitty.make_layout(30, 8, 16)) == 0           # heads do not divide
+    assert kitty.kitty_page_bytes(kitty.make_layout(48, 8, 16)) == 0           # GQA group of 6
+    assert kitty.kitty_page_bytes(kitty.make_layout(32, 8, 16, rank_metric=2)) == 0
+
+
+def test_plan_and_workspace():
+    lay = kitty.make_layout(32, 8, 16)
+    ns, pps = kitty.kitty_decode_plan(lay, 32, 255, 0)
+    assert ns >= 1 and pps >= 1 and ns * pps >= 255 and (ns - 1) * pps < 255
+    for req in (1, 2, 7, 255, 1000):
+        ns, pps = kitty.kitty_decode_plan(lay, 32, 255, req)
+        assert ns * pps >= 255 and (ns - 1) * pps < 255 and ns <= max(req, 1) or pps == 1
+        assert kitty.kitty_decode_workspace_bytes(lay, 32, 255, req) == 32 * 32 * (ns + 1) * 130 * 4
+    lay0 = kitty.make_layout(1, 1, 16, residual_window=0)
+    ns, pps = kitty.kitty_decode_plan(lay0, 1, 8, 4)
+    assert (ns, pps) == (4, 2)
+    assert kitty.kitty_decode_workspace_bytes(lay0, 1, 8, 4) == 4 * 130 * 4
+
+
+def test_invalid_arguments_return_codes_without_touching_a_gpu():
+    lib = kitty.lib()
+    lay = kitty.make_layout(32, 8, 16)
+    bad = kitty.make_layout(32, 8, 16, head_dim=64)
+    assert lib.kitty_quantize_pages(None, None, None, 0, 0, 128, None, None, 1, None, 1, None) == kitty.ERR_INVALID_ARG
+    assert lib.kitty_quantize_pages(C.byref(bad), None, None, 0, 0, 128, None, None, 1, None, 1, None) == kitty.ERR_UNSUPPORTED
+    assert lib.kitty_quantize_pages(C.byref(lay), None, None, 0, 0, 128, None, None, 1, None, 1, None) == kitty.ERR_INVALID_ARG
+    assert lib.kitty_quantize_pages(C.byref(lay), None, None, 0, 0, 128, None, None, 0, None, 1, None) == kitty.KITTY_OK
+    # misaligned source, stride not a multiple of 8
+    assert lib.kitty_quantize_pages(C.byref(lay), 0x1008, 0x2000, 16384, 16384, 128, None, 0x3000, 1, 0x4000, 1, None) == kitty.ERR_INVALID_ARG
+    assert lib.kitty_quantize_pages(C.byref(lay), 0x1000, 0x2000, 16384, 16384, 132, None, 0x3000, 1, 0x4000, 1, None) == kitty.ERR_INVALID_ARG
+    cache = kitty.KittyCache(None, None, None, None, None, None, 4, 8, 32)
+    assert lib.kitty_decode_attention(C.byref(lay), C.byref(cache), None, None, 1.0, 0, 0, None, 0, None) == kitty.ERR_INVALID_ARG
+    assert lib.kitty_append_token(C.byref(lay), None, None, None, None, None) == kitty.ERR_INVALID_ARG
+    assert lib.kitty_decode_split(C.byref(lay), C.byref(cache), None, 1.0, 0, None, 0, None) == kitty.ERR_INVALID_ARG
+    # a complete-looking cache with a workspace that is too small
+    cache = kitty.KittyCache(0x10000, 0x20000, 0x30000, 0x40000, 0x50000, 0x60000, 4, 8, 32)
+    assert lib.kitty_decode_split(C.byref(lay), C.byref(cache), 0x70000, 1.0, 0, 0x80000, 64, None) == kitty.ERR_WORKSPACE
+    assert lib.kitty_decode_merge(C.byref(lay), C.byref(cache), 0x70000, 0, 5, 0x80000, 1 << 30, None) == kitty.ERR_INVALID_ARG
+    lay0 = kitty.make_layout(32, 8, 16, residual_window=0)
+    cache0 = kitty.KittyCache(0x10000, 0x20000, 0x30000, None, None, None, 4, 8, 32)
+    assert lib.kitty_append_token(C.byref(lay0), C.byref(cache0), 0x1000, 0x2000, 0x3000, None) == kitty.ERR_UNSUPPORTED
+    assert b"workspace" in lib.kitty_strerror(kitty.ERR_WORKSPACE)
+    assert lib.kitty_strerror(12345) == b"unknown error"

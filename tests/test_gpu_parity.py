@@ -1,0 +1,178 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs.  Packed records must match byte for byte; attention outputs within max-abs 2e-3."""
+import numpy as np
+import pytest
+
+from oracle import kitty_oracle as ko
+from paper_2511_18643_amd import synth
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-3          # the stated bar (fp32 accumulate, bf16 in/out)
+TOL_FP32 = 3e-4     # the fp32 output has no bf16 rounding: anything above this is a kernel bug
+
+
+def pool_of(c):
+    return c.pool.cpu().numpy()
+
+
+def check_pool(w, lengths, oc, gc):
+    gp = pool_of(gc)
+    for b in range(w.batch):
+        for i in range(int(oc.n_pages[b])):
+            pid = oc.page_table[b, i]
+            for h in range(w.n_kv_heads):
+                if not np.array_equal(gp[pid, h], oc.pool[pid, h]):
+                    bad = np.nonzero(gp[pid, h] != oc.pool[pid, h])[0]
+                    raise AssertionError(f"record b={b} page={i} head={h}: {len(bad)} bytes differ, first at {bad[:8]}")
+
+
+def run_case(w, lengths, n_splits_list=(0,), max_pages=None):
+    # groups of 8 query heads carry two byte terms per value instead of three (coarser fixed point)
+    tol32 = TOL_FP32 if w.gqa <= 4 else 1e-3
+    k, v = H.gen_sequences(w, lengths)
+    mp = max_pages or max(max((w.pages_and_resid(n)[0] if n else 0) for n in lengths), 1)
+    oc = H.oracle_cache(w, lengths, k, v, mp)
+    layout, gc = H.gpu_cache(w, lengths, k, v, mp)
+    check_pool(w, lengths, oc, gc)
+    q = synth.query(w)
+    want = oc.decode_attention(q, w.sm_scale)
+    worst = 0.0
+    for ns in n_splits_list:
+        got = H.gpu_decode(layout, gc, q, w.sm_scale, ns, fp32=True)
+        err = np.abs(got - want).max()
+        assert np.isfinite(got).all()
+        assert err <= tol32, f"fp32 out: max abs err {err} (n_splits={ns})"
+        got16 = H.gpu_decode(layout, gc, q, w.sm_scale, ns, fp32=False)
+        # bf16 output: 2e-3 wherever the bf16 grid allows it (half an ulp is 0.98e-3 below 0.5 but
+        # 1.95e-3 in [0.5, 1) and 3.9e-3 in [1, 2)); above that, half an ulp plus the fp32 error
+        half_ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(want), 1e-30))) - 8)
+        bound = np.where(np.abs(want) < 0.5, TOL, half_ulp + tol32)
+        err16 = np.abs(got16 - want)
+        assert np.all(err16 <= bound), f"bf16 out: max abs err {err16.max()} (n_splits={ns})"
+        # the bf16 output is the fp32 output rounded to nearest even
+        assert np.array_equal(got16, ko.bf16_bits_to_f32(ko.f32_to_bf16_bits(got)))
+        worst = max(worst, err)
+    return worst
+
+
+def test_c1_both_metrics():
+    w = synth.WORKLOADS["c1"]
+    for metric in (1, 0):
+        run_case(synth.scaled(w, rank_metric=metric), [1024], n_splits_list=(0, 1, 2, 8))
+
+
+@pytest.mark.parametrize("nb", [0, 16, 32, 64, 128])
+def test_boost_counts(nb):
+    w = synth.scaled(synth.WORKLOADS["c2"], batch=2, n_q_heads=8, n_kv_heads=2, n_boost=nb)
+    run_case(w, [5 * 128 + 60, 3 * 128 + 128], n_splits_list=(0, 2))
+
+
+@pytest.mark.parametrize("g", [1, 2, 4, 8])
+def test_gqa_groups(g):
+    w = synth.scaled(synth.WORKLOADS["c2"], batch=2, n_q_heads=2 * g, n_kv_heads=2)
+    run_case(w, [9 * 128 + 1, 2 * 128 + 77], n_splits_list=(0, 3))
+
+
+def test_ragged_lengths_and_empty():
+    w = synth.scaled(synth.WORKLOADS["c2"], batch=6, n_q_heads=8, n_kv_heads=2)
+    # empty, window only (1 and 128 rows), one page + 1, many pages, exact multiple
+    run_case(w, [0, 1, 128, 129, 17 * 128 + 5, 4 * 128], n_splits_list=(0, 1, 5, 17))
+
+
+def test_one_page_per_split_and_two_page_chunks():
+    w = synth.scaled(synth.WORKLOADS["c2"], batch=1, n_q_heads=4, n_kv_heads=1)
+    n = 12 * 128 + 128
+    run_case(w, [n], n_splits_list=(12, 6), max_pages=12)      # 1 page and 2 pages (256 tokens) per split
+
+
+def test_c4_shape_small():
+    w = synth.scaled(synth.WORKLOADS["c4"], batch=1, n_q_heads=16, n_kv_heads=2)
+    run_case(w, [20 * 128 + 128], n_splits_list=(0, 4))
+
+
+def test_adversarial_pages_bit_exact():
+    """Ties in the ranking, constant channels/tokens, tiny and huge magnitudes, all-zero page."""
+    import torch
+    from paper_2511_18643_amd import kitty
+    r = np.random.default_rng(77)
+    pages = []
+    x = r.standard_normal((128, 128)).astype(np.float32)
+    pages.append(x.copy())                                              # plain
+    y = np.round(x * 4) / 4; pages.append(y)                            # coarse grid: many range ties
+    z = x.copy(); z[:, 5] = 2.0; z[:, 6] = 0.0; z[17, :] = -1.0; pages.append(z)   # constant channel / token
+    pages.append(np.zeros((128, 128), np.float32))                      # all zero
+    pages.append(x * 1e-6)                                              # tiny: subnormal fp16 scales
+    pages.append(x * 3000.0)                                            # large
+    t = np.tile(np.arange(128, dtype=np.float32)[:, None], (1, 128)); pages.append(t)   # identical channels
+    pages.append(np.where(r.random((128, 128)) < 0.5, -1.0, 1.0).astype(np.float32))    # two-level
+    kbits = np.stack([synth.to_bf16_bits(p) for p in pages])[:, None]   # [n][1][128][128]
+    vbits = kbits[::-1].copy()
+    n = len(pages)
+    for nb in (0, 16, 32):
+        for metric in (0, 1):
+            oc = ko.KittyCacheOracle(1, 1, 1, nb, 128, n, n, metric)
+            oc.quantize_pages(kbits, vbits, list(range(n)))
+            layout = kitty.make_layout(1, 1, nb, 128, metric)
+            gc = kitty.Cache(layout, 1, n, n)
+            gc.pool.fill_(0x5A)
+            kt, vt = H.bf16_tensor(kbits), H.bf16_tensor(vbits)
+            ids = torch.arange(n, dtype=torch.int32, device="cuda")
+            kitty.kitty_quantize_pages(layout, kt, vt, 128 * 128, 128 * 128, 128, ids, n, gc.pool, n)
+            torch.cuda.synchronize()
+            gp = gc.pool.cpu().numpy()
+            for i in range(n):
+                assert np.array_equal(gp[i, 0], oc.pool[i, 0]), f"page {i} nb={nb} metric={metric}"
+
+
+def test_append_loop_matches_oracle():
+    import torch
+    from paper_2511_18643_amd import kitty
+    w = synth.scaled(synth.WORKLOADS["c2"], batch=3, n_q_heads=8, n_kv_heads=2, context=0)
+    mp = 4
+    oc = ko.KittyCacheOracle(3, 2, 8, 16, 128, mp, 3 * mp, 0)
+    layout = kitty.make_layout(8, 2, 16, 128, 0)
+    gc = kitty.Cache(layout, 3, mp, 3 * mp)
+    ws = kitty.new_workspace(layout, 3, mp)
+    # sequences start at different fill levels: empty, window full, one page + 100
+    start = [0, 128, 228]
+    k0, v0 = H.gen_sequences(w, start)
+    oc = H.oracle_cache(w, start, k0, v0, mp)
+    layout, gc = H.gpu_cache(w, start, k0, v0, mp)
+    for step in range(1, 190):
+        kn, vn = synth.new_token(w, step)
+        fresh = np.array([b * mp + int(oc.n_pages[b]) for b in range(3)], np.int32)
+        oc.append_token(kn, vn, fresh)
+        kitty.kitty_append_token(layout, gc, H.bf16_tensor(kn), H.bf16_tensor(vn),
+                                 torch.from_numpy(fresh).cuda())
+        if step in (1, 27, 28, 29, 100, 127, 128, 129, 156, 157, 189):
+            torch.cuda.synchronize()
+            assert np.array_equal(gc.n_pages.cpu().numpy(), oc.n_pages), step
+            assert np.array_equal(gc.n_resid.cpu().numpy(), oc.n_resid), step
+            assert np.array_equal(gc.page_table.cpu().numpy(), oc.page_table), step
+            check_pool(w, None, oc, gc)
+            for b in range(3):
+                rr = int(oc.n_resid[b])
+                gk = gc.resid_k[b, :, :rr].view(torch.int16).cpu().numpy().view(np.uint16)
+                gv = gc.resid_v[b, :, :rr].view(torch.int16).cpu().numpy().view(np.uint16)
+                assert np.array_equal(gk, oc.resid_k[b, :, :rr]) and np.array_equal(gv, oc.resid_v[b, :, :rr])
+            q = synth.query(w, step)
+            want = oc.decode_attention(q, w.sm_scale)
+            got = H.gpu_decode(layout, gc, q, w.sm_scale, 0, fp32=True)
+            assert np.abs(got - want).max() <= TOL_FP32, step
+
+
+def test_append_with_full_page_table_leaves_sequence_unchanged():
+    import torch
+    from paper_2511_18643_amd import kitty
+    w = synth.scaled(synth.WORKLOADS["c2"], batch=1, n_q_heads=4, n_kv_heads=1, context=0)
+    k0, v0 = H.gen_sequences(w, [256])
+    layout, gc = H.gpu_cache(w, [256], k0, v0, 1)          # 1 page + full window, table of 1 page
+    before = (gc.n_pages.clone(), gc.n_resid.clone(), gc.resid_k.clone(), gc.pool.clone())
+    kn, vn = synth.new_token(w, 1)
+    kitty.kitty_append_token(layout, gc, H.bf16_tensor(kn), H.bf16_tensor(vn),
+                             torch.zeros(1, dtype=torch.int32, device="cuda"))
+    torch.cuda.synchronize()
+    assert torch.equal(gc.n_pages, before[0]) and torch.equal(gc.n_resid, before[1])
+    assert torch.equal(gc.resid_k, before[2]) and torch.equal(gc.pool, before[3])
