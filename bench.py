@@ -1,0 +1,270 @@
+#!/usr/bin/env python3
+"""Benchmark of the Kitty decode hot path on one MI355X.
+
+A step is one pass of the whole hot path over one batch: kitty_append_token (window insert, and the
+page quantizer whenever a window is full) followed by kitty_decode_attention (split-K kernel +
+merge) — one decode step of one attention layer.  Inputs are resident in HBM before the timed
+region.  Steps rotate over several copies of the cache so that every step streams its records
+from HBM rather than from the 256 MB last-level cache.
+
+Prints one JSON line: effective HBM GB/s of the step (algorithmic bytes / time), the roofline
+record of the dominant kernel (decode split-K, timed on its own with HIP events) and the CPU
+oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4"])
+    ap.add_argument("--copies", type=int, default=0, help="cache copies to rotate over (0 = enough for >= 1.2 GB)")
+    ap.add_argument("--n-splits", type=int, default=0)
+    ap.add_argument("--src-seqs", type=int, default=2, help="distinct synthetic sequences tiled over the batch")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-pairs", type=int, default=0, help="(sequence, kv-head) pairs in the oracle sample (0 = auto)")
+    return ap.parse_args()
+
+
+def step_bytes(payload, n_pages, n_resid, w):
+    """Algorithmic bytes of one decode_attention call: records + window rows + q + out."""
+    per_pair = n_pages * payload + n_resid * 128 * 2 * 2
+    return w.batch * w.n_kv_heads * per_pair + 2 * w.batch * w.n_q_heads * 128 * 2
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2511_18643_amd import kitty, synth
+    from tests import helpers as H
+
+    kitty.lib()      # fails loudly if libkitty.so is missing
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda"
+    w = synth.WORKLOADS[args.workload]
+    layout = kitty.make_layout(w.n_q_heads, w.n_kv_heads, w.n_boost, w.residual_window, w.rank_metric)
+    payload = kitty.kitty_page_payload_bytes(layout)
+    rec_bytes = kitty.kitty_page_bytes(layout)
+    n_pages0, r0 = w.pages_and_resid()                      # c3: 255 pages + 128 window rows
+    hkv, B = w.n_kv_heads, w.batch
+    copy_bytes = B * hkv * (n_pages0 * rec_bytes + 128 * 128 * 4)
+    n_copies = args.copies or max(2, int(np.ceil(1.2e9 / copy_bytes)))
+    total_steps = args.warmup + args.steps
+    steps_per_copy = (total_steps + n_copies - 1) // n_copies
+    extra_pages = (r0 + steps_per_copy) // 128 + 1
+    max_pages = n_pages0 + extra_pages
+
+    # ---- synthetic K/V: `src_seqs` distinct sequences (all kv-heads), tiled over the batch ----------
+    t0 = time.time()
+    nsrc = min(args.src_seqs, B)
+    L = n_pages0 * 128 + 128
+    ksrc = np.zeros((nsrc, hkv, L, 128), np.uint16)
+    vsrc = np.zeros_like(ksrc)
+    for sb in range(nsrc):
+        for h in range(hkv):
+            ksrc[sb, h], vsrc[sb, h] = synth.kv_block(w, sb, h, L)
+    kt, vt = H.bf16_tensor(ksrc, dev), H.bf16_tensor(vsrc, dev)
+    gen_s = time.time() - t0
+
+    # ---- caches: prefill pages through kitty_quantize_pages, window = the tail tokens ---------------
+    # the window starts `warm_per_copy + 1` rows short of full, so that the first timed step of each copy
+    # runs at exactly the workload's shape (n_pages0 pages + 128 window rows)
+    warm_per_copy = (args.warmup + n_copies - 1) // n_copies
+    r_init = max(128 - 1 - warm_per_copy, 0)
+    caches, states = [], []
+    offs = torch.tensor([(b % nsrc) * hkv * L * 128 + i * 128 * 128 for b in range(B) for i in range(n_pages0)],
+                        dtype=torch.int64, device=dev)
+    ids = torch.tensor([b * max_pages + i for b in range(B) for i in range(n_pages0)], dtype=torch.int32, device=dev)
+    tq0 = time.time()
+    for c in range(n_copies):
+        cache = kitty.Cache(layout, B, max_pages, B * max_pages, device=dev)
+        kitty.kitty_quantize_pages(layout, kt, vt, 128 * 128, L * 128, 128, ids, B * n_pages0, cache.pool,
+                                   cache.n_pool_pages, src_page_offsets=offs)
+        pt = torch.arange(max_pages, dtype=torch.int32, device=dev)[None, :] + \
+            (torch.arange(B, dtype=torch.int32, device=dev) * max_pages)[:, None]
+        cache.page_table.copy_(pt)
+        cache.n_pages.fill_(n_pages0)
+        for b in range(B):
+            cache.resid_k[b] = kt[b % nsrc, :, n_pages0 * 128:]
+            cache.resid_v[b] = vt[b % nsrc, :, n_pages0 * 128:]
+        cache.n_resid.fill_(r_init)
+        caches.append(cache)
+        states.append([n_pages0, r_init])
+    torch.cuda.synchronize()
+    quant_s = time.time() - tq0
+
+    ws = kitty.new_workspace(layout, B, max_pages, args.n_splits, device=dev)
+    ns, pps = kitty.kitty_decode_plan(layout, B, max_pages, args.n_splits)
+    n_rot = 4
+    qs = [H.bf16_tensor(synth.query(w, s), dev) for s in range(n_rot)]
+    newt = [tuple(H.bf16_tensor(x, dev) for x in synth.new_token(w, s)) for s in range(n_rot)]
+    out = torch.empty((B, w.n_q_heads, 128), dtype=torch.bfloat16, device=dev)
+    fresh = [torch.tensor([b * max_pages for b in range(B)], dtype=torch.int32, device=dev) for _ in range(n_copies)]
+
+    def do_step(i):
+        c = i % n_copies
+        cache, st = caches[c], states[c]
+        if st[1] == 128:                       # this append flushes: page id = next free slot of the sequence
+            fresh[c].copy_(torch.arange(B, dtype=torch.int32, device=dev) * max_pages + st[0])
+            st[0] += 1
+            st[1] = 0
+        st[1] += 1
+        kn, vn = newt[i % n_rot]
+        kitty.kitty_append_token(layout, cache, kn, vn, fresh[c])
+        kitty.kitty_decode_attention(layout, cache, qs[i % n_rot], out, w.sm_scale, ws, args.n_splits)
+        return step_bytes(payload, st[0], st[1], w)
+
+    for i in range(args.warmup):
+        do_step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    total_bytes = 0
+    for i in range(args.warmup, total_steps):
+        total_bytes += do_step(i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    gbps = total_bytes / dt / 1e9
+    tokens_per_s = B * args.steps / dt
+
+    # ---- dominant kernel on its own: decode split-K, HIP events on the launch stream ----------------
+    n_kern = max(args.steps, 50)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    kbytes = 0
+    for i in range(4):
+        kitty.kitty_decode_split(layout, caches[i % n_copies], qs[0], w.sm_scale, ws, args.n_splits)
+    torch.cuda.synchronize()
+    ev0.record()
+    for i in range(n_kern):
+        c = i % n_copies
+        kitty.kitty_decode_split(layout, caches[c], qs[i % n_rot], w.sm_scale, ws, args.n_splits)
+        kbytes += step_bytes(payload, states[c][0], states[c][1], w)
+    ev1.record()
+    torch.cuda.synchronize()
+    kern_ms = ev0.elapsed_time(ev1) / n_kern
+    kern_gbps = kbytes / n_kern / (kern_ms * 1e-3) / 1e9
+
+    # ---- page quantizer on its own (prefill rate), for the record ---------------------------------
+    ev0.record()
+    kitty.kitty_quantize_pages(layout, kt, vt, 128 * 128, L * 128, 128, ids, B * n_pages0, caches[0].pool,
+                               caches[0].n_pool_pages, src_page_offsets=offs)
+    ev1.record()
+    torch.cuda.synchronize()
+    quant_ms = ev0.elapsed_time(ev1)
+    quant_pages = B * n_pages0 * hkv
+    # restore: the records just rewritten are identical (same inputs), nothing else to do
+
+    # ---- CPU oracle on a bounded sample of the same workload + live parity on that sample -------
+    cpu = None
+    max_err = None
+    if not args.no_cpu_baseline:
+        from oracle import kitty_oracle as ko
+        c0 = caches[0]
+        n_pairs = args.cpu_pairs or max(1, min(4, int(3.0e8 / (L * 128 * 8))))
+        pairs_kv = [(b, h) for b in range(min(nsrc, B)) for h in range(hkv)][:n_pairs]
+        # rebuild the sampled sequences on the CPU from the inputs (never from GPU results)
+        oc = ko.KittyCacheOracle(B, hkv, w.n_q_heads, w.n_boost, w.residual_window, max_pages, B * max_pages,
+                                 w.rank_metric)
+        tq = time.time()
+        for (b, h) in pairs_kv:
+            for i in range(n_pages0):
+                kp = ko.quantize_k_page(ko.bf16_bits_to_f32(ksrc[b % nsrc, h, 128 * i:128 * (i + 1)]), w.n_boost, w.rank_metric)
+                vp = ko.quantize_v_page(ko.bf16_bits_to_f32(vsrc[b % nsrc, h, 128 * i:128 * (i + 1)]))
+                oc.pool[b * max_pages + i, h] = ko.pack_record(kp, vp)
+        oracle_quant_s = time.time() - tq
+        # replay copy 0's history on the oracle for the sampled pairs: window tail + appended tokens
+        oc.page_table[:] = np.arange(max_pages)[None, :] + (np.arange(B) * max_pages)[:, None]
+        oc.n_pages[:] = n_pages0
+        oc.n_resid[:] = r_init
+        for b in range(B):
+            oc.resid_k[b] = ksrc[b % nsrc, :, n_pages0 * 128:]
+            oc.resid_v[b] = vsrc[b % nsrc, :, n_pages0 * 128:]
+        sample_b = sorted({b for b, _ in pairs_kv})
+        steps_c0 = [i for i in range(total_steps) if i % n_copies == 0]
+        new_np = [tuple(x for x in synth.new_token(w, s)) for s in range(n_rot)]
+        for i in steps_c0:
+            kn, vn = new_np[i % n_rot]
+            for b in sample_b:          # the oracle's append, restricted to the sampled sequences
+                if oc.n_resid[b] == 128:
+                    pid = b * max_pages + int(oc.n_pages[b])
+                    for h in range(hkv):
+                        if (b, h) in pairs_kv:
+                            kp = ko.quantize_k_page(ko.bf16_bits_to_f32(oc.resid_k[b, h]), w.n_boost, w.rank_metric)
+                            vp = ko.quantize_v_page(ko.bf16_bits_to_f32(oc.resid_v[b, h]))
+                            oc.pool[pid, h] = ko.pack_record(kp, vp)
+                    oc.n_pages[b] += 1
+                    oc.n_resid[b] = 0
+                oc.resid_k[b, :, oc.n_resid[b]] = kn[b]
+                oc.resid_v[b, :, oc.n_resid[b]] = vn[b]
+                oc.n_resid[b] += 1
+        # GPU result for the current state of copy 0 with query 0
+        out32 = torch.empty((B, w.n_q_heads, 128), dtype=torch.float32, device=dev)
+        kitty.kitty_decode_attention(layout, c0, qs[0], out32, w.sm_scale, ws, args.n_splits)
+        torch.cuda.synchronize()
+        got = out32.cpu().numpy()
+        qbits = synth.query(w, 0)
+        g = w.gqa
+        hq_pairs = [(b, h * g + e) for (b, h) in pairs_kv for e in range(g)]
+        cpu_t0, wall_t0 = time.process_time(), time.perf_counter()
+        want = oc.decode_attention(qbits, w.sm_scale, pairs=hq_pairs)
+        wall = time.perf_counter() - wall_t0
+        cpu_used = time.process_time() - cpu_t0
+        max_err = max(float(np.abs(got[b, hq] - want[b, hq]).max()) for b, hq in hq_pairs)
+        sample_bytes = len(pairs_kv) * (int(oc.n_pages[sample_b[0]]) * payload + int(oc.n_resid[sample_b[0]]) * 512) \
+            + 2 * len(hq_pairs) * 256
+        cpu = {
+            "value": round(sample_bytes / wall / 1e9, 4), "unit": "GB/s",
+            "cores": max(1, int(round(cpu_used / max(wall, 1e-9)))), "kind": "oracle",
+            "sample": f"{len(pairs_kv)} of {B * hkv} (sequence, kv-head) pairs at full context, all {g} query heads each, "
+                      f"{wall:.1f} s wall (decode attention only; oracle quantization of the sample took {oracle_quant_s:.1f} s)",
+        }
+
+    res = {
+        "metric": "decode_attn_effective_hbm_gbps", "value": round(gbps, 1), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8",
+        "data": "synthetic",
+        "config": {
+            "workload": f"{w.name}: batch {B}, {w.n_q_heads}q/{hkv}kv heads, head_dim 128, context {w.context} "
+                        f"({n_pages0} pages + 128-token bf16 window at the first timed step), n_boost {w.n_boost}, "
+                        f"step = append_token + decode_attention",
+            "n_splits": ns, "pages_per_split": pps, "cache_copies": n_copies, "record_bytes": rec_bytes,
+            "payload_bytes_per_page": payload, "distinct_source_sequences": nsrc,
+        },
+        "pct_of_hbm_peak": round(100.0 * gbps / HBM_PEAK_GBPS, 2),
+        "decode_tokens_per_s": round(tokens_per_s, 1),
+        "roofline": {
+            "bound": "hbm", "kernel": "decode_split_kernel", "achieved": round(kern_gbps, 1), "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s", "frac": round(kern_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+            "avg_launch_ms": round(kern_ms, 5), "algorithmic_bytes_per_launch": int(kbytes / n_kern),
+        },
+        "cpu_baseline": cpu,
+        "max_abs_err_vs_oracle_sample": max_err,
+        "quantize_pages": {"pages": quant_pages, "ms": round(quant_ms, 4),
+                           "input_gbps": round(quant_pages * 65536 / (quant_ms * 1e-3) / 1e9, 1)},
+        "setup_s": {"generate": round(gen_s, 1), "prefill_quantize_all_copies": round(quant_s, 2)},
+    }
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()
