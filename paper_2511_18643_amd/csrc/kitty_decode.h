@@ -96,15 +96,20 @@ __device__ __forceinline__ uint32_t gather_byte(uint32_t a, uint32_t b, uint32_t
   return __builtin_amdgcn_perm(hi, lo, 0x05040100u);
 }
 
-// eight integers -> TR planes of eight signed bytes: n = t0 + 256 t1 (+ 65536 t2), each t in [-128,127]
+// Integer images are kept as the raw bits of (x + 1.5*2^23): for |x| < 2^22 the low 23 bits hold
+// 2^22 + round(x), so byte 0 of the bits is byte 0 of n = round(x), and the carries of the balanced
+// byte split (n = t0 + 256 t1 + 65536 t2, each t in [-128,127]) are single adds on the same bits.
+constexpr float MAGIC = 12582912.0f;            // 1.5 * 2^23 = 0x4b400000
+constexpr uint32_t T1_ADD = 0x80u;              // byte 1 of (bits + 0x80)            = t1
+constexpr uint32_t T2_ADD = 0x8080u - 0x400000u;  // byte 2 of (bits + 0x8080 - 0x400000) = t2
+
 template <int TR>
-__device__ __forceinline__ void split_terms(const int (&n)[8], uint2 (&w)[TR]) {
-  uint32_t u[8], t1[8], t2[8];
+__device__ __forceinline__ void split_terms(const uint32_t (&u)[8], uint2 (&w)[TR]) {
+  uint32_t t1[8], t2[8];
 #pragma unroll
   for (int k = 0; k < 8; ++k) {
-    u[k] = (uint32_t)n[k];
-    t1[k] = u[k] + 0x80u;
-    t2[k] = u[k] + 0x8080u;
+    t1[k] = u[k] + T1_ADD;
+    t2[k] = u[k] + T2_ADD;
   }
   w[0].x = gather_byte<0>(u[0], u[1], u[2], u[3]);
   w[0].y = gather_byte<0>(u[4], u[5], u[6], u[7]);
@@ -114,11 +119,6 @@ __device__ __forceinline__ void split_terms(const int (&n)[8], uint2 (&w)[TR]) {
     w[2].x = gather_byte<2>(t2[0], t2[1], t2[2], t2[3]);
     w[2].y = gather_byte<2>(t2[4], t2[5], t2[6], t2[7]);
   }
-}
-
-// round to nearest for |x| < 2^22: adding 1.5*2^23 leaves the integer in the low mantissa bits
-__device__ __forceinline__ int round_to_int(float x) {
-  return (int)(__float_as_uint(x + 12582912.0f) - 0x4b400000u);
 }
 
 __device__ __forceinline__ void f16x8_to_f32(const uint4& v, float (&f)[8]) {
@@ -142,7 +142,7 @@ __device__ __forceinline__ void wave_lds_fence() {
 // 16-byte reads of the sixteen rows fall into different banks.
 template <int NB16, int HPL>
 struct WaveScratch {
-  int32_t nbuf[4 * HPL][D];                      // integer q*s per (head, channel), for the boost gather
+  uint32_t nbuf[4 * HPL][D];                     // integer image (raw bits) of q*s per (head, channel), for the boost gather
   uint8_t abuf[16][144];                         // rows (head, term) x channel
   uint8_t bbuf[16][16 * (NB16 ? NB16 : 1) + 16];  // rows (head, term) x boost slot
   uint8_t pbuf[16][144];                         // rows (head, term) x position
@@ -163,22 +163,197 @@ union __attribute__((aligned(16))) DecodeSmem {
   MergeScratch<HPL> mg;
 };
 
+// Running state of one wavefront on the packed-page path and the work done per page.
+// Lane l = (j = l & 15, gi = l >> 4).  In the "compact" role the lane owns channels 8j..8j+7 (K side)
+// or positions 8j..8j+7 (V side) of heads gi*HPL + e; in the matrix role it is row/column j of
+// k-block gi.  Both roles put head gi*HPL + e in lane group gi, so no cross-group traffic is needed.
+template <int NB16, int HPL>
+struct PageWorker {
+  static constexpr int TR = HPL == 1 ? 3 : 2;     // byte terms per value
+  static constexpr int RPH = 4 / HPL;             // matrix rows per head
+  static constexpr float NLIM = TR == 3 ? 1048000.0f : 32000.0f;   // bound of the integer images
+
+  WaveScratch<NB16, HPL>& ws;
+  const int j, gi;
+  const uint8_t* a_ptr;      // A operand of the logits: row j, k-block gi
+  const uint8_t* p_ptr;      // A operand of the Value sum
+  const uint8_t* b_ptr[4];   // boost rows for tile kb (zeros unless gi == kb)
+  float qv[HPL][8];          // q * sm_scale * log2(e), compact layout
+  float m_run[HPL], l_run[HPL], z_run[HPL];
+  float acc[HPL][8];         // channel 16*Td + j
+
+  __device__ __forceinline__ PageWorker(WaveScratch<NB16, HPL>& ws_, int l)
+      : ws(ws_), j(l & 15), gi(l >> 4) {
+    a_ptr = &ws.abuf[j][16 * gi];
+    p_ptr = &ws.pbuf[j][16 * gi];
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb) b_ptr[kb] = (gi == kb) ? &ws.bbuf[j][0] : ws.zero;
+#pragma unroll
+    for (int e = 0; e < HPL; ++e) {
+      m_run[e] = -INFINITY; l_run[e] = 0.f; z_run[e] = 0.f;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) acc[e][k] = 0.f;
+    }
+  }
+
+  __device__ __forceinline__ void process(const PageRegs<NB16>& pg) {
+    // ================= A: integer image of q*s, bias q.z =================
+    float ks[8], kz[8];
+    f16x8_to_f32(pg.ksc, ks);
+    f16x8_to_f32(pg.kzr, kz);
+    float inv_alpha[HPL], bias[HPL];
+#pragma unroll
+    for (int e = 0; e < HPL; ++e) {
+      float qs[8], amax = 0.f, bsum = 0.f;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        qs[k] = qv[e][k] * ks[k];
+        amax = fmaxf(amax, fabsf(qs[k]));
+        bsum = fmaf(qv[e][k], kz[k], bsum);
+      }
+      amax = fmaxf(row_max(amax), 1e-30f);
+      bias[e] = row_sum(bsum);
+      const float alpha = NLIM / amax;
+      inv_alpha[e] = amax * (1.0f / NLIM);
+      uint32_t u[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) u[k] = __float_as_uint(fmaf(qs[k], alpha, MAGIC));
+      uint2 tw[TR];
+      split_terms<TR>(u, tw);
+      const int hd = gi * HPL + e;
+#pragma unroll
+      for (int t = 0; t < TR; ++t) *reinterpret_cast<uint2*>(&ws.abuf[hd * RPH + t][8 * j]) = tw[t];
+      if constexpr (NB16 > 0) {
+        *reinterpret_cast<uint4*>(&ws.nbuf[hd][8 * j]) = make_uint4(u[0], u[1], u[2], u[3]);
+        *reinterpret_cast<uint4*>(&ws.nbuf[hd][8 * j + 4]) = make_uint4(u[4], u[5], u[6], u[7]);
+      }
+    }
+    wave_lds_fence();
+    // ================= B: same integers gathered through the boosted-channel list =================
+    if constexpr (NB16 > 0) {
+#pragma unroll
+      for (int s = 0; s < NB16; ++s) {
+#pragma unroll
+        for (int e = 0; e < HPL; ++e) {
+          const int hd = gi * HPL + e;
+          const uint32_t nn = ws.nbuf[hd][pg.chv[s]];
+          ws.bbuf[hd * RPH + 0][16 * s + j] = (uint8_t)nn;
+          ws.bbuf[hd * RPH + 1][16 * s + j] = (uint8_t)((nn + T1_ADD) >> 8);
+          if constexpr (TR == 3) ws.bbuf[hd * RPH + 2][16 * s + j] = (uint8_t)((nn + T2_ADD) >> 16);
+        }
+      }
+      wave_lds_fence();
+    }
+    // ================= C: logits for 128 tokens x heads on the int8 matrix cores =================
+    const v4i a0 = *reinterpret_cast<const v4i*>(a_ptr);
+    const v4i a1 = *reinterpret_cast<const v4i*>(a_ptr + 64);
+    v4i dq[8];
+#pragma unroll
+    for (int T = 0; T < 8; ++T) {
+      const uint4 ld = pg.kd[T >> 1];
+      const uint32_t w0 = (T & 1) ? ld.z : ld.x, w1 = (T & 1) ? ld.w : ld.y;
+      v4i c = {0, 0, 0, 0};
+      c = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0, unpack16(w0), c, 0, 0, 0);
+      c = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1, unpack16(w1), c, 0, 0, 0);
+      dq[T] = c;
+    }
+    if constexpr (NB16 > 0) {
+#pragma unroll
+      for (int s = 0; s < NB16; ++s) {
+        // tile 4u+kb of the boost plane lives in the lanes of k-block kb: feed A only to that block
+        v4i ab[4];
+#pragma unroll
+        for (int kb = 0; kb < 4; ++kb) ab[kb] = *reinterpret_cast<const v4i*>(b_ptr[kb] + (gi == kb ? 16 * s : 0));
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          const v4i bb = unpack16_x4(u ? pg.kb[s].y : pg.kb[s].x);
+#pragma unroll
+          for (int kb = 0; kb < 4; ++kb)
+            dq[4 * u + kb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ab[kb], bb, dq[4 * u + kb], 0, 0, 0);
+        }
+      }
+    }
+    // ================= D: online softmax; lane (j, gi) owns token 16T + j of heads gi*HPL + e ==========
+    float vs[8], vz[8];
+    f16x8_to_f32(pg.vsc, vs);
+    f16x8_to_f32(pg.vzr, vz);
+    float corr[HPL], inv_beta[HPL];
+#pragma unroll
+    for (int e = 0; e < HPL; ++e) {
+      float x[8], mx = -INFINITY;
+#pragma unroll
+      for (int T = 0; T < 8; ++T) {
+        int nl;
+        if constexpr (TR == 3) nl = dq[T][0] + dq[T][1] * 256 + dq[T][2] * 65536;
+        else nl = dq[T][2 * e] + dq[T][2 * e + 1] * 256;
+        x[T] = fmaf((float)nl, inv_alpha[e], bias[e]);
+        mx = fmaxf(mx, x[T]);
+      }
+      mx = row_max(mx);
+      const float m_new = fmaxf(m_run[e], mx);
+      corr[e] = __builtin_amdgcn_exp2f(m_run[e] - m_new);
+      m_run[e] = m_new;
+      float ps[8], psum = 0.f, zsum = 0.f, pmax = 0.f;
+#pragma unroll
+      for (int T = 0; T < 8; ++T) {
+        const float pT = __builtin_amdgcn_exp2f(x[T] - m_new);
+        psum += pT;
+        zsum = fmaf(pT, vz[T], zsum);
+        ps[T] = pT * vs[T];
+        pmax = fmaxf(pmax, ps[T]);
+      }
+      l_run[e] = fmaf(l_run[e], corr[e], psum);
+      z_run[e] = fmaf(z_run[e], corr[e], zsum);
+      pmax = fmaxf(row_max(pmax), 1e-30f);
+      const float beta = NLIM / pmax;
+      inv_beta[e] = pmax * (1.0f / NLIM);
+      uint32_t u[8];
+#pragma unroll
+      for (int T = 0; T < 8; ++T) u[T] = __float_as_uint(fmaf(ps[T], beta, MAGIC));
+      uint2 tw[TR];
+      split_terms<TR>(u, tw);
+      const int hd = gi * HPL + e;
+#pragma unroll
+      for (int t = 0; t < TR; ++t) *reinterpret_cast<uint2*>(&ws.pbuf[hd * RPH + t][8 * j]) = tw[t];
+    }
+    wave_lds_fence();
+    // ================= E: weighted Value sum on the int8 matrix cores =================
+    const v4i pa0 = *reinterpret_cast<const v4i*>(p_ptr);
+    const v4i pa1 = *reinterpret_cast<const v4i*>(p_ptr + 64);
+#pragma unroll
+    for (int Td = 0; Td < 8; ++Td) {
+      const uint4 ld = pg.vd[Td >> 1];
+      const uint32_t w0 = (Td & 1) ? ld.z : ld.x, w1 = (Td & 1) ? ld.w : ld.y;
+      v4i c = {0, 0, 0, 0};
+      c = __builtin_amdgcn_mfma_i32_16x16x64_i8(pa0, unpack16(w0), c, 0, 0, 0);
+      c = __builtin_amdgcn_mfma_i32_16x16x64_i8(pa1, unpack16(w1), c, 0, 0, 0);
+#pragma unroll
+      for (int e = 0; e < HPL; ++e) {
+        int ne;
+        if constexpr (TR == 3) ne = c[0] + c[1] * 256 + c[2] * 65536;
+        else ne = c[2 * e] + c[2 * e + 1] * 256;
+        acc[e][Td] = fmaf(acc[e][Td], corr[e], (float)ne * inv_beta[e]);
+      }
+    }
+    wave_lds_fence();   // the next page overwrites abuf/pbuf
+  }
+};
+
 // HPL = query heads per lane: 1 for GQA groups of 1, 2, 4 (three byte terms), 2 for groups of 8
 // (two byte terms).  Grid: x = split slot (n_splits page ranges, then the window), y = kv-head,
-// z = sequence.  Block = 4 wavefronts.
+// z = sequence.  Block = 4 wavefronts; wavefront w takes pages p0+w, p0+w+4, ... of the range.
 template <int NB16, int HPL>
 __global__ __launch_bounds__(256, 2) void decode_split_kernel(DecodeParams p) {
   using R = Rec<NB16>;
-  constexpr int TR = HPL == 1 ? 3 : 2;     // byte terms
-  constexpr int RPH = 4 / HPL;             // matrix rows per head
+  constexpr int RPH = 4 / HPL;
   constexpr int NH = 4 * HPL;              // heads handled by the block
-  constexpr float NLIM = TR == 3 ? 1048000.0f : 32000.0f;   // bound of the integer images
 
   __shared__ DecodeSmem<NB16, HPL> smem;
 
   const int slot = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x;
-  const int w = tid >> 6, l = tid & 63, j = l & 15, gi = l >> 4;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: page ids stay in scalar registers
+  const int l = tid & 63, j = l & 15, gi = l >> 4;
   const int g = p.gqa;
   const int n_slots = p.n_splits + p.has_window;
 
@@ -194,21 +369,12 @@ __global__ __launch_bounds__(256, 2) void decode_split_kernel(DecodeParams p) {
     if (r <= 0) return;
   }
 
-  // running state of this wavefront, per head handled by the lane (head = gi*HPL + e)
-  float m_run[HPL], l_run[HPL], z_run[HPL];
-  float acc[HPL][8];        // page path: channel 16*Td + j ; window path: see below
-#pragma unroll
-  for (int e = 0; e < HPL; ++e) {
-    m_run[e] = -INFINITY; l_run[e] = 0.f; z_run[e] = 0.f;
-#pragma unroll
-    for (int k = 0; k < 8; ++k) acc[e][k] = 0.f;
-  }
+  WaveScratch<NB16, HPL>& ws = smem.w[w];
+  const size_t qrow = ((size_t)b * p.n_q_heads + (size_t)h * g);
+  PageWorker<NB16, HPL> pw(ws, l);
   float accw[NH][2];        // window path: channels 2l, 2l+1 of every head
 #pragma unroll
   for (int hh = 0; hh < NH; ++hh) accw[hh][0] = accw[hh][1] = 0.f;
-
-  WaveScratch<NB16, HPL>& ws = smem.w[w];
-  const size_t qrow = ((size_t)b * p.n_q_heads + (size_t)h * g);
 
   if (!is_window) {
     // ---- zero the operand matrices once (rows of absent heads and the unused term row stay zero)
@@ -219,8 +385,7 @@ __global__ __launch_bounds__(256, 2) void decode_split_kernel(DecodeParams p) {
       for (int i = l; i < nwords; i += 64) z32[i] = 0u;
       if (l < 4) reinterpret_cast<uint32_t*>(ws.zero)[l] = 0u;
     }
-    // ---- q in "compact" layout: lane (gi, j) holds channels 8j..8j+7 of heads gi*HPL + e, pre-scaled
-    float qv[HPL][8];
+    // ---- q in compact layout, pre-scaled
 #pragma unroll
     for (int e = 0; e < HPL; ++e) {
       const int hd = gi * HPL + e;
@@ -229,173 +394,36 @@ __global__ __launch_bounds__(256, 2) void decode_split_kernel(DecodeParams p) {
         const uint32_t rw[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-          qv[e][2 * k] = __uint_as_float(rw[k] << 16) * p.qk_scale_log2;
-          qv[e][2 * k + 1] = __uint_as_float(rw[k] & 0xffff0000u) * p.qk_scale_log2;
+          pw.qv[e][2 * k] = __uint_as_float(rw[k] << 16) * p.qk_scale_log2;
+          pw.qv[e][2 * k + 1] = __uint_as_float(rw[k] & 0xffff0000u) * p.qk_scale_log2;
         }
       } else {
 #pragma unroll
-        for (int k = 0; k < 8; ++k) qv[e][k] = 0.f;
+        for (int k = 0; k < 8; ++k) pw.qv[e][k] = 0.f;
       }
     }
-    // LDS addresses of the A operands: lane (row i = j, k-block gi)
-    const uint8_t* a_ptr = &ws.abuf[j][16 * gi];
-    const uint8_t* p_ptr = &ws.pbuf[j][16 * gi];
     wave_lds_fence();
 
     const int32_t* pt = p.page_table + (size_t)b * p.max_pages;
     const size_t rec_stride = (size_t)p.n_kv_heads * R::bytes;
     const uint8_t* pool_h = p.pool + (size_t)h * R::bytes;
+    auto rec_of = [&](int idx) { return pool_h + (size_t)pt[idx] * rec_stride; };
 
-    PageRegs<NB16> cur{}, nxt{};
+    // two register buffers, alternately loaded one page ahead of the one being processed
+    PageRegs<NB16> bufA{}, bufB{};
     int idx = p0 + w;
-    if (idx < p1) load_page<NB16>(cur, pool_h + (size_t)pt[idx] * rec_stride, l);
-
-    for (; idx < p1; idx += 4) {
-      if (idx + 4 < p1) load_page<NB16>(nxt, pool_h + (size_t)pt[idx + 4] * rec_stride, l);
-
-      // ================= A: integer image of q*s, bias q.z =================
-      float ks[8], kz[8];
-      f16x8_to_f32(cur.ksc, ks);
-      f16x8_to_f32(cur.kzr, kz);
-      float inv_alpha[HPL], bias[HPL];
-#pragma unroll
-      for (int e = 0; e < HPL; ++e) {
-        float qs[8], amax = 0.f, bsum = 0.f;
-#pragma unroll
-        for (int k = 0; k < 8; ++k) {
-          qs[k] = qv[e][k] * ks[k];
-          amax = fmaxf(amax, fabsf(qs[k]));
-          bsum = fmaf(qv[e][k], kz[k], bsum);
-        }
-        amax = fmaxf(row_max(amax), 1e-30f);
-        bias[e] = row_sum(bsum);
-        const float alpha = NLIM / amax;
-        inv_alpha[e] = amax * (1.0f / NLIM);
-        int n[8];
-#pragma unroll
-        for (int k = 0; k < 8; ++k) n[k] = round_to_int(qs[k] * alpha);
-        uint2 tw[TR];
-        split_terms<TR>(n, tw);
-        const int hd = gi * HPL + e;
-#pragma unroll
-        for (int t = 0; t < TR; ++t) *reinterpret_cast<uint2*>(&ws.abuf[hd * RPH + t][8 * j]) = tw[t];
-        if constexpr (NB16 > 0) {
-          *reinterpret_cast<int4*>(&ws.nbuf[hd][8 * j]) = make_int4(n[0], n[1], n[2], n[3]);
-          *reinterpret_cast<int4*>(&ws.nbuf[hd][8 * j + 4]) = make_int4(n[4], n[5], n[6], n[7]);
-        }
+    if (idx < p1) {
+      load_page<NB16>(bufA, rec_of(idx), l);
+      while (true) {
+        if (idx + 4 < p1) load_page<NB16>(bufB, rec_of(idx + 4), l);
+        pw.process(bufA);
+        idx += 4;
+        if (idx >= p1) break;
+        if (idx + 4 < p1) load_page<NB16>(bufA, rec_of(idx + 4), l);
+        pw.process(bufB);
+        idx += 4;
+        if (idx >= p1) break;
       }
-      wave_lds_fence();
-      // ================= B: same integers gathered through the boosted-channel list =================
-      if constexpr (NB16 > 0) {
-#pragma unroll
-        for (int s = 0; s < NB16; ++s) {
-#pragma unroll
-          for (int e = 0; e < HPL; ++e) {
-            const int hd = gi * HPL + e;
-            const uint32_t nn = (uint32_t)ws.nbuf[hd][cur.chv[s]];
-            ws.bbuf[hd * RPH + 0][16 * s + j] = (uint8_t)nn;
-            ws.bbuf[hd * RPH + 1][16 * s + j] = (uint8_t)((nn + 0x80u) >> 8);
-            if constexpr (TR == 3) ws.bbuf[hd * RPH + 2][16 * s + j] = (uint8_t)((nn + 0x8080u) >> 16);
-          }
-        }
-        wave_lds_fence();
-      }
-      // ================= C: logits for 128 tokens x heads on the int8 matrix cores =================
-      const v4i a0 = *reinterpret_cast<const v4i*>(a_ptr);
-      const v4i a1 = *reinterpret_cast<const v4i*>(a_ptr + 64);
-      v4i dq[8];
-#pragma unroll
-      for (int T = 0; T < 8; ++T) {
-        const uint4 ld = cur.kd[T >> 1];
-        const uint32_t w0 = (T & 1) ? ld.z : ld.x, w1 = (T & 1) ? ld.w : ld.y;
-        v4i c = {0, 0, 0, 0};
-        c = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0, unpack16(w0), c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1, unpack16(w1), c, 0, 0, 0);
-        dq[T] = c;
-      }
-      if constexpr (NB16 > 0) {
-#pragma unroll
-        for (int s = 0; s < NB16; ++s) {
-          // tile 4u+kb of the boost plane lives in the lanes of k-block kb: feed A only to that block
-          v4i ab[4];
-#pragma unroll
-          for (int kb = 0; kb < 4; ++kb) {
-            const uint8_t* src = (gi == kb) ? &ws.bbuf[j][16 * s] : ws.zero;
-            ab[kb] = *reinterpret_cast<const v4i*>(src);
-          }
-#pragma unroll
-          for (int u = 0; u < 2; ++u) {
-            const v4i bb = unpack16_x4(u ? cur.kb[s].y : cur.kb[s].x);
-#pragma unroll
-            for (int kb = 0; kb < 4; ++kb)
-              dq[4 * u + kb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ab[kb], bb, dq[4 * u + kb], 0, 0, 0);
-          }
-        }
-      }
-      // ================= D: online softmax; lane (j, gi) owns token 16T + j of heads gi*HPL + e ==========
-      float vs[8], vz[8];
-      f16x8_to_f32(cur.vsc, vs);
-      f16x8_to_f32(cur.vzr, vz);
-      float corr[HPL], inv_beta[HPL];
-#pragma unroll
-      for (int e = 0; e < HPL; ++e) {
-        float x[8], mx = -INFINITY;
-#pragma unroll
-        for (int T = 0; T < 8; ++T) {
-          int nl;
-          if constexpr (TR == 3) nl = dq[T][0] + dq[T][1] * 256 + dq[T][2] * 65536;
-          else nl = dq[T][2 * e] + dq[T][2 * e + 1] * 256;
-          x[T] = fmaf((float)nl, inv_alpha[e], bias[e]);
-          mx = fmaxf(mx, x[T]);
-        }
-        mx = row_max(mx);
-        const float m_new = fmaxf(m_run[e], mx);
-        corr[e] = __builtin_amdgcn_exp2f(m_run[e] - m_new);
-        m_run[e] = m_new;
-        float ps[8], psum = 0.f, zsum = 0.f, pmax = 0.f;
-#pragma unroll
-        for (int T = 0; T < 8; ++T) {
-          const float pT = __builtin_amdgcn_exp2f(x[T] - m_new);
-          psum += pT;
-          zsum = fmaf(pT, vz[T], zsum);
-          ps[T] = pT * vs[T];
-          pmax = fmaxf(pmax, ps[T]);
-        }
-        l_run[e] = fmaf(l_run[e], corr[e], psum);
-        z_run[e] = fmaf(z_run[e], corr[e], zsum);
-        pmax = fmaxf(row_max(pmax), 1e-30f);
-        const float beta = NLIM / pmax;
-        inv_beta[e] = pmax * (1.0f / NLIM);
-        int n[8];
-#pragma unroll
-        for (int T = 0; T < 8; ++T) n[T] = (int)fmaf(ps[T], beta, 0.5f);   // ps >= 0: round half up
-        uint2 tw[TR];
-        split_terms<TR>(n, tw);
-        const int hd = gi * HPL + e;
-#pragma unroll
-        for (int t = 0; t < TR; ++t) *reinterpret_cast<uint2*>(&ws.pbuf[hd * RPH + t][8 * j]) = tw[t];
-      }
-      wave_lds_fence();
-      // ================= E: weighted Value sum on the int8 matrix cores =================
-      const v4i pa0 = *reinterpret_cast<const v4i*>(p_ptr);
-      const v4i pa1 = *reinterpret_cast<const v4i*>(p_ptr + 64);
-#pragma unroll
-      for (int Td = 0; Td < 8; ++Td) {
-        const uint4 ld = cur.vd[Td >> 1];
-        const uint32_t w0 = (Td & 1) ? ld.z : ld.x, w1 = (Td & 1) ? ld.w : ld.y;
-        v4i c = {0, 0, 0, 0};
-        c = __builtin_amdgcn_mfma_i32_16x16x64_i8(pa0, unpack16(w0), c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_i32_16x16x64_i8(pa1, unpack16(w1), c, 0, 0, 0);
-#pragma unroll
-        for (int e = 0; e < HPL; ++e) {
-          int ne;
-          if constexpr (TR == 3) ne = c[0] + c[1] * 256 + c[2] * 65536;
-          else ne = c[2 * e] + c[2 * e + 1] * 256;
-          acc[e][Td] = fmaf(acc[e][Td], corr[e], (float)ne * inv_beta[e]);
-        }
-      }
-      wave_lds_fence();   // the next page overwrites abuf/pbuf
-      cur = nxt;
     }
   } else {
     // ================= residual window: bf16 rows, 32 tokens per wavefront =================
@@ -429,9 +457,9 @@ __global__ __launch_bounds__(256, 2) void decode_split_kernel(DecodeParams p) {
 #pragma unroll
       for (int e = 0; e < HPL; ++e) {
         const float mx = row_max(fmaxf(x[e][0], x[e][1]));
-        m_run[e] = mx;
+        pw.m_run[e] = mx;
         const float pa = __builtin_amdgcn_exp2f(x[e][0] - mx), pb = __builtin_amdgcn_exp2f(x[e][1] - mx);
-        l_run[e] = pa + pb;
+        pw.l_run[e] = pa + pb;
         ws.pw[j][gi * HPL + e] = pa;
         ws.pw[16 + j][gi * HPL + e] = pb;
       }
@@ -453,7 +481,7 @@ __global__ __launch_bounds__(256, 2) void decode_split_kernel(DecodeParams p) {
   // ================= merge the four wavefronts, write the partial =================
   float lsum[HPL], zsum[HPL];
 #pragma unroll
-  for (int e = 0; e < HPL; ++e) { lsum[e] = row_sum(l_run[e]); zsum[e] = row_sum(z_run[e]); }
+  for (int e = 0; e < HPL; ++e) { lsum[e] = row_sum(pw.l_run[e]); zsum[e] = row_sum(pw.z_run[e]); }
   __syncthreads();   // every wavefront is done with its scratch
   MergeScratch<HPL>& mg = smem.mg;
   if (!is_window) {
@@ -461,8 +489,8 @@ __global__ __launch_bounds__(256, 2) void decode_split_kernel(DecodeParams p) {
     for (int e = 0; e < HPL; ++e) {
       const int hd = gi * HPL + e;
 #pragma unroll
-      for (int Td = 0; Td < 8; ++Td) mg.acc[w][hd][16 * Td + j] = acc[e][Td] + zsum[e];
-      if (j == 0) { mg.m[w][hd] = m_run[e]; mg.l[w][hd] = lsum[e]; }
+      for (int Td = 0; Td < 8; ++Td) mg.acc[w][hd][16 * Td + j] = pw.acc[e][Td] + zsum[e];
+      if (j == 0) { mg.m[w][hd] = pw.m_run[e]; mg.l[w][hd] = lsum[e]; }
     }
   } else {
 #pragma unroll
@@ -472,7 +500,7 @@ __global__ __launch_bounds__(256, 2) void decode_split_kernel(DecodeParams p) {
     }
 #pragma unroll
     for (int e = 0; e < HPL; ++e)
-      if (j == 0) { mg.m[w][gi * HPL + e] = m_run[e]; mg.l[w][gi * HPL + e] = lsum[e]; }
+      if (j == 0) { mg.m[w][gi * HPL + e] = pw.m_run[e]; mg.l[w][gi * HPL + e] = lsum[e]; }
   }
   __syncthreads();
   float* out = p.ws + (((size_t)b * p.n_kv_heads + h) * n_slots + slot) * (size_t)g * WS_STRIDE;
