@@ -247,7 +247,7 @@ def main():
             "workload": f"{w.name}: batch {B}, {w.n_q_heads}q/{hkv}kv heads, head_dim 128, context {w.context} "
                         f"({n_pages0} pages + 128-token bf16 window at the first timed step), n_boost {w.n_boost}, "
                         f"step = append_token + decode_attention",
-            "n_splits": ns, "pages_per_split": pps, "cache_copies": n_copies, "record_bytes": rec_bytes,
+            "n_splits": ns, "min_pages_per_split": pps, "cache_copies": n_copies, "record_bytes": rec_bytes,
             "payload_bytes_per_page": payload, "distinct_source_sequences": nsrc,
         },
         "pct_of_hbm_peak": round(100.0 * gbps / HBM_PEAK_GBPS, 2),

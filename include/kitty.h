@@ -67,10 +67,12 @@ size_t kitty_page_bytes(const kitty_layout* layout /*host*/);
 size_t kitty_page_payload_bytes(const kitty_layout* layout /*host*/);
 
 /* Split plan used by the decode calls.  n_splits_req = 0 picks a plan from the sizes and the
- * GPU's compute-unit count.  On return *n_splits is the number of page ranges per (sequence,
- * kv-head) and *pages_per_split the length of each range.  Host pointers. */
+ * GPU's compute-unit count; otherwise n_splits_req ranges are used.  On return *n_splits is the
+ * number of page ranges per (sequence, kv-head) and *min_pages the fewest pages a range covers:
+ * a sequence with np pages uses min(n_splits, max(1, np / min_pages)) ranges of near-equal
+ * length, and its last range also takes the bf16 window.  Host pointers. */
 int kitty_decode_plan(const kitty_layout* layout, int32_t batch, int32_t max_pages,
-                      int32_t n_splits_req, int32_t* n_splits, int32_t* pages_per_split);
+                      int32_t n_splits_req, int32_t* n_splits, int32_t* min_pages);
 
 /* Device workspace needed by the decode calls for the plan kitty_decode_plan() returns for the
  * same arguments.  0 if the arguments are invalid. */

@@ -51,24 +51,26 @@ int num_compute_units() {
   return cus;
 }
 
-void plan_splits(const kitty_layout* L, int32_t batch, int32_t max_pages, int32_t req, int32_t* n_splits, int32_t* pps) {
-  if (max_pages <= 0) { *n_splits = 0; *pps = 1; return; }
-  int32_t per;
+// n_splits page ranges per (sequence, kv-head); a range never covers fewer than min_pages pages
+// unless the sequence has fewer (see active_splits in the kernels).
+void plan_splits(const kitty_layout* L, int32_t batch, int32_t max_pages, int32_t req, int32_t* n_splits, int32_t* min_pages) {
+  int32_t ns, mp;
   if (req > 0) {
-    per = (max_pages + req - 1) / req;
+    ns = req;
+    mp = 1;
   } else {
-    // aim at several workgroups per compute unit; a wavefront should see at least two pages
+    // fill the chip once: two workgroups fit on a compute unit
     const int64_t pairs = (int64_t)batch * L->n_kv_heads;
-    const int64_t target = (int64_t)num_compute_units() * 8;
-    int64_t want = (target + pairs - 1) / pairs;          // splits per pair
-    if (want < 1) want = 1;
-    per = (int32_t)((max_pages + want - 1) / want);
-    if (per < 8) per = 8;
+    const int64_t slots = (int64_t)num_compute_units() * 2;
+    int64_t want = (slots + pairs - 1) / pairs;           // one resident round: each workgroup streams a long range
+    mp = 8;                                               // a wavefront should see at least two pages
+    if (want > max_pages / mp) want = max_pages / mp;
+    ns = (int32_t)want;
   }
-  if (per < 1) per = 1;
-  if (per > max_pages) per = max_pages;
-  *pps = per;
-  *n_splits = (max_pages + per - 1) / per;
+  if (ns > max_pages) ns = max_pages;
+  if (ns < 1) ns = 1;
+  *n_splits = ns;
+  *min_pages = mp;
 }
 
 template <typename F>
@@ -113,7 +115,7 @@ int fill_decode_params(const kitty_layout* L, const kitty_cache* C, int32_t n_sp
   P->n_kv_heads = L->n_kv_heads;
   P->gqa = L->n_q_heads / L->n_kv_heads;
   P->n_splits = ns;
-  P->pages_per_split = pps;
+  P->min_pages = pps;
   P->has_window = L->residual_window > 0 ? 1 : 0;
   P->out_dtype = 0;
   return KITTY_OK;
@@ -146,9 +148,7 @@ size_t kitty_decode_workspace_bytes(const kitty_layout* L, int32_t batch, int32_
   if (check_layout(L) != KITTY_OK || batch <= 0 || max_pages < 0 || n_splits_req < 0) return 0;
   int32_t ns, pps;
   plan_splits(L, batch, max_pages, n_splits_req, &ns, &pps);
-  const size_t slots = (size_t)ns + (L->residual_window > 0 ? 1 : 0);
-  const size_t bytes = (size_t)batch * L->n_q_heads * slots * WS_STRIDE * sizeof(float);
-  return bytes ? bytes : 16;
+  return (size_t)batch * L->n_q_heads * (size_t)ns * WS_STRIDE * sizeof(float);
 }
 
 int kitty_quantize_pages(const kitty_layout* L, const void* k_src, const void* v_src, int64_t page_stride,
@@ -230,10 +230,8 @@ int kitty_decode_split(const kitty_layout* L, const kitty_cache* C, const void* 
   if (L->n_kv_heads > 65535 || C->batch > 65535) return KITTY_ERR_UNSUPPORTED;
   P.q = static_cast<const uint16_t*>(q);
   P.qk_scale_log2 = sm_scale * 1.44269504088896340736f;
-  const int n_slots = P.n_splits + P.has_window;
-  if (n_slots == 0) return KITTY_OK;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  const dim3 grid(n_slots, L->n_kv_heads, C->batch);
+  const dim3 grid(P.n_splits, L->n_kv_heads, C->batch);
   const bool wide = P.gqa == 8;
   return dispatch_nb16(L->n_boost / 16, [&](auto nb) {
     constexpr int NB = decltype(nb)::value;

@@ -34,8 +34,16 @@ struct DecodeParams {
   void* out;
   float qk_scale_log2;   // sm_scale * log2(e)
   int32_t batch, max_pages, n_q_heads, n_kv_heads, gqa;
-  int32_t n_splits, pages_per_split, has_window, out_dtype;
+  int32_t n_splits, min_pages, has_window, out_dtype;
 };
+
+// Page ranges of one sequence: with np pages and a window of r rows, the sequence uses
+// Sb = min(n_splits, max(1, np / min_pages)) ranges (one if it only has a window, none if it is empty);
+// range s covers pages [s*np/Sb, (s+1)*np/Sb) and the last range also takes the window.
+__device__ __forceinline__ int active_splits(int np, int r, int n_splits, int min_pages) {
+  if (np <= 0) return r > 0 ? 1 : 0;
+  return min(n_splits, max(1, np / min_pages));
+}
 
 template <int NB16>
 struct PageRegs {
@@ -74,6 +82,16 @@ __device__ __forceinline__ v4i unpack16(uint32_t w) {
   r.x = (int)(w & 0x03030303u);
   r.y = (int)((w >> 2) & 0x03030303u);
   r.z = (int)((w >> 4) & 0x03030303u);
+  r.w = (int)((w >> 6) & 0x03030303u);
+  return r;
+}
+// cheaper variant: elements 4..7 come out multiplied by 4 and elements 8..11 by 16 (mask only, no
+// shift); the other operand carries the inverse weights
+__device__ __forceinline__ v4i unpack16_w(uint32_t w) {
+  v4i r;
+  r.x = (int)(w & 0x03030303u);
+  r.y = (int)(w & 0x0c0c0c0cu);
+  r.z = (int)(w & 0x30303030u);
   r.w = (int)((w >> 6) & 0x03030303u);
   return r;
 }
@@ -121,6 +139,12 @@ __device__ __forceinline__ void split_terms(const uint32_t (&u)[8], uint2 (&w)[T
   }
 }
 
+// t0 + 256 t1 + 65536 t2 by two 24-bit multiply-adds (every intermediate stays below 2^23)
+__device__ __forceinline__ int join_terms(int t0, int t1, int t2) {
+  return __mul24(__mul24(t2, 256) + t1, 256) + t0;
+}
+__device__ __forceinline__ int join_terms(int t0, int t1) { return __mul24(t1, 256) + t0; }
+
 __device__ __forceinline__ void f16x8_to_f32(const uint4& v, float (&f)[8]) {
   const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
@@ -152,9 +176,9 @@ struct WaveScratch {
 
 template <int HPL>
 struct MergeScratch {
-  float acc[4][4 * HPL][D];
-  float m[4][4 * HPL];
-  float l[4][4 * HPL];
+  float acc[8][4 * HPL][D];   // 4 wavefronts x {pages, window}
+  float m[8][4 * HPL];
+  float l[8][4 * HPL];
 };
 
 template <int NB16, int HPL>
@@ -167,10 +191,17 @@ union __attribute__((aligned(16))) DecodeSmem {
 // Lane l = (j = l & 15, gi = l >> 4).  In the "compact" role the lane owns channels 8j..8j+7 (K side)
 // or positions 8j..8j+7 (V side) of heads gi*HPL + e; in the matrix role it is row/column j of
 // k-block gi.  Both roles put head gi*HPL + e in lane group gi, so no cross-group traffic is needed.
+//
+// With three byte terms (HPL == 1) the code planes are unpacked with masks only (unpack16_w), which
+// leaves elements 4..7 of a word multiplied by 4 and elements 8..11 by 16.  The compact lane owns
+// elements 8*(j&1)..8*(j&1)+7, i.e. its first four values have weight wA and its last four wB with
+// (wA, wB) = (1, 4) for even j and (16, 1) for odd j; it divides its values by that weight before
+// taking the integer image, and keeps sums and maxima of unweighted values by recombining two halves.
 template <int NB16, int HPL>
 struct PageWorker {
   static constexpr int TR = HPL == 1 ? 3 : 2;     // byte terms per value
   static constexpr int RPH = 4 / HPL;             // matrix rows per head
+  static constexpr bool WEIGHTED = HPL == 1;      // mask-only unpack (needs the precision of three terms)
   static constexpr float NLIM = TR == 3 ? 1048000.0f : 32000.0f;   // bound of the integer images
 
   WaveScratch<NB16, HPL>& ws;
@@ -178,7 +209,8 @@ struct PageWorker {
   const uint8_t* a_ptr;      // A operand of the logits: row j, k-block gi
   const uint8_t* p_ptr;      // A operand of the Value sum
   const uint8_t* b_ptr[4];   // boost rows for tile kb (zeros unless gi == kb)
-  float qv[HPL][8];          // q * sm_scale * log2(e), compact layout
+  float wA, wB, oA, oB;      // weights of the lane's two halves and their log2
+  float qv[HPL][8];          // q * sm_scale * log2(e) (divided by the weight if WEIGHTED), compact layout
   float m_run[HPL], l_run[HPL], z_run[HPL];
   float acc[HPL][8];         // channel 16*Td + j
 
@@ -188,6 +220,11 @@ struct PageWorker {
     p_ptr = &ws.pbuf[j][16 * gi];
 #pragma unroll
     for (int kb = 0; kb < 4; ++kb) b_ptr[kb] = (gi == kb) ? &ws.bbuf[j][0] : ws.zero;
+    const bool odd = j & 1;
+    wA = WEIGHTED ? (odd ? 16.f : 1.f) : 1.f;
+    wB = WEIGHTED ? (odd ? 1.f : 4.f) : 1.f;
+    oA = WEIGHTED ? (odd ? 4.f : 0.f) : 0.f;
+    oB = WEIGHTED ? (odd ? 0.f : 2.f) : 0.f;
 #pragma unroll
     for (int e = 0; e < HPL; ++e) {
       m_run[e] = -INFINITY; l_run[e] = 0.f; z_run[e] = 0.f;
@@ -195,6 +232,19 @@ struct PageWorker {
       for (int k = 0; k < 8; ++k) acc[e][k] = 0.f;
     }
   }
+
+  // q for head slot e from eight bf16 values (or zeros), scaled by sm_scale*log2(e)
+  __device__ __forceinline__ void set_q(int e, const uint4& raw, float scale, bool live) {
+    const uint32_t rw[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const float inv_w = 1.0f / (2 * k < 4 ? wA : wB);
+      qv[e][2 * k] = live ? __uint_as_float(rw[k] << 16) * scale * inv_w : 0.f;
+      qv[e][2 * k + 1] = live ? __uint_as_float(rw[k] & 0xffff0000u) * scale * inv_w : 0.f;
+    }
+  }
+
+  __device__ __forceinline__ v4i unpack(uint32_t w) const { return WEIGHTED ? unpack16_w(w) : unpack16(w); }
 
   __device__ __forceinline__ void process(const PageRegs<NB16>& pg) {
     // ================= A: integer image of q*s, bias q.z =================
@@ -204,16 +254,22 @@ struct PageWorker {
     float inv_alpha[HPL], bias[HPL];
 #pragma unroll
     for (int e = 0; e < HPL; ++e) {
-      float qs[8], amax = 0.f, bsum = 0.f;
+      float qs[8], amaxA = 0.f, amaxB = 0.f, bsA = 0.f, bsB = 0.f;
 #pragma unroll
-      for (int k = 0; k < 8; ++k) {
+      for (int k = 0; k < 4; ++k) {
         qs[k] = qv[e][k] * ks[k];
-        amax = fmaxf(amax, fabsf(qs[k]));
-        bsum = fmaf(qv[e][k], kz[k], bsum);
+        qs[k + 4] = qv[e][k + 4] * ks[k + 4];
+        amaxA = fmaxf(amaxA, fabsf(qs[k]));
+        amaxB = fmaxf(amaxB, fabsf(qs[k + 4]));
+        bsA = fmaf(qv[e][k], kz[k], bsA);
+        bsB = fmaf(qv[e][k + 4], kz[k + 4], bsB);
       }
+      float amax, bsum;
+      if constexpr (WEIGHTED) { amax = fmaxf(amaxA * wA, amaxB * wB); bsum = fmaf(bsA, wA, bsB * wB); }
+      else { amax = fmaxf(amaxA, amaxB); bsum = bsA + bsB; }
       amax = fmaxf(row_max(amax), 1e-30f);
       bias[e] = row_sum(bsum);
-      const float alpha = NLIM / amax;
+      const float alpha = NLIM * __builtin_amdgcn_rcpf(amax);
       inv_alpha[e] = amax * (1.0f / NLIM);
       uint32_t u[8];
 #pragma unroll
@@ -233,10 +289,15 @@ struct PageWorker {
     if constexpr (NB16 > 0) {
 #pragma unroll
       for (int s = 0; s < NB16; ++s) {
+        const uint32_t ch = pg.chv[s];
+        // weight the dense plane applies to this channel: 1, 4, 16, 1 for elements 0-3, 4-7, 8-11, 12-15
+        const uint32_t grp = (ch >> 2) & 3u;
+        const uint32_t sh = WEIGHTED ? (grp == 1u ? 2u : (grp == 2u ? 4u : 0u)) : 0u;
 #pragma unroll
         for (int e = 0; e < HPL; ++e) {
           const int hd = gi * HPL + e;
-          const uint32_t nn = ws.nbuf[hd][pg.chv[s]];
+          uint32_t nn = ws.nbuf[hd][ch];
+          if constexpr (WEIGHTED) nn = ((nn - 0x4b400000u) << sh) + 0x4b400000u;   // undo the division: exact multiple
           ws.bbuf[hd * RPH + 0][16 * s + j] = (uint8_t)nn;
           ws.bbuf[hd * RPH + 1][16 * s + j] = (uint8_t)((nn + T1_ADD) >> 8);
           if constexpr (TR == 3) ws.bbuf[hd * RPH + 2][16 * s + j] = (uint8_t)((nn + T2_ADD) >> 16);
@@ -253,8 +314,8 @@ struct PageWorker {
       const uint4 ld = pg.kd[T >> 1];
       const uint32_t w0 = (T & 1) ? ld.z : ld.x, w1 = (T & 1) ? ld.w : ld.y;
       v4i c = {0, 0, 0, 0};
-      c = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0, unpack16(w0), c, 0, 0, 0);
-      c = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1, unpack16(w1), c, 0, 0, 0);
+      c = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0, unpack(w0), c, 0, 0, 0);
+      c = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1, unpack(w1), c, 0, 0, 0);
       dq[T] = c;
     }
     if constexpr (NB16 > 0) {
@@ -284,8 +345,8 @@ struct PageWorker {
 #pragma unroll
       for (int T = 0; T < 8; ++T) {
         int nl;
-        if constexpr (TR == 3) nl = dq[T][0] + dq[T][1] * 256 + dq[T][2] * 65536;
-        else nl = dq[T][2 * e] + dq[T][2 * e + 1] * 256;
+        if constexpr (TR == 3) nl = join_terms(dq[T][0], dq[T][1], dq[T][2]);
+        else nl = join_terms(dq[T][2 * e], dq[T][2 * e + 1]);
         x[T] = fmaf((float)nl, inv_alpha[e], bias[e]);
         mx = fmaxf(mx, x[T]);
       }
@@ -293,19 +354,24 @@ struct PageWorker {
       const float m_new = fmaxf(m_run[e], mx);
       corr[e] = __builtin_amdgcn_exp2f(m_run[e] - m_new);
       m_run[e] = m_new;
-      float ps[8], psum = 0.f, zsum = 0.f, pmax = 0.f;
+      // the weights of the Value-side unpack are taken out of p through the exponent
+      const float mA = m_new + oA, mB = m_new + oB;
+      float ps[8], psA = 0.f, psB = 0.f, zsA = 0.f, zsB = 0.f, pmA = 0.f, pmB = 0.f;
 #pragma unroll
-      for (int T = 0; T < 8; ++T) {
-        const float pT = __builtin_amdgcn_exp2f(x[T] - m_new);
-        psum += pT;
-        zsum = fmaf(pT, vz[T], zsum);
-        ps[T] = pT * vs[T];
-        pmax = fmaxf(pmax, ps[T]);
+      for (int T = 0; T < 4; ++T) {
+        const float pa = __builtin_amdgcn_exp2f(x[T] - mA), pb = __builtin_amdgcn_exp2f(x[T + 4] - mB);
+        psA += pa; psB += pb;
+        zsA = fmaf(pa, vz[T], zsA); zsB = fmaf(pb, vz[T + 4], zsB);
+        ps[T] = pa * vs[T]; ps[T + 4] = pb * vs[T + 4];
+        pmA = fmaxf(pmA, ps[T]); pmB = fmaxf(pmB, ps[T + 4]);
       }
+      float psum, zsum, pmax;
+      if constexpr (WEIGHTED) { psum = fmaf(psA, wA, psB * wB); zsum = fmaf(zsA, wA, zsB * wB); pmax = fmaxf(pmA * wA, pmB * wB); }
+      else { psum = psA + psB; zsum = zsA + zsB; pmax = fmaxf(pmA, pmB); }
       l_run[e] = fmaf(l_run[e], corr[e], psum);
       z_run[e] = fmaf(z_run[e], corr[e], zsum);
       pmax = fmaxf(row_max(pmax), 1e-30f);
-      const float beta = NLIM / pmax;
+      const float beta = NLIM * __builtin_amdgcn_rcpf(pmax);
       inv_beta[e] = pmax * (1.0f / NLIM);
       uint32_t u[8];
 #pragma unroll
@@ -325,13 +391,13 @@ struct PageWorker {
       const uint4 ld = pg.vd[Td >> 1];
       const uint32_t w0 = (Td & 1) ? ld.z : ld.x, w1 = (Td & 1) ? ld.w : ld.y;
       v4i c = {0, 0, 0, 0};
-      c = __builtin_amdgcn_mfma_i32_16x16x64_i8(pa0, unpack16(w0), c, 0, 0, 0);
-      c = __builtin_amdgcn_mfma_i32_16x16x64_i8(pa1, unpack16(w1), c, 0, 0, 0);
+      c = __builtin_amdgcn_mfma_i32_16x16x64_i8(pa0, unpack(w0), c, 0, 0, 0);
+      c = __builtin_amdgcn_mfma_i32_16x16x64_i8(pa1, unpack(w1), c, 0, 0, 0);
 #pragma unroll
       for (int e = 0; e < HPL; ++e) {
         int ne;
-        if constexpr (TR == 3) ne = c[0] + c[1] * 256 + c[2] * 65536;
-        else ne = c[2 * e] + c[2 * e + 1] * 256;
+        if constexpr (TR == 3) ne = join_terms(c[0], c[1], c[2]);
+        else ne = join_terms(c[2 * e], c[2 * e + 1]);
         acc[e][Td] = fmaf(acc[e][Td], corr[e], (float)ne * inv_beta[e]);
       }
     }
@@ -340,8 +406,9 @@ struct PageWorker {
 };
 
 // HPL = query heads per lane: 1 for GQA groups of 1, 2, 4 (three byte terms), 2 for groups of 8
-// (two byte terms).  Grid: x = split slot (n_splits page ranges, then the window), y = kv-head,
-// z = sequence.  Block = 4 wavefronts; wavefront w takes pages p0+w, p0+w+4, ... of the range.
+// (two byte terms).  Grid: x = page range (see active_splits), y = kv-head, z = sequence.
+// Block = 4 wavefronts; wavefront w takes pages p0+w, p0+w+4, ... of the range and, in the last
+// range of a sequence, 32 rows of the bf16 window.
 template <int NB16, int HPL>
 __global__ __launch_bounds__(256, 2) void decode_split_kernel(DecodeParams p) {
   using R = Rec<NB16>;
@@ -355,28 +422,19 @@ __global__ __launch_bounds__(256, 2) void decode_split_kernel(DecodeParams p) {
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: page ids stay in scalar registers
   const int l = tid & 63, j = l & 15, gi = l >> 4;
   const int g = p.gqa;
-  const int n_slots = p.n_splits + p.has_window;
 
-  const bool is_window = slot >= p.n_splits;
-  int p0 = 0, p1 = 0, r = 0;
-  if (!is_window) {
-    const int np = min(p.n_pages[b], p.max_pages);
-    p0 = slot * p.pages_per_split;
-    p1 = min(p0 + p.pages_per_split, np);
-    if (p0 >= p1) return;
-  } else {
-    r = min(p.n_resid[b], G);
-    if (r <= 0) return;
-  }
+  const int np = min(p.n_pages[b], p.max_pages);
+  const int r = p.has_window ? min(p.n_resid[b], G) : 0;
+  const int sb = active_splits(np, r, p.n_splits, p.min_pages);
+  if (slot >= sb) return;
+  const int p0 = (int)((long long)slot * np / sb), p1 = (int)((long long)(slot + 1) * np / sb);
+  const bool with_window = slot == sb - 1 && r > 0;
 
   WaveScratch<NB16, HPL>& ws = smem.w[w];
   const size_t qrow = ((size_t)b * p.n_q_heads + (size_t)h * g);
   PageWorker<NB16, HPL> pw(ws, l);
-  float accw[NH][2];        // window path: channels 2l, 2l+1 of every head
-#pragma unroll
-  for (int hh = 0; hh < NH; ++hh) accw[hh][0] = accw[hh][1] = 0.f;
 
-  if (!is_window) {
+  if (p0 < p1) {
     // ---- zero the operand matrices once (rows of absent heads and the unused term row stay zero)
     {
       uint32_t* z32 = reinterpret_cast<uint32_t*>(&ws.abuf[0][0]);
@@ -385,22 +443,12 @@ __global__ __launch_bounds__(256, 2) void decode_split_kernel(DecodeParams p) {
       for (int i = l; i < nwords; i += 64) z32[i] = 0u;
       if (l < 4) reinterpret_cast<uint32_t*>(ws.zero)[l] = 0u;
     }
-    // ---- q in compact layout, pre-scaled
 #pragma unroll
     for (int e = 0; e < HPL; ++e) {
       const int hd = gi * HPL + e;
-      if (hd < g) {
-        const uint4 raw = *reinterpret_cast<const uint4*>(p.q + (qrow + hd) * D + 8 * j);
-        const uint32_t rw[4] = {raw.x, raw.y, raw.z, raw.w};
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          pw.qv[e][2 * k] = __uint_as_float(rw[k] << 16) * p.qk_scale_log2;
-          pw.qv[e][2 * k + 1] = __uint_as_float(rw[k] & 0xffff0000u) * p.qk_scale_log2;
-        }
-      } else {
-#pragma unroll
-        for (int k = 0; k < 8; ++k) pw.qv[e][k] = 0.f;
-      }
+      const bool live = hd < g;
+      const uint4 raw = live ? *reinterpret_cast<const uint4*>(p.q + (qrow + hd) * D + 8 * j) : make_uint4(0, 0, 0, 0);
+      pw.set_q(e, raw, p.qk_scale_log2, live);
     }
     wave_lds_fence();
 
@@ -425,92 +473,94 @@ __global__ __launch_bounds__(256, 2) void decode_split_kernel(DecodeParams p) {
         if (idx >= p1) break;
       }
     }
-  } else {
-    // ================= residual window: bf16 rows, 32 tokens per wavefront =================
-    const int t0 = 32 * w;
-    if (t0 < r) {
-      const uint16_t* wk = p.resid_k + ((size_t)b * p.n_kv_heads + h) * (size_t)(G * D);
-      const uint16_t* wv = p.resid_v + ((size_t)b * p.n_kv_heads + h) * (size_t)(G * D);
-      // A operand: query rows; row hd*RPH carries head hd, the other rows are zero
-      const int arow_head = j / RPH;
-      const bool arow_live = (j % RPH) == 0 && arow_head < g;
-      v8bf aq[4];
+  }
+
+  // ================= residual window: bf16 rows, 32 tokens per wavefront =================
+  float accw[NH][2];        // channels 2l, 2l+1 of every head
+  float mw[HPL], lw[HPL];
+#pragma unroll
+  for (int hh = 0; hh < NH; ++hh) accw[hh][0] = accw[hh][1] = 0.f;
+#pragma unroll
+  for (int e = 0; e < HPL; ++e) { mw[e] = -INFINITY; lw[e] = 0.f; }
+  const int t0 = 32 * w;
+  if (with_window && t0 < r) {
+    const uint16_t* wk = p.resid_k + ((size_t)b * p.n_kv_heads + h) * (size_t)(G * D);
+    const uint16_t* wv = p.resid_v + ((size_t)b * p.n_kv_heads + h) * (size_t)(G * D);
+    // A operand: query rows; row hd*RPH carries head hd, the other rows are zero
+    const int arow_head = j / RPH;
+    const bool arow_live = (j % RPH) == 0 && arow_head < g;
+    v8bf aq[4];
+#pragma unroll
+    for (int mm = 0; mm < 4; ++mm) {
+      uint4 raw = make_uint4(0, 0, 0, 0);
+      if (arow_live) raw = *reinterpret_cast<const uint4*>(p.q + (qrow + arow_head) * D + 32 * mm + 8 * gi);
+      aq[mm] = __builtin_bit_cast(v8bf, raw);
+    }
+    float x[HPL][2];
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt) {
+      const int t = t0 + 16 * tt + j;
+      v4f c = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int mm = 0; mm < 4; ++mm) {
-        uint4 raw = make_uint4(0, 0, 0, 0);
-        if (arow_live) raw = *reinterpret_cast<const uint4*>(p.q + (qrow + arow_head) * D + 32 * mm + 8 * gi);
-        aq[mm] = __builtin_bit_cast(v8bf, raw);
-      }
-      float x[HPL][2];
-#pragma unroll
-      for (int tt = 0; tt < 2; ++tt) {
-        const int t = t0 + 16 * tt + j;
-        v4f c = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int mm = 0; mm < 4; ++mm) {
-          const uint4 raw = *reinterpret_cast<const uint4*>(wk + (size_t)t * D + 32 * mm + 8 * gi);
-          c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aq[mm], __builtin_bit_cast(v8bf, raw), c, 0, 0, 0);
-        }
-#pragma unroll
-        for (int e = 0; e < HPL; ++e) x[e][tt] = t < r ? c[e * RPH] * p.qk_scale_log2 : -INFINITY;
+        const uint4 raw = *reinterpret_cast<const uint4*>(wk + (size_t)t * D + 32 * mm + 8 * gi);
+        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aq[mm], __builtin_bit_cast(v8bf, raw), c, 0, 0, 0);
       }
 #pragma unroll
-      for (int e = 0; e < HPL; ++e) {
-        const float mx = row_max(fmaxf(x[e][0], x[e][1]));
-        pw.m_run[e] = mx;
-        const float pa = __builtin_amdgcn_exp2f(x[e][0] - mx), pb = __builtin_amdgcn_exp2f(x[e][1] - mx);
-        pw.l_run[e] = pa + pb;
-        ws.pw[j][gi * HPL + e] = pa;
-        ws.pw[16 + j][gi * HPL + e] = pb;
-      }
-      wave_lds_fence();
-      const int nt = min(32, r - t0);
-      for (int t = 0; t < nt; ++t) {
-        const uint32_t two = *reinterpret_cast<const uint32_t*>(wv + (size_t)(t0 + t) * D + 2 * l);
-        const float v0 = __uint_as_float(two << 16), v1 = __uint_as_float(two & 0xffff0000u);
+      for (int e = 0; e < HPL; ++e) x[e][tt] = t < r ? c[e * RPH] * p.qk_scale_log2 : -INFINITY;
+    }
 #pragma unroll
-        for (int hh = 0; hh < NH; ++hh) {
-          const float ph = ws.pw[t][hh];
-          accw[hh][0] = fmaf(ph, v0, accw[hh][0]);
-          accw[hh][1] = fmaf(ph, v1, accw[hh][1]);
-        }
+    for (int e = 0; e < HPL; ++e) {
+      const float mx = row_max(fmaxf(x[e][0], x[e][1]));
+      mw[e] = mx;
+      const float pa = __builtin_amdgcn_exp2f(x[e][0] - mx), pb = __builtin_amdgcn_exp2f(x[e][1] - mx);
+      lw[e] = pa + pb;
+      ws.pw[j][gi * HPL + e] = pa;
+      ws.pw[16 + j][gi * HPL + e] = pb;
+    }
+    wave_lds_fence();
+    const int nt = min(32, r - t0);
+    for (int t = 0; t < nt; ++t) {
+      const uint32_t two = *reinterpret_cast<const uint32_t*>(wv + (size_t)(t0 + t) * D + 2 * l);
+      const float v0 = __uint_as_float(two << 16), v1 = __uint_as_float(two & 0xffff0000u);
+#pragma unroll
+      for (int hh = 0; hh < NH; ++hh) {
+        const float ph = ws.pw[t][hh];
+        accw[hh][0] = fmaf(ph, v0, accw[hh][0]);
+        accw[hh][1] = fmaf(ph, v1, accw[hh][1]);
       }
     }
   }
 
-  // ================= merge the four wavefronts, write the partial =================
-  float lsum[HPL], zsum[HPL];
+  // ================= merge the eight partials (4 wavefronts x {pages, window}), write the result ===========
+  float lsum[HPL], zsum[HPL], lwsum[HPL];
 #pragma unroll
-  for (int e = 0; e < HPL; ++e) { lsum[e] = row_sum(pw.l_run[e]); zsum[e] = row_sum(pw.z_run[e]); }
+  for (int e = 0; e < HPL; ++e) { lsum[e] = row_sum(pw.l_run[e]); zsum[e] = row_sum(pw.z_run[e]); lwsum[e] = row_sum(lw[e]); }
   __syncthreads();   // every wavefront is done with its scratch
   MergeScratch<HPL>& mg = smem.mg;
-  if (!is_window) {
 #pragma unroll
-    for (int e = 0; e < HPL; ++e) {
-      const int hd = gi * HPL + e;
+  for (int e = 0; e < HPL; ++e) {
+    const int hd = gi * HPL + e;
 #pragma unroll
-      for (int Td = 0; Td < 8; ++Td) mg.acc[w][hd][16 * Td + j] = pw.acc[e][Td] + zsum[e];
-      if (j == 0) { mg.m[w][hd] = pw.m_run[e]; mg.l[w][hd] = lsum[e]; }
-    }
-  } else {
+    for (int Td = 0; Td < 8; ++Td) mg.acc[w][hd][16 * Td + j] = pw.acc[e][Td] + zsum[e];
+    if (j == 0) { mg.m[w][hd] = pw.m_run[e]; mg.l[w][hd] = lsum[e]; mg.m[4 + w][hd] = mw[e]; mg.l[4 + w][hd] = lwsum[e]; }
+  }
 #pragma unroll
-    for (int hh = 0; hh < NH; ++hh) {
-      mg.acc[w][hh][2 * l] = accw[hh][0];
-      mg.acc[w][hh][2 * l + 1] = accw[hh][1];
-    }
-#pragma unroll
-    for (int e = 0; e < HPL; ++e)
-      if (j == 0) { mg.m[w][gi * HPL + e] = pw.m_run[e]; mg.l[w][gi * HPL + e] = lsum[e]; }
+  for (int hh = 0; hh < NH; ++hh) {
+    mg.acc[4 + w][hh][2 * l] = accw[hh][0];
+    mg.acc[4 + w][hh][2 * l + 1] = accw[hh][1];
   }
   __syncthreads();
-  float* out = p.ws + (((size_t)b * p.n_kv_heads + h) * n_slots + slot) * (size_t)g * WS_STRIDE;
+  float* out = p.ws + (((size_t)b * p.n_kv_heads + h) * p.n_splits + slot) * (size_t)g * WS_STRIDE;
   for (int o = tid; o < g * D; o += 256) {
     const int hd = o >> 7, d = o & 127;
-    float M = fmaxf(fmaxf(mg.m[0][hd], mg.m[1][hd]), fmaxf(mg.m[2][hd], mg.m[3][hd]));
+    float M = -INFINITY;
+#pragma unroll
+    for (int ww = 0; ww < 8; ++ww) M = fmaxf(M, mg.m[ww][hd]);
     float a = 0.f, L = 0.f;
 #pragma unroll
-    for (int ww = 0; ww < 4; ++ww) {
-      const float f = __builtin_amdgcn_exp2f(mg.m[ww][hd] - M);   // exp2(-inf) = 0 for idle wavefronts
+    for (int ww = 0; ww < 8; ++ww) {
+      const float f = __builtin_amdgcn_exp2f(mg.m[ww][hd] - M);   // exp2(-inf) = 0 for idle partials
       a = fmaf(mg.acc[ww][hd][d], f, a);
       L = fmaf(mg.l[ww][hd], f, L);
     }
@@ -523,24 +573,18 @@ __global__ __launch_bounds__(256, 2) void decode_split_kernel(DecodeParams p) {
 __global__ __launch_bounds__(128) void decode_merge_kernel(DecodeParams p) {
   const int hq = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
   const int g = p.gqa, h = hq / g, hd = hq % g;
-  const int n_slots = p.n_splits + p.has_window;
   const int np = min(p.n_pages[b], p.max_pages);
-  const int r = p.has_window ? p.n_resid[b] : 0;
-  const float* base = p.ws + (((size_t)b * p.n_kv_heads + h) * n_slots) * (size_t)g * WS_STRIDE + (size_t)hd * WS_STRIDE;
+  const int r = p.has_window ? min(p.n_resid[b], G) : 0;
+  const int sb = active_splits(np, r, p.n_splits, p.min_pages);
+  const float* base = p.ws + (((size_t)b * p.n_kv_heads + h) * p.n_splits) * (size_t)g * WS_STRIDE + (size_t)hd * WS_STRIDE;
   const size_t slot_stride = (size_t)g * WS_STRIDE;
   float M = -INFINITY;
-  for (int s = 0; s < n_slots; ++s) {
-    const bool valid = s < p.n_splits ? (s * p.pages_per_split < np) : (r > 0);
-    if (valid) M = fmaxf(M, base[s * slot_stride + D]);
-  }
+  for (int s = 0; s < sb; ++s) M = fmaxf(M, base[s * slot_stride + D]);
   float a = 0.f, L = 0.f;
-  for (int s = 0; s < n_slots; ++s) {
-    const bool valid = s < p.n_splits ? (s * p.pages_per_split < np) : (r > 0);
-    if (valid) {
-      const float f = __builtin_amdgcn_exp2f(base[s * slot_stride + D] - M);
-      a = fmaf(base[s * slot_stride + d], f, a);
-      L = fmaf(base[s * slot_stride + D + 1], f, L);
-    }
+  for (int s = 0; s < sb; ++s) {
+    const float f = __builtin_amdgcn_exp2f(base[s * slot_stride + D] - M);
+    a = fmaf(base[s * slot_stride + d], f, a);
+    L = fmaf(base[s * slot_stride + D + 1], f, L);
   }
   const float o = L > 0.f ? a / L : 0.f;
   const size_t oi = ((size_t)b * p.n_q_heads + hq) * D + d;

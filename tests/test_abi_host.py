@@ -49,16 +49,18 @@ def test_unsupported_layouts_are_rejected():
 
 def test_plan_and_workspace():
     lay = kitty.make_layout(32, 8, 16)
-    ns, pps = kitty.kitty_decode_plan(lay, 32, 255, 0)
-    assert ns >= 1 and pps >= 1 and ns * pps >= 255 and (ns - 1) * pps < 255
+    ns, mp = kitty.kitty_decode_plan(lay, 32, 255, 0)
+    assert 1 <= ns <= 255 and mp >= 1 and ns * mp <= 255
+    assert kitty.kitty_decode_workspace_bytes(lay, 32, 255, 0) == 32 * 32 * ns * 130 * 4
     for req in (1, 2, 7, 255, 1000):
-        ns, pps = kitty.kitty_decode_plan(lay, 32, 255, req)
-        assert ns * pps >= 255 and (ns - 1) * pps < 255 and ns <= max(req, 1) or pps == 1
-        assert kitty.kitty_decode_workspace_bytes(lay, 32, 255, req) == 32 * 32 * (ns + 1) * 130 * 4
+        ns, mp = kitty.kitty_decode_plan(lay, 32, 255, req)
+        assert ns == min(req, 255) and mp == 1
+        assert kitty.kitty_decode_workspace_bytes(lay, 32, 255, req) == 32 * 32 * ns * 130 * 4
     lay0 = kitty.make_layout(1, 1, 16, residual_window=0)
-    ns, pps = kitty.kitty_decode_plan(lay0, 1, 8, 4)
-    assert (ns, pps) == (4, 2)
+    assert kitty.kitty_decode_plan(lay0, 1, 8, 4) == (4, 1)
     assert kitty.kitty_decode_workspace_bytes(lay0, 1, 8, 4) == 4 * 130 * 4
+    # a cache with no page table still needs one range for the window
+    assert kitty.kitty_decode_plan(lay, 4, 0, 0)[0] == 1
 
 
 def test_invalid_arguments_return_codes_without_touching_a_gpu():
