@@ -573,18 +573,44 @@ __global__ __launch_bounds__(256, 2) void decode_split_kernel(DecodeParams p) {
 __global__ __launch_bounds__(128) void decode_merge_kernel(DecodeParams p) {
   const int hq = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
   const int g = p.gqa, h = hq / g, hd = hq % g;
-  const int np = min(p.n_pages[b], p.max_pages);
-  const int r = p.has_window ? min(p.n_resid[b], G) : 0;
-  const int sb = active_splits(np, r, p.n_splits, p.min_pages);
   const float* base = p.ws + (((size_t)b * p.n_kv_heads + h) * p.n_splits) * (size_t)g * WS_STRIDE + (size_t)hd * WS_STRIDE;
   const size_t slot_stride = (size_t)g * WS_STRIDE;
-  float M = -INFINITY;
-  for (int s = 0; s < sb; ++s) M = fmaxf(M, base[s * slot_stride + D]);
   float a = 0.f, L = 0.f;
-  for (int s = 0; s < sb; ++s) {
-    const float f = __builtin_amdgcn_exp2f(base[s * slot_stride + D] - M);
-    a = fmaf(base[s * slot_stride + d], f, a);
-    L = fmaf(base[s * slot_stride + D + 1], f, L);
+  if (p.n_splits <= 8) {
+    // few ranges: fetch every slot before the sequence state arrives (one memory round trip), then mask
+    float m[8], lv[8], av[8];
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      const bool in = s < p.n_splits;
+      m[s] = in ? base[s * slot_stride + D] : 0.f;
+      lv[s] = in ? base[s * slot_stride + D + 1] : 0.f;
+      av[s] = in ? base[s * slot_stride + d] : 0.f;
+    }
+    const int np = min(p.n_pages[b], p.max_pages);
+    const int r = p.has_window ? min(p.n_resid[b], G) : 0;
+    const int sb = active_splits(np, r, p.n_splits, p.min_pages);
+    float M = -INFINITY;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) M = s < sb ? fmaxf(M, m[s]) : M;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      if (s < sb) {   // slots beyond sb hold stale bytes: select, never multiply
+        const float f = __builtin_amdgcn_exp2f(m[s] - M);
+        a = fmaf(av[s], f, a);
+        L = fmaf(lv[s], f, L);
+      }
+    }
+  } else {
+    const int np = min(p.n_pages[b], p.max_pages);
+    const int r = p.has_window ? min(p.n_resid[b], G) : 0;
+    const int sb = active_splits(np, r, p.n_splits, p.min_pages);
+    float M = -INFINITY;
+    for (int s = 0; s < sb; ++s) M = fmaxf(M, base[s * slot_stride + D]);
+    for (int s = 0; s < sb; ++s) {
+      const float f = __builtin_amdgcn_exp2f(base[s * slot_stride + D] - M);
+      a = fmaf(base[s * slot_stride + d], f, a);
+      L = fmaf(base[s * slot_stride + D + 1], f, L);
+    }
   }
   const float o = L > 0.f ? a / L : 0.f;
   const size_t oi = ((size_t)b * p.n_q_heads + hq) * D + d;
