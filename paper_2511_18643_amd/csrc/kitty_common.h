@@ -52,10 +52,32 @@ __device__ __forceinline__ uint16_t f32_to_f16_bits(float f) {
 }
 
 // DPP rotate within each row of 16 lanes; all-reduce over the row by four rotate+op steps.
+// Maxima are taken on integers (bit patterns of non-negative floats order like unsigned integers), which
+// keeps the float canonicalisation the compiler attaches to fmaxf out of the reduction.
 template <int N>
-__device__ __forceinline__ float row_ror(float v) {
-  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x120 + N, 0xf, 0xf, false));
+__device__ __forceinline__ int row_ror_i(int v) {
+  return __builtin_amdgcn_update_dpp(v, v, 0x120 + N, 0xf, 0xf, true);
 }
+template <int N>
+__device__ __forceinline__ float row_ror(float v) { return __builtin_bit_cast(float, row_ror_i<N>(__builtin_bit_cast(int, v))); }
+
+__device__ __forceinline__ int row_max_i32(int v) {
+  v = max(v, row_ror_i<8>(v));
+  v = max(v, row_ror_i<4>(v));
+  v = max(v, row_ror_i<2>(v));
+  v = max(v, row_ror_i<1>(v));
+  return v;
+}
+__device__ __forceinline__ uint32_t row_max_u32(uint32_t v) {
+  v = max(v, (uint32_t)row_ror_i<8>((int)v));
+  v = max(v, (uint32_t)row_ror_i<4>((int)v));
+  v = max(v, (uint32_t)row_ror_i<2>((int)v));
+  v = max(v, (uint32_t)row_ror_i<1>((int)v));
+  return v;
+}
+// row maximum of non-negative floats
+__device__ __forceinline__ float row_max_nonneg(float v) { return __uint_as_float(row_max_u32(__float_as_uint(v))); }
+// row maximum of arbitrary finite floats (or -inf)
 __device__ __forceinline__ float row_max(float v) {
   v = fmaxf(v, row_ror<8>(v));
   v = fmaxf(v, row_ror<4>(v));

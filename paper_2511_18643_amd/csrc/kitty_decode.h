@@ -10,6 +10,7 @@
 // The high bits of boosted channels are one more short contraction against the same q*s values
 // gathered through the channel list (the only gather, and it is of q, never of cache bytes).
 #pragma once
+#include <climits>
 #include <cstddef>
 
 #include "kitty_common.h"
@@ -45,35 +46,60 @@ __device__ __forceinline__ int active_splits(int np, int r, int n_splits, int mi
   return min(n_splits, max(1, np / min_pages));
 }
 
+// One page's record as it sits in a lane's registers.  `meta` is the lane's 16 bytes of one of the four
+// fp16 arrays (lane group 0: k_scale, 1: k_zero, 2: v_scale, 3: v_zero; entries 8j..8j+7), exchanged
+// between the lane groups through LDS.
 template <int NB16>
 struct PageRegs {
   uint4 kd[4];
   uint2 kb[NB16 ? NB16 : 1];
-  uint4 ksc, kzr;
   uint32_t chv[NB16 ? NB16 : 1];
   uint4 vd[4];
-  uint4 vsc, vzr;
+  uint4 meta;
 };
 
+// Byte offsets of a lane into a record (32-bit, so loads take the scalar record base + one VGPR offset).
+struct LaneOffsets {
+  uint32_t o16, o8, j, meta;
+};
 template <int NB16>
-__device__ __forceinline__ void load_page(PageRegs<NB16>& r, const uint8_t* __restrict__ rec, int l) {
+__device__ __forceinline__ LaneOffsets lane_offsets(int l) {
   using R = Rec<NB16>;
-  const int j = l & 15;
-  const uint4* kd = reinterpret_cast<const uint4*>(rec + R::kd) + l;
+  const uint32_t j = l & 15, gi = l >> 4;
+  const uint32_t base = gi == 0 ? R::ks : (gi == 1 ? R::kz : (gi == 2 ? R::vs : R::vz));
+  return LaneOffsets{(uint32_t)l * 16u, (uint32_t)l * 8u, j, base + 16u * j};
+}
+
+// The loads of a page are issued in four groups spread over the processing of the previous page.
+template <int NB16, int PART>
+__device__ __forceinline__ void load_part(PageRegs<NB16>& r, const uint8_t* __restrict__ rec, const LaneOffsets& o) {
+  using R = Rec<NB16>;
+  if constexpr (PART == 0) {
+    r.meta = *reinterpret_cast<const uint4*>(rec + o.meta);
+    r.kd[0] = *reinterpret_cast<const uint4*>(rec + R::kd + o.o16);
+    r.kd[1] = *reinterpret_cast<const uint4*>(rec + R::kd + 1024 + o.o16);
+  } else if constexpr (PART == 1) {
+    r.kd[2] = *reinterpret_cast<const uint4*>(rec + R::kd + 2048 + o.o16);
+    r.kd[3] = *reinterpret_cast<const uint4*>(rec + R::kd + 3072 + o.o16);
 #pragma unroll
-  for (int i = 0; i < 4; ++i) r.kd[i] = kd[64 * i];
-#pragma unroll
-  for (int s = 0; s < NB16; ++s) {
-    r.kb[s] = *reinterpret_cast<const uint2*>(rec + R::kb + 512 * s + 8 * l);
-    r.chv[s] = rec[R::ch + 16 * s + j];
+    for (int s = 0; s < NB16; ++s) {
+      r.kb[s] = *reinterpret_cast<const uint2*>(rec + R::kb + 512 * s + o.o8);
+      r.chv[s] = rec[R::ch + 16 * s + o.j];
+    }
+  } else if constexpr (PART == 2) {
+    r.vd[0] = *reinterpret_cast<const uint4*>(rec + R::vd + o.o16);
+    r.vd[1] = *reinterpret_cast<const uint4*>(rec + R::vd + 1024 + o.o16);
+  } else {
+    r.vd[2] = *reinterpret_cast<const uint4*>(rec + R::vd + 2048 + o.o16);
+    r.vd[3] = *reinterpret_cast<const uint4*>(rec + R::vd + 3072 + o.o16);
   }
-  r.ksc = *reinterpret_cast<const uint4*>(rec + R::ks + 16 * j);
-  r.kzr = *reinterpret_cast<const uint4*>(rec + R::kz + 16 * j);
-  const uint4* vd = reinterpret_cast<const uint4*>(rec + R::vd) + l;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) r.vd[i] = vd[64 * i];
-  r.vsc = *reinterpret_cast<const uint4*>(rec + R::vs + 16 * j);
-  r.vzr = *reinterpret_cast<const uint4*>(rec + R::vz + 16 * j);
+}
+template <int NB16>
+__device__ __forceinline__ void load_page(PageRegs<NB16>& r, const uint8_t* __restrict__ rec, const LaneOffsets& o) {
+  load_part<NB16, 0>(r, rec, o);
+  load_part<NB16, 1>(r, rec, o);
+  load_part<NB16, 2>(r, rec, o);
+  load_part<NB16, 3>(r, rec, o);
 }
 
 // sixteen 2-bit elements -> four registers of four int8 each (elements 4v..4v+3 in register v)
@@ -139,11 +165,14 @@ __device__ __forceinline__ void split_terms(const uint32_t (&u)[8], uint2 (&w)[T
   }
 }
 
-// t0 + 256 t1 + 65536 t2 by two 24-bit multiply-adds (every intermediate stays below 2^23)
+// t0 + 256 t1 + 65536 t2 as two shift-adds (v_lshl_add_u32); the empty asm keeps the compiler from
+// re-associating them into two shifts and a three-way add
 __device__ __forceinline__ int join_terms(int t0, int t1, int t2) {
-  return __mul24(__mul24(t2, 256) + t1, 256) + t0;
+  uint32_t hi = ((uint32_t)t2 << 8) + (uint32_t)t1;
+  asm volatile("" : "+v"(hi));
+  return (int)((hi << 8) + (uint32_t)t0);
 }
-__device__ __forceinline__ int join_terms(int t0, int t1) { return __mul24(t1, 256) + t0; }
+__device__ __forceinline__ int join_terms(int t0, int t1) { return (int)(((uint32_t)t1 << 8) + (uint32_t)t0); }
 
 __device__ __forceinline__ void f16x8_to_f32(const uint4& v, float (&f)[8]) {
   const uint32_t w[4] = {v.x, v.y, v.z, v.w};
@@ -171,6 +200,7 @@ struct WaveScratch {
   uint8_t bbuf[16][16 * (NB16 ? NB16 : 1) + 16];  // rows (head, term) x boost slot
   uint8_t pbuf[16][144];                         // rows (head, term) x position
   float pw[32][8];                               // window path: softmax weights [token][head]
+  uint8_t meta[4][256];                          // k_scale, k_zero, v_scale, v_zero of the page being processed
   uint8_t zero[16];
 };
 
@@ -209,13 +239,14 @@ struct PageWorker {
   const uint8_t* a_ptr;      // A operand of the logits: row j, k-block gi
   const uint8_t* p_ptr;      // A operand of the Value sum
   const uint8_t* b_ptr[4];   // boost rows for tile kb (zeros unless gi == kb)
+  LaneOffsets lo;            // byte offsets of the lane into a record
   float wA, wB, oA, oB;      // weights of the lane's two halves and their log2
   float qv[HPL][8];          // q * sm_scale * log2(e) (divided by the weight if WEIGHTED), compact layout
   float m_run[HPL], l_run[HPL], z_run[HPL];
   float acc[HPL][8];         // channel 16*Td + j
 
   __device__ __forceinline__ PageWorker(WaveScratch<NB16, HPL>& ws_, int l)
-      : ws(ws_), j(l & 15), gi(l >> 4) {
+      : ws(ws_), j(l & 15), gi(l >> 4), lo(lane_offsets<NB16>(l)) {
     a_ptr = &ws.abuf[j][16 * gi];
     p_ptr = &ws.pbuf[j][16 * gi];
 #pragma unroll
@@ -246,11 +277,19 @@ struct PageWorker {
 
   __device__ __forceinline__ v4i unpack(uint32_t w) const { return WEIGHTED ? unpack16_w(w) : unpack16(w); }
 
-  __device__ __forceinline__ void process(const PageRegs<NB16>& pg) {
+  // stage a page's fp16 arrays in LDS (each lane group holds one of the four)
+  __device__ __forceinline__ void stage_meta(const PageRegs<NB16>& pg) {
+    *reinterpret_cast<uint4*>(&ws.meta[gi][16 * j]) = pg.meta;
+  }
+
+  // Processes page `pg` (whose fp16 arrays are already staged in LDS) while issuing the loads of the
+  // wavefront's next page into `nx` (record `rec_nx`, or nothing if `has_nx` is false).
+  __device__ __forceinline__ void process(const PageRegs<NB16>& pg, PageRegs<NB16>& nx, const uint8_t* rec_nx, bool has_nx) {
+    if (has_nx) load_part<NB16, 0>(nx, rec_nx, lo);
     // ================= A: integer image of q*s, bias q.z =================
     float ks[8], kz[8];
-    f16x8_to_f32(pg.ksc, ks);
-    f16x8_to_f32(pg.kzr, kz);
+    f16x8_to_f32(*reinterpret_cast<const uint4*>(&ws.meta[0][16 * j]), ks);
+    f16x8_to_f32(*reinterpret_cast<const uint4*>(&ws.meta[1][16 * j]), kz);
     float inv_alpha[HPL], bias[HPL];
 #pragma unroll
     for (int e = 0; e < HPL; ++e) {
@@ -267,7 +306,7 @@ struct PageWorker {
       float amax, bsum;
       if constexpr (WEIGHTED) { amax = fmaxf(amaxA * wA, amaxB * wB); bsum = fmaf(bsA, wA, bsB * wB); }
       else { amax = fmaxf(amaxA, amaxB); bsum = bsA + bsB; }
-      amax = fmaxf(row_max(amax), 1e-30f);
+      amax = fmaxf(row_max_nonneg(amax), 1e-30f);
       bias[e] = row_sum(bsum);
       const float alpha = NLIM * __builtin_amdgcn_rcpf(amax);
       inv_alpha[e] = amax * (1.0f / NLIM);
@@ -285,6 +324,7 @@ struct PageWorker {
       }
     }
     wave_lds_fence();
+    if (has_nx) load_part<NB16, 1>(nx, rec_nx, lo);
     // ================= B: same integers gathered through the boosted-channel list =================
     if constexpr (NB16 > 0) {
 #pragma unroll
@@ -334,32 +374,33 @@ struct PageWorker {
         }
       }
     }
+    if (has_nx) load_part<NB16, 2>(nx, rec_nx, lo);
     // ================= D: online softmax; lane (j, gi) owns token 16T + j of heads gi*HPL + e ==========
     float vs[8], vz[8];
-    f16x8_to_f32(pg.vsc, vs);
-    f16x8_to_f32(pg.vzr, vz);
+    f16x8_to_f32(*reinterpret_cast<const uint4*>(&ws.meta[2][16 * j]), vs);
+    f16x8_to_f32(*reinterpret_cast<const uint4*>(&ws.meta[3][16 * j]), vz);
     float corr[HPL], inv_beta[HPL];
 #pragma unroll
     for (int e = 0; e < HPL; ++e) {
-      float x[8], mx = -INFINITY;
+      // logits are inv_alpha * nl + bias with inv_alpha > 0: take the maximum on the integers
+      int nl[8], mxi = INT_MIN;
 #pragma unroll
       for (int T = 0; T < 8; ++T) {
-        int nl;
-        if constexpr (TR == 3) nl = join_terms(dq[T][0], dq[T][1], dq[T][2]);
-        else nl = join_terms(dq[T][2 * e], dq[T][2 * e + 1]);
-        x[T] = fmaf((float)nl, inv_alpha[e], bias[e]);
-        mx = fmaxf(mx, x[T]);
+        if constexpr (TR == 3) nl[T] = join_terms(dq[T][0], dq[T][1], dq[T][2]);
+        else nl[T] = join_terms(dq[T][2 * e], dq[T][2 * e + 1]);
+        mxi = max(mxi, nl[T]);
       }
-      mx = row_max(mx);
-      const float m_new = fmaxf(m_run[e], mx);
+      mxi = row_max_i32(mxi);
+      const float m_new = fmaxf(m_run[e], fmaf((float)mxi, inv_alpha[e], bias[e]));
       corr[e] = __builtin_amdgcn_exp2f(m_run[e] - m_new);
       m_run[e] = m_new;
       // the weights of the Value-side unpack are taken out of p through the exponent
-      const float mA = m_new + oA, mB = m_new + oB;
+      const float cA = bias[e] - (m_new + oA), cB = bias[e] - (m_new + oB);
       float ps[8], psA = 0.f, psB = 0.f, zsA = 0.f, zsB = 0.f, pmA = 0.f, pmB = 0.f;
 #pragma unroll
       for (int T = 0; T < 4; ++T) {
-        const float pa = __builtin_amdgcn_exp2f(x[T] - mA), pb = __builtin_amdgcn_exp2f(x[T + 4] - mB);
+        const float pa = __builtin_amdgcn_exp2f(fmaf((float)nl[T], inv_alpha[e], cA));
+        const float pb = __builtin_amdgcn_exp2f(fmaf((float)nl[T + 4], inv_alpha[e], cB));
         psA += pa; psB += pb;
         zsA = fmaf(pa, vz[T], zsA); zsB = fmaf(pb, vz[T + 4], zsB);
         ps[T] = pa * vs[T]; ps[T + 4] = pb * vs[T + 4];
@@ -370,7 +411,7 @@ struct PageWorker {
       else { psum = psA + psB; zsum = zsA + zsB; pmax = fmaxf(pmA, pmB); }
       l_run[e] = fmaf(l_run[e], corr[e], psum);
       z_run[e] = fmaf(z_run[e], corr[e], zsum);
-      pmax = fmaxf(row_max(pmax), 1e-30f);
+      pmax = fmaxf(row_max_nonneg(pmax), 1e-30f);
       const float beta = NLIM * __builtin_amdgcn_rcpf(pmax);
       inv_beta[e] = pmax * (1.0f / NLIM);
       uint32_t u[8];
@@ -383,6 +424,7 @@ struct PageWorker {
       for (int t = 0; t < TR; ++t) *reinterpret_cast<uint2*>(&ws.pbuf[hd * RPH + t][8 * j]) = tw[t];
     }
     wave_lds_fence();
+    if (has_nx) load_part<NB16, 3>(nx, rec_nx, lo);
     // ================= E: weighted Value sum on the int8 matrix cores =================
     const v4i pa0 = *reinterpret_cast<const v4i*>(p_ptr);
     const v4i pa1 = *reinterpret_cast<const v4i*>(p_ptr + 64);
@@ -401,7 +443,8 @@ struct PageWorker {
         acc[e][Td] = fmaf(acc[e][Td], corr[e], (float)ne * inv_beta[e]);
       }
     }
-    wave_lds_fence();   // the next page overwrites abuf/pbuf
+    if (has_nx) stage_meta(nx);   // issued a page ago: arrived long since
+    wave_lds_fence();   // the next page overwrites abuf/pbuf and reads the staged arrays
   }
 };
 
@@ -457,18 +500,20 @@ __global__ __launch_bounds__(256, 2) void decode_split_kernel(DecodeParams p) {
     const uint8_t* pool_h = p.pool + (size_t)h * R::bytes;
     auto rec_of = [&](int idx) { return pool_h + (size_t)pt[idx] * rec_stride; };
 
-    // two register buffers, alternately loaded one page ahead of the one being processed
+    // two register buffers; the loads of the next page are issued while the current one is processed
     PageRegs<NB16> bufA{}, bufB{};
     int idx = p0 + w;
     if (idx < p1) {
-      load_page<NB16>(bufA, rec_of(idx), l);
+      load_page<NB16>(bufA, rec_of(idx), pw.lo);
+      pw.stage_meta(bufA);
+      wave_lds_fence();
       while (true) {
-        if (idx + 4 < p1) load_page<NB16>(bufB, rec_of(idx + 4), l);
-        pw.process(bufA);
+        bool has_nx = idx + 4 < p1;
+        pw.process(bufA, bufB, has_nx ? rec_of(idx + 4) : pool_h, has_nx);
         idx += 4;
         if (idx >= p1) break;
-        if (idx + 4 < p1) load_page<NB16>(bufA, rec_of(idx + 4), l);
-        pw.process(bufB);
+        has_nx = idx + 4 < p1;
+        pw.process(bufB, bufA, has_nx ? rec_of(idx + 4) : pool_h, has_nx);
         idx += 4;
         if (idx >= p1) break;
       }
