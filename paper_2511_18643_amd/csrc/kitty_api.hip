@@ -51,6 +51,9 @@ int num_compute_units() {
   return cus;
 }
 
+// Blocks of 8 wavefronts when a range can feed them (>= 4 pages per wavefront), else 4.
+int waves_per_block(int32_t max_pages, int32_t n_splits) { return max_pages / (n_splits > 0 ? n_splits : 1) >= 32 ? 8 : 4; }
+
 // n_splits page ranges per (sequence, kv-head); a range never covers fewer than min_pages pages
 // unless the sequence has fewer (see active_splits in the kernels).
 void plan_splits(const kitty_layout* L, int32_t batch, int32_t max_pages, int32_t req, int32_t* n_splits, int32_t* min_pages) {
@@ -59,11 +62,12 @@ void plan_splits(const kitty_layout* L, int32_t batch, int32_t max_pages, int32_
     ns = req;
     mp = 1;
   } else {
-    // fill the chip once: two workgroups fit on a compute unit
+    // fill the chip once with 8 wavefronts per compute unit (measured: streams best); one range per
+    // (sequence, kv-head) whenever there are enough of them, which also makes the merge pass unnecessary
     const int64_t pairs = (int64_t)batch * L->n_kv_heads;
-    const int64_t slots = (int64_t)num_compute_units() * 2;
-    int64_t want = (slots + pairs - 1) / pairs;           // one resident round: each workgroup streams a long range
-    mp = 8;                                               // a wavefront should see at least two pages
+    const int64_t slots = (int64_t)num_compute_units();
+    int64_t want = (slots + pairs - 1) / pairs;
+    mp = 16;                                              // a wavefront should see at least two pages
     if (want > max_pages / mp) want = max_pages / mp;
     ns = (int32_t)want;
   }
@@ -118,6 +122,7 @@ int fill_decode_params(const kitty_layout* L, const kitty_cache* C, int32_t n_sp
   P->min_pages = pps;
   P->has_window = L->residual_window > 0 ? 1 : 0;
   P->out_dtype = 0;
+  P->direct_out = 0;
   return KITTY_OK;
 }
 
@@ -221,8 +226,10 @@ int kitty_append_token(const kitty_layout* L, const kitty_cache* C, const void* 
   });
 }
 
-int kitty_decode_split(const kitty_layout* L, const kitty_cache* C, const void* q, float sm_scale, int32_t n_splits,
-                       void* workspace, size_t workspace_bytes, void* hip_stream) {
+namespace {
+// Launches the streaming kernel.  With `out` non-null and a one-range plan the kernel stores the result itself.
+int launch_split(const kitty_layout* L, const kitty_cache* C, const void* q, float sm_scale, int32_t n_splits,
+                 void* workspace, size_t workspace_bytes, void* out, int32_t out_dtype, void* hip_stream, bool* merged) {
   DecodeParams P;
   int rc = fill_decode_params(L, C, n_splits, workspace, workspace_bytes, &P);
   if (rc) return rc;
@@ -230,15 +237,31 @@ int kitty_decode_split(const kitty_layout* L, const kitty_cache* C, const void* 
   if (L->n_kv_heads > 65535 || C->batch > 65535) return KITTY_ERR_UNSUPPORTED;
   P.q = static_cast<const uint16_t*>(q);
   P.qk_scale_log2 = sm_scale * 1.44269504088896340736f;
+  P.direct_out = (out && P.n_splits == 1) ? 1 : 0;
+  P.out = out;
+  P.out_dtype = out_dtype;
+  if (merged) *merged = P.direct_out != 0;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   const dim3 grid(P.n_splits, L->n_kv_heads, C->batch);
   const bool wide = P.gqa == 8;
+  const bool big = waves_per_block(C->max_pages, P.n_splits) == 8;
   return dispatch_nb16(L->n_boost / 16, [&](auto nb) {
     constexpr int NB = decltype(nb)::value;
-    if (wide) hipLaunchKernelGGL((decode_split_kernel<NB, 2>), grid, dim3(256), 0, st, P);
-    else hipLaunchKernelGGL((decode_split_kernel<NB, 1>), grid, dim3(256), 0, st, P);
+    if (wide) {
+      if (big) hipLaunchKernelGGL((decode_split_kernel<NB, 2, 8>), grid, dim3(512), 0, st, P);
+      else hipLaunchKernelGGL((decode_split_kernel<NB, 2, 4>), grid, dim3(256), 0, st, P);
+    } else {
+      if (big) hipLaunchKernelGGL((decode_split_kernel<NB, 1, 8>), grid, dim3(512), 0, st, P);
+      else hipLaunchKernelGGL((decode_split_kernel<NB, 1, 4>), grid, dim3(256), 0, st, P);
+    }
     return launch_status();
   });
+}
+}  // namespace
+
+int kitty_decode_split(const kitty_layout* L, const kitty_cache* C, const void* q, float sm_scale, int32_t n_splits,
+                       void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return launch_split(L, C, q, sm_scale, n_splits, workspace, workspace_bytes, nullptr, 0, hip_stream, nullptr);
 }
 
 int kitty_decode_merge(const kitty_layout* L, const kitty_cache* C, void* out, int32_t n_splits, int32_t out_dtype,
@@ -259,8 +282,9 @@ int kitty_decode_attention(const kitty_layout* L, const kitty_cache* C, const vo
                            int32_t n_splits, int32_t out_dtype, void* workspace, size_t workspace_bytes,
                            void* hip_stream) {
   if (!out || (out_dtype != 0 && out_dtype != 1)) return KITTY_ERR_INVALID_ARG;
-  int rc = kitty_decode_split(L, C, q, sm_scale, n_splits, workspace, workspace_bytes, hip_stream);
-  if (rc) return rc;
+  bool merged = false;
+  int rc = launch_split(L, C, q, sm_scale, n_splits, workspace, workspace_bytes, out, out_dtype, hip_stream, &merged);
+  if (rc || merged) return rc;
   return kitty_decode_merge(L, C, out, n_splits, out_dtype, workspace, workspace_bytes, hip_stream);
 }
 

@@ -36,26 +36,26 @@ struct DecodeParams {
   float qk_scale_log2;   // sm_scale * log2(e)
   int32_t batch, max_pages, n_q_heads, n_kv_heads, gqa;
   int32_t n_splits, min_pages, has_window, out_dtype;
+  int32_t direct_out;    // split kernel with n_splits == 1: normalise and store `out` itself, no partials
 };
 
 // Page ranges of one sequence: with np pages and a window of r rows, the sequence uses
 // Sb = min(n_splits, max(1, np / min_pages)) ranges (one if it only has a window, none if it is empty);
-// range s covers pages [s*np/Sb, (s+1)*np/Sb) and the last range also takes the window.
+// range s covers pages [s*np/Sb, (s+1)*np/Sb) and window rows [s*r/Sb, (s+1)*r/Sb).
 __device__ __forceinline__ int active_splits(int np, int r, int n_splits, int min_pages) {
   if (np <= 0) return r > 0 ? 1 : 0;
   return min(n_splits, max(1, np / min_pages));
 }
 
-// One page's record as it sits in a lane's registers.  `meta` is the lane's 16 bytes of one of the four
-// fp16 arrays (lane group 0: k_scale, 1: k_zero, 2: v_scale, 3: v_zero; entries 8j..8j+7), exchanged
-// between the lane groups through LDS.
+// One page's code planes as they sit in a lane's registers.  The four fp16 arrays travel separately: lane
+// group 0 fetches k_scale, 1 k_zero, 2 v_scale, 3 v_zero (entries 8j..8j+7 each) and the groups exchange
+// them through LDS.
 template <int NB16>
 struct PageRegs {
   uint4 kd[4];
   uint2 kb[NB16 ? NB16 : 1];
   uint32_t chv[NB16 ? NB16 : 1];
   uint4 vd[4];
-  uint4 meta;
 };
 
 // Byte offsets of a lane into a record (32-bit, so loads take the scalar record base + one VGPR offset).
@@ -70,36 +70,28 @@ __device__ __forceinline__ LaneOffsets lane_offsets(int l) {
   return LaneOffsets{(uint32_t)l * 16u, (uint32_t)l * 8u, j, base + 16u * j};
 }
 
-// The loads of a page are issued in four groups spread over the processing of the previous page.
-template <int NB16, int PART>
-__device__ __forceinline__ void load_part(PageRegs<NB16>& r, const uint8_t* __restrict__ rec, const LaneOffsets& o) {
+// A page is fetched in three pieces: the lane's 16 bytes of fp16 arrays, the Key planes (+ channel list), the
+// Value plane.  Each piece of the next page is requested as soon as the registers of the current one are dead.
+template <int NB16>
+__device__ __forceinline__ uint4 load_meta(const uint8_t* __restrict__ rec, const LaneOffsets& o) {
+  return *reinterpret_cast<const uint4*>(rec + o.meta);
+}
+template <int NB16>
+__device__ __forceinline__ void load_k(PageRegs<NB16>& r, const uint8_t* __restrict__ rec, const LaneOffsets& o) {
   using R = Rec<NB16>;
-  if constexpr (PART == 0) {
-    r.meta = *reinterpret_cast<const uint4*>(rec + o.meta);
-    r.kd[0] = *reinterpret_cast<const uint4*>(rec + R::kd + o.o16);
-    r.kd[1] = *reinterpret_cast<const uint4*>(rec + R::kd + 1024 + o.o16);
-  } else if constexpr (PART == 1) {
-    r.kd[2] = *reinterpret_cast<const uint4*>(rec + R::kd + 2048 + o.o16);
-    r.kd[3] = *reinterpret_cast<const uint4*>(rec + R::kd + 3072 + o.o16);
 #pragma unroll
-    for (int s = 0; s < NB16; ++s) {
-      r.kb[s] = *reinterpret_cast<const uint2*>(rec + R::kb + 512 * s + o.o8);
-      r.chv[s] = rec[R::ch + 16 * s + o.j];
-    }
-  } else if constexpr (PART == 2) {
-    r.vd[0] = *reinterpret_cast<const uint4*>(rec + R::vd + o.o16);
-    r.vd[1] = *reinterpret_cast<const uint4*>(rec + R::vd + 1024 + o.o16);
-  } else {
-    r.vd[2] = *reinterpret_cast<const uint4*>(rec + R::vd + 2048 + o.o16);
-    r.vd[3] = *reinterpret_cast<const uint4*>(rec + R::vd + 3072 + o.o16);
+  for (int i = 0; i < 4; ++i) r.kd[i] = *reinterpret_cast<const uint4*>(rec + R::kd + 1024 * i + o.o16);
+#pragma unroll
+  for (int s = 0; s < NB16; ++s) {
+    r.kb[s] = *reinterpret_cast<const uint2*>(rec + R::kb + 512 * s + o.o8);
+    r.chv[s] = rec[R::ch + 16 * s + o.j];
   }
 }
 template <int NB16>
-__device__ __forceinline__ void load_page(PageRegs<NB16>& r, const uint8_t* __restrict__ rec, const LaneOffsets& o) {
-  load_part<NB16, 0>(r, rec, o);
-  load_part<NB16, 1>(r, rec, o);
-  load_part<NB16, 2>(r, rec, o);
-  load_part<NB16, 3>(r, rec, o);
+__device__ __forceinline__ void load_v(PageRegs<NB16>& r, const uint8_t* __restrict__ rec, const LaneOffsets& o) {
+  using R = Rec<NB16>;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) r.vd[i] = *reinterpret_cast<const uint4*>(rec + R::vd + 1024 * i + o.o16);
 }
 
 // sixteen 2-bit elements -> four registers of four int8 each (elements 4v..4v+3 in register v)
@@ -204,17 +196,17 @@ struct WaveScratch {
   uint8_t zero[16];
 };
 
-template <int HPL>
+template <int HPL, int NW>
 struct MergeScratch {
-  float acc[8][4 * HPL][D];   // 4 wavefronts x {pages, window}
-  float m[8][4 * HPL];
-  float l[8][4 * HPL];
+  float acc[2 * NW][4 * HPL][D];   // NW wavefronts x {pages, window}
+  float m[2 * NW][4 * HPL];
+  float l[2 * NW][4 * HPL];
 };
 
-template <int NB16, int HPL>
+template <int NB16, int HPL, int NW>
 union __attribute__((aligned(16))) DecodeSmem {
-  WaveScratch<NB16, HPL> w[4];
-  MergeScratch<HPL> mg;
+  WaveScratch<NB16, HPL> w[NW];
+  MergeScratch<HPL, NW> mg;
 };
 
 // Running state of one wavefront on the packed-page path and the work done per page.
@@ -278,14 +270,15 @@ struct PageWorker {
   __device__ __forceinline__ v4i unpack(uint32_t w) const { return WEIGHTED ? unpack16_w(w) : unpack16(w); }
 
   // stage a page's fp16 arrays in LDS (each lane group holds one of the four)
-  __device__ __forceinline__ void stage_meta(const PageRegs<NB16>& pg) {
-    *reinterpret_cast<uint4*>(&ws.meta[gi][16 * j]) = pg.meta;
+  __device__ __forceinline__ void stage_meta(const uint4& meta) {
+    *reinterpret_cast<uint4*>(&ws.meta[gi][16 * j]) = meta;
   }
 
-  // Processes page `pg` (whose fp16 arrays are already staged in LDS) while issuing the loads of the
-  // wavefront's next page into `nx` (record `rec_nx`, or nothing if `has_nx` is false).
-  __device__ __forceinline__ void process(const PageRegs<NB16>& pg, PageRegs<NB16>& nx, const uint8_t* rec_nx, bool has_nx) {
-    if (has_nx) load_part<NB16, 0>(nx, rec_nx, lo);
+  // Processes the page held in `pg` (its fp16 arrays already staged in LDS).  The pieces of the wavefront's
+  // next page (record `rec_nx`, if `has_nx`) are requested into the same registers as soon as they are dead.
+  __device__ __forceinline__ void process(PageRegs<NB16>& pg, const uint8_t* rec_nx, bool has_nx) {
+    uint4 meta_nx = make_uint4(0, 0, 0, 0);
+    if (has_nx) meta_nx = load_meta<NB16>(rec_nx, lo);
     // ================= A: integer image of q*s, bias q.z =================
     float ks[8], kz[8];
     f16x8_to_f32(*reinterpret_cast<const uint4*>(&ws.meta[0][16 * j]), ks);
@@ -324,7 +317,6 @@ struct PageWorker {
       }
     }
     wave_lds_fence();
-    if (has_nx) load_part<NB16, 1>(nx, rec_nx, lo);
     // ================= B: same integers gathered through the boosted-channel list =================
     if constexpr (NB16 > 0) {
 #pragma unroll
@@ -374,7 +366,7 @@ struct PageWorker {
         }
       }
     }
-    if (has_nx) load_part<NB16, 2>(nx, rec_nx, lo);
+    if (has_nx) load_k<NB16>(pg, rec_nx, lo);   // the Key planes of this page are in the matrix pipeline now
     // ================= D: online softmax; lane (j, gi) owns token 16T + j of heads gi*HPL + e ==========
     float vs[8], vz[8];
     f16x8_to_f32(*reinterpret_cast<const uint4*>(&ws.meta[2][16 * j]), vs);
@@ -424,7 +416,6 @@ struct PageWorker {
       for (int t = 0; t < TR; ++t) *reinterpret_cast<uint2*>(&ws.pbuf[hd * RPH + t][8 * j]) = tw[t];
     }
     wave_lds_fence();
-    if (has_nx) load_part<NB16, 3>(nx, rec_nx, lo);
     // ================= E: weighted Value sum on the int8 matrix cores =================
     const v4i pa0 = *reinterpret_cast<const v4i*>(p_ptr);
     const v4i pa1 = *reinterpret_cast<const v4i*>(p_ptr + 64);
@@ -443,22 +434,29 @@ struct PageWorker {
         acc[e][Td] = fmaf(acc[e][Td], corr[e], (float)ne * inv_beta[e]);
       }
     }
-    if (has_nx) stage_meta(nx);   // issued a page ago: arrived long since
+    if (has_nx) {
+      load_v<NB16>(pg, rec_nx, lo);
+      stage_meta(meta_nx);   // requested at the top of this page
+    }
     wave_lds_fence();   // the next page overwrites abuf/pbuf and reads the staged arrays
   }
 };
 
 // HPL = query heads per lane: 1 for GQA groups of 1, 2, 4 (three byte terms), 2 for groups of 8
 // (two byte terms).  Grid: x = page range (see active_splits), y = kv-head, z = sequence.
-// Block = 4 wavefronts; wavefront w takes pages p0+w, p0+w+4, ... of the range and, in the last
-// range of a sequence, 32 rows of the bf16 window.
+// Block = NW wavefronts (4 or 8); wavefront w takes pages p0+w, p0+w+NW, ... of the range and a slice of
+// the range's share of the bf16 window.
+// wavefronts per SIMD the kernel is compiled for (register budget 512 / n)
 template <int NB16, int HPL>
-__global__ __launch_bounds__(256, 2) void decode_split_kernel(DecodeParams p) {
+constexpr int decode_waves_per_simd() { return 2; }
+
+template <int NB16, int HPL, int NW>
+__global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void decode_split_kernel(DecodeParams p) {
   using R = Rec<NB16>;
   constexpr int RPH = 4 / HPL;
   constexpr int NH = 4 * HPL;              // heads handled by the block
 
-  __shared__ DecodeSmem<NB16, HPL> smem;
+  __shared__ DecodeSmem<NB16, HPL, NW> smem;
 
   const int slot = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x;
@@ -469,15 +467,33 @@ __global__ __launch_bounds__(256, 2) void decode_split_kernel(DecodeParams p) {
   const int np = min(p.n_pages[b], p.max_pages);
   const int r = p.has_window ? min(p.n_resid[b], G) : 0;
   const int sb = active_splits(np, r, p.n_splits, p.min_pages);
-  if (slot >= sb) return;
+  if (slot >= sb) {
+    if (p.direct_out && slot == 0) {   // empty sequence: the result is defined as zeros
+      for (int o = tid; o < g * D; o += 64 * NW) {
+        const size_t oi = ((size_t)b * p.n_q_heads + (size_t)h * g) * D + o;
+        if (p.out_dtype == 0) reinterpret_cast<uint16_t*>(p.out)[oi] = 0;
+        else reinterpret_cast<float*>(p.out)[oi] = 0.f;
+      }
+    }
+    return;
+  }
   const int p0 = (int)((long long)slot * np / sb), p1 = (int)((long long)(slot + 1) * np / sb);
-  const bool with_window = slot == sb - 1 && r > 0;
 
   WaveScratch<NB16, HPL>& ws = smem.w[w];
   const size_t qrow = ((size_t)b * p.n_q_heads + (size_t)h * g);
   PageWorker<NB16, HPL> pw(ws, l);
 
   if (p0 < p1) {
+    const int32_t* pt = p.page_table + (size_t)b * p.max_pages;
+    const size_t rec_stride = (size_t)p.n_kv_heads * R::bytes;
+    const uint8_t* pool_h = p.pool + (size_t)h * R::bytes;
+    auto rec_of = [&](int idx) { return pool_h + (size_t)pt[idx] * rec_stride; };
+
+    // one register buffer: each piece of the next page is requested when the current page no longer needs it.
+    // The first page is requested before anything else so that its latency overlaps the set-up below.
+    PageRegs<NB16> pg{};
+    int idx = p0 + w;
+    uint4 m0 = make_uint4(0, 0, 0, 0);
     // ---- zero the operand matrices once (rows of absent heads and the unused term row stay zero)
     {
       uint32_t* z32 = reinterpret_cast<uint32_t*>(&ws.abuf[0][0]);
@@ -493,44 +509,45 @@ __global__ __launch_bounds__(256, 2) void decode_split_kernel(DecodeParams p) {
       const uint4 raw = live ? *reinterpret_cast<const uint4*>(p.q + (qrow + hd) * D + 8 * j) : make_uint4(0, 0, 0, 0);
       pw.set_q(e, raw, p.qk_scale_log2, live);
     }
-    wave_lds_fence();
-
-    const int32_t* pt = p.page_table + (size_t)b * p.max_pages;
-    const size_t rec_stride = (size_t)p.n_kv_heads * R::bytes;
-    const uint8_t* pool_h = p.pool + (size_t)h * R::bytes;
-    auto rec_of = [&](int idx) { return pool_h + (size_t)pt[idx] * rec_stride; };
-
-    // two register buffers; the loads of the next page are issued while the current one is processed
-    PageRegs<NB16> bufA{}, bufB{};
-    int idx = p0 + w;
     if (idx < p1) {
-      load_page<NB16>(bufA, rec_of(idx), pw.lo);
-      pw.stage_meta(bufA);
+      const uint8_t* rec = rec_of(idx);
+      m0 = load_meta<NB16>(rec, pw.lo);
+      load_k<NB16>(pg, rec, pw.lo);
+      load_v<NB16>(pg, rec, pw.lo);
+      pw.stage_meta(m0);
       wave_lds_fence();
-      while (true) {
-        bool has_nx = idx + 4 < p1;
-        pw.process(bufA, bufB, has_nx ? rec_of(idx + 4) : pool_h, has_nx);
-        idx += 4;
-        if (idx >= p1) break;
-        has_nx = idx + 4 < p1;
-        pw.process(bufB, bufA, has_nx ? rec_of(idx + 4) : pool_h, has_nx);
-        idx += 4;
-        if (idx >= p1) break;
+      for (; idx < p1; idx += NW) {
+        const bool has_nx = idx + NW < p1;
+        pw.process(pg, has_nx ? rec_of(idx + NW) : pool_h, has_nx);
       }
     }
   }
 
-  // ================= residual window: bf16 rows, 32 tokens per wavefront =================
-  float accw[NH][2];        // channels 2l, 2l+1 of every head
+  // ================= residual window: bf16 rows, spread over the ranges of the sequence =================
+  // range `slot` of `sb` takes window rows [slot*r/sb, (slot+1)*r/sb); its four wavefronts split them evenly
+  // (at most 32 rows each since the window holds 128).
+  float accw[NH][8];        // channels 8j..8j+7 of every head (after the cross-group sum)
   float mw[HPL], lw[HPL];
 #pragma unroll
-  for (int hh = 0; hh < NH; ++hh) accw[hh][0] = accw[hh][1] = 0.f;
+  for (int hh = 0; hh < NH; ++hh)
+#pragma unroll
+    for (int k = 0; k < 8; ++k) accw[hh][k] = 0.f;
 #pragma unroll
   for (int e = 0; e < HPL; ++e) { mw[e] = -INFINITY; lw[e] = 0.f; }
-  const int t0 = 32 * w;
-  if (with_window && t0 < r) {
+  const int wr0 = (int)((long long)slot * r / sb), wr1 = (int)((long long)(slot + 1) * r / sb);
+  const int per = (wr1 - wr0 + NW - 1) / NW;
+  const int t0 = wr0 + w * per, t1 = min(t0 + per, wr1);
+  if (t0 < t1) {
     const uint16_t* wk = p.resid_k + ((size_t)b * p.n_kv_heads + h) * (size_t)(G * D);
     const uint16_t* wv = p.resid_v + ((size_t)b * p.n_kv_heads + h) * (size_t)(G * D);
+    // Value rows t0 + 4i + gi (i < 8), channels 8j..8j+7: requested first, used last.  Rows past the slice are
+    // clamped to its last row (their weight is zero; uninitialised rows are never touched).
+    uint4 vrow[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int row = min(t0 + 4 * i + gi, t1 - 1);
+      vrow[i] = *reinterpret_cast<const uint4*>(wv + (size_t)row * D + 8 * j);
+    }
     // A operand: query rows; row hd*RPH carries head hd, the other rows are zero
     const int arow_head = j / RPH;
     const bool arow_live = (j % RPH) == 0 && arow_head < g;
@@ -545,14 +562,15 @@ __global__ __launch_bounds__(256, 2) void decode_split_kernel(DecodeParams p) {
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
       const int t = t0 + 16 * tt + j;
+      const int trow = min(t, t1 - 1);
       v4f c = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int mm = 0; mm < 4; ++mm) {
-        const uint4 raw = *reinterpret_cast<const uint4*>(wk + (size_t)t * D + 32 * mm + 8 * gi);
+        const uint4 raw = *reinterpret_cast<const uint4*>(wk + (size_t)trow * D + 32 * mm + 8 * gi);
         c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aq[mm], __builtin_bit_cast(v8bf, raw), c, 0, 0, 0);
       }
 #pragma unroll
-      for (int e = 0; e < HPL; ++e) x[e][tt] = t < r ? c[e * RPH] * p.qk_scale_log2 : -INFINITY;
+      for (int e = 0; e < HPL; ++e) x[e][tt] = t < t1 ? c[e * RPH] * p.qk_scale_log2 : -INFINITY;
     }
 #pragma unroll
     for (int e = 0; e < HPL; ++e) {
@@ -564,17 +582,36 @@ __global__ __launch_bounds__(256, 2) void decode_split_kernel(DecodeParams p) {
       ws.pw[16 + j][gi * HPL + e] = pb;
     }
     wave_lds_fence();
-    const int nt = min(32, r - t0);
-    for (int t = 0; t < nt; ++t) {
-      const uint32_t two = *reinterpret_cast<const uint32_t*>(wv + (size_t)(t0 + t) * D + 2 * l);
-      const float v0 = __uint_as_float(two << 16), v1 = __uint_as_float(two & 0xffff0000u);
 #pragma unroll
-      for (int hh = 0; hh < NH; ++hh) {
-        const float ph = ws.pw[t][hh];
-        accw[hh][0] = fmaf(ph, v0, accw[hh][0]);
-        accw[hh][1] = fmaf(ph, v1, accw[hh][1]);
+    for (int i = 0; i < 8; ++i) {
+      const int tl = 4 * i + gi;          // row within the wavefront's slice (weight 0 beyond it)
+      float ph[NH];
+#pragma unroll
+      for (int q4 = 0; q4 < NH / 4; ++q4) {
+        const float4 f = *reinterpret_cast<const float4*>(&ws.pw[tl][4 * q4]);
+        ph[4 * q4] = f.x; ph[4 * q4 + 1] = f.y; ph[4 * q4 + 2] = f.z; ph[4 * q4 + 3] = f.w;
+      }
+      const uint32_t vw[4] = {vrow[i].x, vrow[i].y, vrow[i].z, vrow[i].w};
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const float v0 = __uint_as_float(vw[k] << 16), v1 = __uint_as_float(vw[k] & 0xffff0000u);
+#pragma unroll
+        for (int hh = 0; hh < NH; ++hh) {
+          accw[hh][2 * k] = fmaf(ph[hh], v0, accw[hh][2 * k]);
+          accw[hh][2 * k + 1] = fmaf(ph[hh], v1, accw[hh][2 * k + 1]);
+        }
       }
     }
+    // sum over the four lane groups (rows 4i + gi): two butterfly steps across groups
+#pragma unroll
+    for (int hh = 0; hh < NH; ++hh)
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        float v = accw[hh][k];
+        v += __shfl_xor(v, 16);
+        v += __shfl_xor(v, 32);
+        accw[hh][k] = v;
+      }
   }
 
   // ================= merge the eight partials (4 wavefronts x {pages, window}), write the result ===========
@@ -582,35 +619,49 @@ __global__ __launch_bounds__(256, 2) void decode_split_kernel(DecodeParams p) {
 #pragma unroll
   for (int e = 0; e < HPL; ++e) { lsum[e] = row_sum(pw.l_run[e]); zsum[e] = row_sum(pw.z_run[e]); lwsum[e] = row_sum(lw[e]); }
   __syncthreads();   // every wavefront is done with its scratch
-  MergeScratch<HPL>& mg = smem.mg;
+  MergeScratch<HPL, NW>& mg = smem.mg;
 #pragma unroll
   for (int e = 0; e < HPL; ++e) {
     const int hd = gi * HPL + e;
 #pragma unroll
     for (int Td = 0; Td < 8; ++Td) mg.acc[w][hd][16 * Td + j] = pw.acc[e][Td] + zsum[e];
-    if (j == 0) { mg.m[w][hd] = pw.m_run[e]; mg.l[w][hd] = lsum[e]; mg.m[4 + w][hd] = mw[e]; mg.l[4 + w][hd] = lwsum[e]; }
+    if (j == 0) { mg.m[w][hd] = pw.m_run[e]; mg.l[w][hd] = lsum[e]; mg.m[NW + w][hd] = mw[e]; mg.l[NW + w][hd] = lwsum[e]; }
   }
 #pragma unroll
-  for (int hh = 0; hh < NH; ++hh) {
-    mg.acc[4 + w][hh][2 * l] = accw[hh][0];
-    mg.acc[4 + w][hh][2 * l + 1] = accw[hh][1];
+  for (int e = 0; e < HPL; ++e) {
+    const int hd = gi * HPL + e;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      // every lane group holds the full sums; group gi stores its own heads
+      float v = 0.f;
+#pragma unroll
+      for (int hh = 0; hh < NH; ++hh) v = (hh == hd) ? accw[hh][k] : v;
+      mg.acc[NW + w][hd][8 * j + k] = v;
+    }
   }
   __syncthreads();
-  float* out = p.ws + (((size_t)b * p.n_kv_heads + h) * p.n_splits + slot) * (size_t)g * WS_STRIDE;
-  for (int o = tid; o < g * D; o += 256) {
+  float* part = p.ws + (((size_t)b * p.n_kv_heads + h) * p.n_splits + slot) * (size_t)g * WS_STRIDE;
+  for (int o = tid; o < g * D; o += 64 * NW) {
     const int hd = o >> 7, d = o & 127;
     float M = -INFINITY;
 #pragma unroll
-    for (int ww = 0; ww < 8; ++ww) M = fmaxf(M, mg.m[ww][hd]);
+    for (int ww = 0; ww < 2 * NW; ++ww) M = fmaxf(M, mg.m[ww][hd]);
     float a = 0.f, L = 0.f;
 #pragma unroll
-    for (int ww = 0; ww < 8; ++ww) {
+    for (int ww = 0; ww < 2 * NW; ++ww) {
       const float f = __builtin_amdgcn_exp2f(mg.m[ww][hd] - M);   // exp2(-inf) = 0 for idle partials
       a = fmaf(mg.acc[ww][hd][d], f, a);
       L = fmaf(mg.l[ww][hd], f, L);
     }
-    out[hd * WS_STRIDE + d] = a;
-    if (d == 0) { out[hd * WS_STRIDE + D] = M; out[hd * WS_STRIDE + D + 1] = L; }
+    if (p.direct_out) {   // the only range of this (sequence, kv-head): finish here
+      const float v = L > 0.f ? a / L : 0.f;
+      const size_t oi = (qrow + hd) * D + d;
+      if (p.out_dtype == 0) reinterpret_cast<uint16_t*>(p.out)[oi] = f32_to_bf16_rne(v);
+      else reinterpret_cast<float*>(p.out)[oi] = v;
+    } else {
+      part[hd * WS_STRIDE + d] = a;
+      if (d == 0) { part[hd * WS_STRIDE + D] = M; part[hd * WS_STRIDE + D + 1] = L; }
+    }
   }
 }
 

@@ -12,7 +12,8 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libkitty.so")
+# KITTY_LIB selects another build of the same library (A/B timing of kernel variants)
+LIB_PATH = os.environ.get("KITTY_LIB") or os.path.join(_HERE, "libkitty.so")
 
 KITTY_OK = 0
 ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = -1, -2, -3, -4
