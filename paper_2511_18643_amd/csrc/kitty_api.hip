@@ -220,8 +220,6 @@ int kitty_append_token(const kitty_layout* L, const kitty_cache* C, const void* 
   return dispatch_nb16(L->n_boost / 16, [&](auto nb) {
     constexpr int NB = decltype(nb)::value;
     hipLaunchKernelGGL(append_token_kernel<NB>, dim3(L->n_kv_heads, C->batch), dim3(256), 0, st, P);
-    if (hipGetLastError() != hipSuccess) return KITTY_ERR_HIP;
-    hipLaunchKernelGGL(append_state_kernel, dim3((C->batch + 255) / 256), dim3(256), 0, st, P);
     return launch_status();
   });
 }

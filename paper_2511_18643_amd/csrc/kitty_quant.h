@@ -216,47 +216,55 @@ struct AppendParams {
   int32_t batch, max_pages, n_pool_pages, n_kv_heads, rank_metric;
 };
 
-// Grid (n_kv_heads, batch).  Reads the sequence state, flushes a full window into a page, stores the
-// new token.  The state itself is advanced by append_state_kernel after every head has read it.
+// Grid (n_kv_heads, batch).  Reads the sequence state, flushes a full window into a page, stores the new
+// token.  Every head's block must see the old state, so the state is advanced by the block of a sequence
+// that finishes last: blocks take a ticket in bits 8.. of n_resid[b] (the row count needs bits 0..7) once
+// they are done, and the holder of the last ticket writes the new state, which also clears the tickets.
+constexpr int TICKET_SHIFT = 8;
+
 template <int NB16>
 __global__ __launch_bounds__(256) void append_token_kernel(AppendParams p) {
   __shared__ QuantSmem smem;
   const int h = blockIdx.x, b = blockIdx.y;
-  const int nr = p.n_resid[b];
+  const int nr = p.n_resid[b] & ((1 << TICKET_SHIFT) - 1);
+  const int np = p.n_pages[b];
+  const int32_t pid = p.fresh_page_ids[b];
   uint16_t* wk = p.resid_k + ((size_t)b * p.n_kv_heads + h) * (size_t)(G * D);
   uint16_t* wv = p.resid_v + ((size_t)b * p.n_kv_heads + h) * (size_t)(G * D);
-  if (nr < 0) return;
-  int slot = nr;
-  if (nr >= G) {
-    const int32_t pid = p.fresh_page_ids[b];
-    if (p.n_pages[b] >= p.max_pages || pid < 0 || pid >= p.n_pool_pages) return;   // cannot flush: leave unchanged
-    uint8_t* rec = p.pool + ((size_t)pid * p.n_kv_heads + h) * (size_t)Rec<NB16>::bytes;
-    quantize_page<NB16>(smem, wk, wv, D, rec, p.rank_metric);
-    slot = 0;
-  }
+  const bool flush = nr >= G;
+  // a flush that cannot happen (page table full, id outside the pool) leaves the sequence unchanged
+  const bool ok = !flush || (np >= 0 && np < p.max_pages && pid >= 0 && pid < p.n_pool_pages);
   const int tid = threadIdx.x;
-  if (tid < 32) {
-    const int part = tid & 15;
-    const uint16_t* src = (tid < 16 ? p.k_new : p.v_new) + ((size_t)b * p.n_kv_heads + h) * D + part * 8;
-    uint16_t* dst = (tid < 16 ? wk : wv) + (size_t)slot * D + part * 8;
-    *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
+  if (ok) {
+    int slot = nr;
+    if (flush) {
+      uint8_t* rec = p.pool + ((size_t)pid * p.n_kv_heads + h) * (size_t)Rec<NB16>::bytes;
+      quantize_page<NB16>(smem, wk, wv, D, rec, p.rank_metric);
+      slot = 0;
+    }
+    if (tid < 32) {
+      const int part = tid & 15;
+      const uint16_t* src = (tid < 16 ? p.k_new : p.v_new) + ((size_t)b * p.n_kv_heads + h) * D + part * 8;
+      uint16_t* dst = (tid < 16 ? wk : wv) + (size_t)slot * D + part * 8;
+      *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
+    }
   }
-}
-
-__global__ void append_state_kernel(AppendParams p) {
-  const int b = blockIdx.x * blockDim.x + threadIdx.x;
-  if (b >= p.batch) return;
-  const int nr = p.n_resid[b];
-  if (nr < 0) return;
-  if (nr >= G) {
-    const int32_t pid = p.fresh_page_ids[b];
-    const int np = p.n_pages[b];
-    if (np >= p.max_pages || pid < 0 || pid >= p.n_pool_pages) return;
-    p.page_table[(size_t)b * p.max_pages + np] = pid;
-    p.n_pages[b] = np + 1;
-    p.n_resid[b] = 1;
-  } else {
-    p.n_resid[b] = nr + 1;
+  __syncthreads();   // every thread of the block has read the old state
+  if (tid == 0) {
+    const int old = atomicAdd(&p.n_resid[b], 1 << TICKET_SHIFT);
+    if ((old >> TICKET_SHIFT) == p.n_kv_heads - 1) {   // every block of this sequence has read the state
+      int new_nr = nr;
+      if (ok) {
+        if (flush) {
+          p.page_table[(size_t)b * p.max_pages + np] = pid;
+          p.n_pages[b] = np + 1;
+          new_nr = 1;
+        } else {
+          new_nr = nr + 1;
+        }
+      }
+      atomicExch(&p.n_resid[b], new_nr);
+    }
   }
 }
 

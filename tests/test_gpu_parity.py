@@ -176,3 +176,75 @@ def test_append_with_full_page_table_leaves_sequence_unchanged():
     torch.cuda.synchronize()
     assert torch.equal(gc.n_pages, before[0]) and torch.equal(gc.n_resid, before[1])
     assert torch.equal(gc.resid_k, before[2]) and torch.equal(gc.pool, before[3])
+
+
+# ------------------------------------------------------------------ full-size workloads, sampled
+def _full_size_case(name, n_src_seqs, sample_pairs, tol32):
+    """The benchmark's launch configuration at the workload's full size: the cache is built from
+    `n_src_seqs` distinct synthetic sequences tiled over the batch (as bench.py does), prefilled through
+    kitty_quantize_pages; a sample of (sequence, query head) outputs and of packed records is checked
+    against the oracle, which rebuilds the sampled sequences from the inputs."""
+    import torch
+    from paper_2511_18643_amd import kitty
+    w = synth.WORKLOADS[name]
+    B, hkv, g = w.batch, w.n_kv_heads, w.gqa
+    n_pages, r = w.pages_and_resid()
+    L = n_pages * 128 + r
+    ksrc = np.zeros((n_src_seqs, hkv, L, 128), np.uint16)
+    vsrc = np.zeros_like(ksrc)
+    need = sorted({(b % n_src_seqs, h) for b, h in sample_pairs})
+    for sb, h in need:                      # only the sampled source streams carry data; the rest stay zero
+        ksrc[sb, h], vsrc[sb, h] = synth.kv_block(w, sb, h, L)
+    kt, vt = H.bf16_tensor(ksrc), H.bf16_tensor(vsrc)
+    layout = kitty.make_layout(w.n_q_heads, hkv, w.n_boost, w.residual_window, w.rank_metric)
+    cache = kitty.Cache(layout, B, n_pages, B * n_pages)
+    offs = torch.tensor([(b % n_src_seqs) * hkv * L * 128 + i * 128 * 128 for b in range(B) for i in range(n_pages)],
+                        dtype=torch.int64, device="cuda")
+    ids = torch.arange(B * n_pages, dtype=torch.int32, device="cuda")
+    kitty.kitty_quantize_pages(layout, kt, vt, 128 * 128, L * 128, 128, ids, B * n_pages, cache.pool,
+                               cache.n_pool_pages, src_page_offsets=offs)
+    cache.page_table.copy_(ids.view(B, n_pages))
+    cache.n_pages.fill_(n_pages)
+    for b in range(B):
+        cache.resid_k[b, :, :r] = kt[b % n_src_seqs, :, n_pages * 128:]
+        cache.resid_v[b, :, :r] = vt[b % n_src_seqs, :, n_pages * 128:]
+    cache.n_resid.fill_(r)
+    q = synth.query(w)
+    ws = kitty.new_workspace(layout, B, n_pages)
+    out = torch.empty((B, w.n_q_heads, 128), dtype=torch.float32, device="cuda")
+    kitty.kitty_decode_attention(layout, cache, H.bf16_tensor(q), out, w.sm_scale, ws)       # automatic plan
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert np.isfinite(got).all()
+    # oracle on the sampled pairs, from the inputs
+    worst = 0.0
+    r_np = np.random.default_rng(5)
+    for b, h in sample_pairs:
+        sb = b % n_src_seqs
+        oc = ko.KittyCacheOracle(1, 1, g, w.n_boost, w.residual_window, n_pages, n_pages, w.rank_metric)
+        oc.quantize_pages(ksrc[sb, h, :n_pages * 128].reshape(n_pages, 1, 128, 128),
+                          vsrc[sb, h, :n_pages * 128].reshape(n_pages, 1, 128, 128), list(range(n_pages)))
+        oc.page_table[0] = np.arange(n_pages); oc.n_pages[0] = n_pages
+        oc.resid_k[0, 0, :r] = ksrc[sb, h, n_pages * 128:]; oc.resid_v[0, 0, :r] = vsrc[sb, h, n_pages * 128:]
+        oc.n_resid[0] = r
+        # packed records: a sample of this pair's pages, byte for byte
+        for i in r_np.choice(n_pages, size=min(6, n_pages), replace=False):
+            rec = cache.pool[b * n_pages + int(i), h].cpu().numpy()
+            assert np.array_equal(rec, oc.pool[int(i), 0]), f"record mismatch b={b} h={h} page={i}"
+        want = oc.decode_attention(q[b:b + 1, h * g:(h + 1) * g], w.sm_scale)[0]
+        err = float(np.abs(got[b, h * g:(h + 1) * g] - want).max())
+        worst = max(worst, err)
+    assert worst <= tol32, f"{name}: max abs err {worst}"
+    return worst
+
+
+def test_c2_full_size_sampled():
+    _full_size_case("c2", 2, [(0, 0), (1, 3), (7, 5), (15, 7)], TOL_FP32)
+
+
+def test_c3_full_size_sampled():
+    _full_size_case("c3", 2, [(0, 0), (1, 7), (18, 2), (31, 4)], TOL_FP32)
+
+
+def test_c4_full_size_sampled():
+    _full_size_case("c4", 1, [(0, 0), (7, 5)], 1e-3)
