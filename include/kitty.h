@@ -92,7 +92,8 @@ size_t kitty_decode_workspace_bytes(const kitty_layout* layout, int32_t batch, i
  * Per page and head: per-channel min/max of K over the G tokens, channel score, the n_boost
  * best channels (score descending, index ascending) get 4-bit codes and the rest 2-bit codes;
  * V gets 2-bit codes per token.  scale = fp16((max-min)/qmax), zero = fp16(min),
- * code = clamp(rint((x-zero)/scale), 0, qmax) in fp32 against the stored fp16 values. */
+ * code = clamp(rint((x-zero) * inv), 0, qmax) with inv = fp32(1/scale) (0 for a zero scale), all in IEEE
+ * fp32 against the stored fp16 values, ties to even. */
 int kitty_quantize_pages(const kitty_layout* layout, const void* k_src, const void* v_src,
                          int64_t page_stride, int64_t head_stride, int64_t token_stride,
                          const int64_t* src_page_offsets, const int32_t* dst_page_ids,

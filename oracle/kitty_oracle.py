@@ -19,8 +19,9 @@ What it follows (arXiv 2511.18643):
 
 Readings taken where the paper is silent (each is listed in the design notes too):
   * quantizer formula: asymmetric min/max, scale = fp16((mx-mn)/qmax), zero = fp16(mn),
-    code = clamp(rint((x - zero)/scale), 0, qmax) in fp32 against the *stored* fp16 values,
-    round-half-even; a zero scale gives code 0.
+    code = clamp(rint((x - zero) * inv), 0, qmax) with inv = fp32(1/scale) taken once per
+    channel (token), all in IEEE fp32 against the *stored* fp16 values, round-half-even;
+    a zero scale gives code 0.
   * ranking: score descending, channel index ascending; boosted channels take slots in
     ascending channel order.  rank_metric 0 = sum_t |x| (Eq. 2 without the rank-irrelevant
     1/T, accumulated in fp64), rank_metric 1 = fp32(mx - mn).
@@ -105,9 +106,9 @@ def _asym_quant(x: np.ndarray, mn: np.ndarray, mx: np.ndarray, qmax: np.ndarray)
     s = scale_h.astype(np.float32)
     z = zero_h.astype(np.float32)
     with np.errstate(divide="ignore", invalid="ignore"):
-        r = np.rint(((x - z).astype(np.float32) / s).astype(np.float32))
+        inv = np.where(s > 0, (np.float32(1.0) / s).astype(np.float32), np.float32(0.0)).astype(np.float32)
+    r = np.rint(((x - z).astype(np.float32) * inv).astype(np.float32))
     r = np.minimum(np.maximum(r, np.float32(0.0)), qmax.astype(np.float32))
-    r = np.where(s > 0, r, np.float32(0.0))
     return r.astype(np.uint8), scale_h, zero_h
 
 

@@ -12,9 +12,9 @@ struct QuantSmem {
   double score[D];
   float mn[2][D];
   float mx[2][D];
-  float sc[D];             // scale as float(fp16), per channel (K phase) or per token (V phase)
-  float zr[D];
-  float qm[D];
+  float inv[D];            // 1 / float(fp16 scale) (0 if the scale is 0), per channel (K phase) or per token (V phase)
+  float zr[D];             // float(fp16 zero-point)
+  float qm[D];             // 15 or 3
   unsigned long long ballot0;
   uint8_t chl[D];
 };
@@ -23,12 +23,13 @@ __device__ __forceinline__ float tile_elem(const QuantSmem& s, int t, int c) {
   return bf16_to_f32(reinterpret_cast<const uint16_t*>(s.tile)[t * 130 + c]);
 }
 
-// code = clamp(rint((x - zero)/scale), 0, qmax) with IEEE fp32 subtract and divide; 0 if scale == 0.
-__device__ __forceinline__ uint32_t qcode(float x, float s, float z, float qmax) {
-  float r = rintf(__fdiv_rn(__fsub_rn(x, z), s));
-  r = fminf(fmaxf(r, 0.0f), qmax);
-  return s > 0.0f ? (uint32_t)r : 0u;
+// code = clamp(rint((x - zero) * inv), 0, qmax), inv = 1/scale rounded once (IEEE), 0 for a zero scale.
+// fp32 subtract and multiply, ties to even; with inv == 0 every code is 0.
+__device__ __forceinline__ uint32_t qcode(float x, float inv, float z, float qmax) {
+  const float r = rintf(__fmul_rn(__fsub_rn(x, z), inv));
+  return (uint32_t)fminf(fmaxf(r, 0.0f), qmax);
 }
+__device__ __forceinline__ float inv_scale(float s) { return s > 0.0f ? __fdiv_rn(1.0f, s) : 0.0f; }
 
 __device__ __forceinline__ int elem_shift(int a) { return 8 * (a & 3) + 2 * (a >> 2); }
 
@@ -44,17 +45,19 @@ __device__ __forceinline__ void load_tile(QuantSmem& s, const uint16_t* __restri
   }
 }
 
+// One block of at least 256 threads; threads 0..255 do the work, every thread takes part in the barriers.
 template <int NB16>
 __device__ void quantize_page(QuantSmem& s, const uint16_t* __restrict__ ksrc, const uint16_t* __restrict__ vsrc,
                               int64_t token_stride, uint8_t* __restrict__ rec, int rank_metric) {
   using R = Rec<NB16>;
   const int tid = threadIdx.x;
-  const int c = tid & 127, half = tid >> 7;
+  const bool act = tid < 256;
+  const int c = tid & 127, half = (tid >> 7) & 1;
 
   // ---------------- Key page ----------------
-  load_tile(s, ksrc, token_stride, tid);
+  if (act) load_tile(s, ksrc, token_stride, tid);
   __syncthreads();
-  {  // per-channel min, max, sum |x| over half of the tokens
+  if (act) {  // per-channel min, max, sum |x| over half of the tokens
     float mn = INFINITY, mx = -INFINITY;
     double sum = 0.0;
     for (int t = half * 64; t < half * 64 + 64; ++t) {
@@ -92,7 +95,7 @@ __device__ void quantize_page(QuantSmem& s, const uint16_t* __restrict__ ksrc, c
     const float qmax = boosted ? 15.0f : 3.0f;
     const uint16_t sh = f32_to_f16_bits(__fdiv_rn(__fsub_rn(mx, mn), qmax));
     const uint16_t zh = f32_to_f16_bits(mn);
-    s.sc[c] = f16_bits_to_f32(sh);
+    s.inv[c] = inv_scale(f16_bits_to_f32(sh));
     s.zr[c] = f16_bits_to_f32(zh);
     s.qm[c] = qmax;
     reinterpret_cast<uint16_t*>(rec + R::ks)[c] = sh;
@@ -101,42 +104,59 @@ __device__ void quantize_page(QuantSmem& s, const uint16_t* __restrict__ ksrc, c
     if (c >= 16 * NB16) rec[R::ch + c] = 0;   // pad bytes of the channel list
   }
   __syncthreads();
-  {  // dense plane: thread (q, lane) builds the 16 bytes that lane reads back in the decode kernel
+  if (act) {  // dense plane: thread (q, lane) builds the 16 bytes that lane reads back in the decode kernel
     const int q = tid >> 6, lane = tid & 63;
     uint32_t w[4];
 #pragma unroll
-    for (int wi = 0; wi < 4; ++wi) {
-      const int t = 32 * q + 16 * (wi >> 1) + (lane & 15);
-      const int cb = 4 * (wi & 1) + (lane >> 4);
-      uint32_t word = 0;
+    for (int csel = 0; csel < 2; ++csel) {
+      const int cb = 4 * csel + (lane >> 4);
+      float inv[16], zr[16], qm[16];
 #pragma unroll
-      for (int a = 0; a < 16; ++a) {
-        const int ch = 16 * cb + a;
-        word |= (qcode(tile_elem(s, t, ch), s.sc[ch], s.zr[ch], s.qm[ch]) & 3u) << elem_shift(a);
+      for (int a4 = 0; a4 < 4; ++a4) {
+        const float4 i4 = *reinterpret_cast<const float4*>(&s.inv[16 * cb + 4 * a4]);
+        const float4 z4 = *reinterpret_cast<const float4*>(&s.zr[16 * cb + 4 * a4]);
+        const float4 q4 = *reinterpret_cast<const float4*>(&s.qm[16 * cb + 4 * a4]);
+        inv[4 * a4] = i4.x; inv[4 * a4 + 1] = i4.y; inv[4 * a4 + 2] = i4.z; inv[4 * a4 + 3] = i4.w;
+        zr[4 * a4] = z4.x; zr[4 * a4 + 1] = z4.y; zr[4 * a4 + 2] = z4.z; zr[4 * a4 + 3] = z4.w;
+        qm[4 * a4] = q4.x; qm[4 * a4 + 1] = q4.y; qm[4 * a4 + 2] = q4.z; qm[4 * a4 + 3] = q4.w;
       }
-      w[wi] = word;
+#pragma unroll
+      for (int tsel = 0; tsel < 2; ++tsel) {
+        const int t = 32 * q + 16 * tsel + (lane & 15);
+        uint32_t word = 0;
+#pragma unroll
+        for (int a2 = 0; a2 < 8; ++a2) {
+          const uint32_t two = s.tile[t * 65 + 8 * cb + a2];
+          const float x0 = __uint_as_float(two << 16), x1 = __uint_as_float(two & 0xffff0000u);
+          word |= (qcode(x0, inv[2 * a2], zr[2 * a2], qm[2 * a2]) & 3u) << elem_shift(2 * a2);
+          word |= (qcode(x1, inv[2 * a2 + 1], zr[2 * a2 + 1], qm[2 * a2 + 1]) & 3u) << elem_shift(2 * a2 + 1);
+        }
+        w[2 * tsel + csel] = word;
+      }
     }
     reinterpret_cast<uint4*>(rec + R::kd)[64 * q + lane] = make_uint4(w[0], w[1], w[2], w[3]);
   }
   if constexpr (NB16 > 0) {  // boost plane: high two bits of the boosted channels, slot order
-    for (int idx = tid; idx < 128 * NB16; idx += 256) {
-      const int sblk = idx >> 7, u = (idx >> 6) & 1, lane = idx & 63;
-      const int t = 16 * (4 * u + (lane >> 4)) + (lane & 15);
-      uint32_t word = 0;
+    if (act) {
+      for (int idx = tid; idx < 128 * NB16; idx += 256) {
+        const int sblk = idx >> 7, u = (idx >> 6) & 1, lane = idx & 63;
+        const int t = 16 * (4 * u + (lane >> 4)) + (lane & 15);
+        uint32_t word = 0;
 #pragma unroll
-      for (int a = 0; a < 16; ++a) {
-        const int ch = s.chl[16 * sblk + a];
-        word |= (qcode(tile_elem(s, t, ch), s.sc[ch], s.zr[ch], 15.0f) >> 2) << elem_shift(a);
+        for (int a = 0; a < 16; ++a) {
+          const int ch = s.chl[16 * sblk + a];
+          word |= (qcode(tile_elem(s, t, ch), s.inv[ch], s.zr[ch], 15.0f) >> 2) << elem_shift(a);
+        }
+        *reinterpret_cast<uint32_t*>(rec + R::kb + 512 * sblk + 8 * lane + 4 * u) = word;
       }
-      *reinterpret_cast<uint32_t*>(rec + R::kb + 512 * sblk + 8 * lane + 4 * u) = word;
     }
   }
   __syncthreads();
 
   // ---------------- Value page ----------------
-  load_tile(s, vsrc, token_stride, tid);
+  if (act) load_tile(s, vsrc, token_stride, tid);
   __syncthreads();
-  {  // per-token min, max over half of the channels
+  if (act) {  // per-token min, max over half of the channels
     const int t = c;
     float mn2 = INFINITY, mx2 = -INFINITY;
     for (int k = 0; k < 32; ++k) {
@@ -154,28 +174,40 @@ __device__ void quantize_page(QuantSmem& s, const uint16_t* __restrict__ ksrc, c
     const float mxv = fmaxf(s.mx[0][t], s.mx[1][t]);
     const uint16_t sh = f32_to_f16_bits(__fdiv_rn(__fsub_rn(mxv, mnv), 3.0f));
     const uint16_t zh = f32_to_f16_bits(mnv);
-    s.sc[t] = f16_bits_to_f32(sh);
-    s.zr[t] = f16_bits_to_f32(zh);
+    // kept in position order: position p holds token 16*(p%8) + p/8
     const int p = 8 * (t & 15) + (t >> 4);
+    s.inv[p] = inv_scale(f16_bits_to_f32(sh));
+    s.zr[p] = f16_bits_to_f32(zh);
     reinterpret_cast<uint16_t*>(rec + R::vs)[p] = sh;
     reinterpret_cast<uint16_t*>(rec + R::vz)[p] = zh;
   }
   __syncthreads();
-  {
+  if (act) {
     const int q = tid >> 6, lane = tid & 63;
     uint32_t w[4];
 #pragma unroll
-    for (int wi = 0; wi < 4; ++wi) {
-      const int d = 32 * q + 16 * (wi >> 1) + (lane & 15);
-      const int wv = 4 * (wi & 1) + (lane >> 4);
-      uint32_t word = 0;
+    for (int vsel = 0; vsel < 2; ++vsel) {
+      const int wv = 4 * vsel + (lane >> 4);
+      float inv[16], zr[16];
 #pragma unroll
-      for (int a = 0; a < 16; ++a) {
-        const int p = 16 * wv + a;
-        const int t = 16 * (p & 7) + (p >> 3);
-        word |= qcode(tile_elem(s, t, d), s.sc[t], s.zr[t], 3.0f) << elem_shift(a);
+      for (int a4 = 0; a4 < 4; ++a4) {
+        const float4 i4 = *reinterpret_cast<const float4*>(&s.inv[16 * wv + 4 * a4]);
+        const float4 z4 = *reinterpret_cast<const float4*>(&s.zr[16 * wv + 4 * a4]);
+        inv[4 * a4] = i4.x; inv[4 * a4 + 1] = i4.y; inv[4 * a4 + 2] = i4.z; inv[4 * a4 + 3] = i4.w;
+        zr[4 * a4] = z4.x; zr[4 * a4 + 1] = z4.y; zr[4 * a4 + 2] = z4.z; zr[4 * a4 + 3] = z4.w;
       }
-      w[wi] = word;
+#pragma unroll
+      for (int dsel = 0; dsel < 2; ++dsel) {
+        const int d = 32 * q + 16 * dsel + (lane & 15);
+        uint32_t word = 0;
+#pragma unroll
+        for (int a = 0; a < 16; ++a) {
+          const int p = 16 * wv + a;
+          const int t = 16 * (p & 7) + (p >> 3);
+          word |= qcode(tile_elem(s, t, d), inv[a], zr[a], 3.0f) << elem_shift(a);
+        }
+        w[2 * dsel + vsel] = word;
+      }
     }
     reinterpret_cast<uint4*>(rec + R::vd)[64 * q + lane] = make_uint4(w[0], w[1], w[2], w[3]);
   }
