@@ -2,8 +2,8 @@
 """Benchmark of the Kitty decode hot path on one MI355X.
 
 A step is one pass of the whole hot path over one batch: kitty_append_token (window insert, and the
-page quantizer whenever a window is full) followed by kitty_decode_attention (split-K kernel +
-merge) — one decode step of one attention layer.  Inputs are resident in HBM before the timed
+page quantizer whenever a window is full) followed by kitty_decode_attention — one decode step of one
+attention layer, issued as the single call kitty_decode_step (or as the two calls with --two-calls).  Inputs are resident in HBM before the timed
 region.  Steps rotate over several copies of the cache so that every step streams its records
 from HBM rather than from the 256 MB last-level cache.
 
@@ -41,6 +41,10 @@ def parse():
                     help="graph: each step (4 kernel launches) is replayed from a captured HIP graph")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (scale reference for FETCH_SIZE/WRITE_SIZE)")
+    ap.add_argument("--prewarm-ms", type=float, default=300.0,
+                    help="untimed launches of the streaming kernel before the warm-up steps (clocks and TLBs settle)")
+    ap.add_argument("--two-calls", action="store_true",
+                    help="step = kitty_append_token + kitty_decode_attention instead of the single kitty_decode_step call")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-pairs", type=int, default=0, help="(sequence, kv-head) pairs in the oracle sample (0 = auto)")
     return ap.parse_args()
@@ -138,8 +142,11 @@ def main():
 
     def launch_step(c, j):
         kn, vn = newt[j]
-        kitty.kitty_append_token(layout, caches[c], kn, vn, fresh[c])
-        kitty.kitty_decode_attention(layout, caches[c], qs[j], out, w.sm_scale, ws, args.n_splits)
+        if args.two_calls:
+            kitty.kitty_append_token(layout, caches[c], kn, vn, fresh[c])
+            kitty.kitty_decode_attention(layout, caches[c], qs[j], out, w.sm_scale, ws, args.n_splits)
+        else:
+            kitty.kitty_decode_step(layout, caches[c], kn, vn, fresh[c], qs[j], out, w.sm_scale, ws, args.n_splits)
 
     # one captured graph per cache copy (fixed q / new-token buffers per copy); the kernels read the
     # sequence state from device memory, so the same graph serves every step, flushes included
@@ -180,6 +187,13 @@ def main():
             fresh[c].copy_(torch.arange(B, dtype=torch.int32, device=dev) * max_pages + st[0])
         return step_bytes(payload, st[0], st[1], w)
 
+    # bring the GPU to its steady state first (the first ~100 ms after set-up run ~8 % slower); these launches
+    # do not touch the sequence state
+    t_pre = time.perf_counter()
+    while (time.perf_counter() - t_pre) * 1e3 < args.prewarm_ms:
+        for c in range(n_copies):
+            kitty.kitty_decode_split(layout, caches[c], qs[0], w.sm_scale, ws, args.n_splits)
+        torch.cuda.synchronize()
     for i in range(args.warmup):
         do_step(i)
     torch.cuda.synchronize()
@@ -307,7 +321,7 @@ def main():
         "config": {
             "workload": f"{w.name}: batch {B}, {w.n_q_heads}q/{hkv}kv heads, head_dim 128, context {w.context} "
                         f"({n_pages0} pages + 128-token bf16 window at the first timed step), n_boost {w.n_boost}, "
-                        f"step = append_token + decode_attention ({args.launch} launch)",
+                        f"step = append_token + decode_attention ({'two calls' if args.two_calls else 'kitty_decode_step'}, {args.launch} launch)",
             "n_splits": ns, "min_pages_per_split": pps, "cache_copies": n_copies, "record_bytes": rec_bytes,
             "payload_bytes_per_page": payload, "distinct_source_sequences": nsrc,
         },

@@ -137,6 +137,16 @@ int kitty_decode_merge(const kitty_layout* layout, const kitty_cache* cache, voi
                        int32_t n_splits, int32_t out_dtype, const void* workspace,
                        size_t workspace_bytes, void* hip_stream);
 
+/* One decode step of one layer in a single call: kitty_append_token(k_new, v_new, fresh_page_ids) followed by
+ * kitty_decode_attention(q -> out) (Sec. 4.3 steps 1-3), with the same arguments and results as those two
+ * calls.  When the plan has one page range per (sequence, kv-head) both halves run in one kernel launch (each
+ * block appends its own (sequence, kv-head) share, flushing a full window first, then attends); otherwise the
+ * two calls are made one after the other.  Requires residual_window == page_size. */
+int kitty_decode_step(const kitty_layout* layout, const kitty_cache* cache, const void* k_new,
+                      const void* v_new, const int32_t* fresh_page_ids, const void* q, void* out,
+                      float sm_scale, int32_t n_splits, int32_t out_dtype, void* workspace,
+                      size_t workspace_bytes, void* hip_stream);
+
 /* Static description of an error code. */
 const char* kitty_strerror(int code);
 

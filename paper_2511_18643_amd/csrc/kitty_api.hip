@@ -4,7 +4,6 @@
 #include <type_traits>
 
 #include "kitty_decode.h"
-#include "kitty_quant.h"
 
 namespace {
 
@@ -123,6 +122,15 @@ int fill_decode_params(const kitty_layout* L, const kitty_cache* C, int32_t n_sp
   P->has_window = L->residual_window > 0 ? 1 : 0;
   P->out_dtype = 0;
   P->direct_out = 0;
+  P->k_new = P->v_new = nullptr;
+  P->fresh_page_ids = nullptr;
+  P->pool_w = nullptr;
+  P->page_table_w = nullptr;
+  P->n_pages_w = nullptr;
+  P->resid_k_w = P->resid_v_w = nullptr;
+  P->n_resid_w = nullptr;
+  P->n_pool_pages = C->n_pool_pages;
+  P->rank_metric = L->rank_metric;
   return KITTY_OK;
 }
 
@@ -225,9 +233,17 @@ int kitty_append_token(const kitty_layout* L, const kitty_cache* C, const void* 
 }
 
 namespace {
-// Launches the streaming kernel.  With `out` non-null and a one-range plan the kernel stores the result itself.
+struct StepArgs {   // the append half of a fused step
+  const void* k_new;
+  const void* v_new;
+  const int32_t* fresh_page_ids;
+};
+
+// Launches the streaming kernel.  With `out` non-null and a one-range plan the kernel stores the result itself;
+// with `step` non-null (one-range plans only) it also performs the append first.
 int launch_split(const kitty_layout* L, const kitty_cache* C, const void* q, float sm_scale, int32_t n_splits,
-                 void* workspace, size_t workspace_bytes, void* out, int32_t out_dtype, void* hip_stream, bool* merged) {
+                 void* workspace, size_t workspace_bytes, void* out, int32_t out_dtype, void* hip_stream, bool* merged,
+                 const StepArgs* step) {
   DecodeParams P;
   int rc = fill_decode_params(L, C, n_splits, workspace, workspace_bytes, &P);
   if (rc) return rc;
@@ -239,18 +255,38 @@ int launch_split(const kitty_layout* L, const kitty_cache* C, const void* q, flo
   P.out = out;
   P.out_dtype = out_dtype;
   if (merged) *merged = P.direct_out != 0;
+  if (step) {
+    if (!P.direct_out) return KITTY_ERR_INVALID_ARG;   // callers check the plan first
+    P.k_new = static_cast<const uint16_t*>(step->k_new);
+    P.v_new = static_cast<const uint16_t*>(step->v_new);
+    P.fresh_page_ids = step->fresh_page_ids;
+    P.pool_w = static_cast<uint8_t*>(C->page_pool);
+    P.page_table_w = C->page_table;
+    P.n_pages_w = C->n_pages;
+    P.resid_k_w = static_cast<uint16_t*>(C->resid_k);
+    P.resid_v_w = static_cast<uint16_t*>(C->resid_v);
+    P.n_resid_w = C->n_resid;
+  }
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   const dim3 grid(P.n_splits, L->n_kv_heads, C->batch);
   const bool wide = P.gqa == 8;
   const bool big = waves_per_block(C->max_pages, P.n_splits) == 8;
+  const bool fused = step != nullptr;
   return dispatch_nb16(L->n_boost / 16, [&](auto nb) {
     constexpr int NB = decltype(nb)::value;
-    if (wide) {
-      if (big) hipLaunchKernelGGL((decode_split_kernel<NB, 2, 8>), grid, dim3(512), 0, st, P);
-      else hipLaunchKernelGGL((decode_split_kernel<NB, 2, 4>), grid, dim3(256), 0, st, P);
+    auto go = [&](auto hpl, auto nw, auto fu) {
+      constexpr int HPL = decltype(hpl)::value, NW = decltype(nw)::value;
+      constexpr bool FU = decltype(fu)::value;
+      hipLaunchKernelGGL((decode_split_kernel<NB, HPL, NW, FU>), grid, dim3(64 * NW), 0, st, P);
+    };
+    using I1 = std::integral_constant<int, 1>; using I2 = std::integral_constant<int, 2>;
+    using I4 = std::integral_constant<int, 4>; using I8 = std::integral_constant<int, 8>;
+    if (fused) {
+      if (wide) { if (big) go(I2{}, I8{}, std::true_type{}); else go(I2{}, I4{}, std::true_type{}); }
+      else      { if (big) go(I1{}, I8{}, std::true_type{}); else go(I1{}, I4{}, std::true_type{}); }
     } else {
-      if (big) hipLaunchKernelGGL((decode_split_kernel<NB, 1, 8>), grid, dim3(512), 0, st, P);
-      else hipLaunchKernelGGL((decode_split_kernel<NB, 1, 4>), grid, dim3(256), 0, st, P);
+      if (wide) { if (big) go(I2{}, I8{}, std::false_type{}); else go(I2{}, I4{}, std::false_type{}); }
+      else      { if (big) go(I1{}, I8{}, std::false_type{}); else go(I1{}, I4{}, std::false_type{}); }
     }
     return launch_status();
   });
@@ -259,7 +295,7 @@ int launch_split(const kitty_layout* L, const kitty_cache* C, const void* q, flo
 
 int kitty_decode_split(const kitty_layout* L, const kitty_cache* C, const void* q, float sm_scale, int32_t n_splits,
                        void* workspace, size_t workspace_bytes, void* hip_stream) {
-  return launch_split(L, C, q, sm_scale, n_splits, workspace, workspace_bytes, nullptr, 0, hip_stream, nullptr);
+  return launch_split(L, C, q, sm_scale, n_splits, workspace, workspace_bytes, nullptr, 0, hip_stream, nullptr, nullptr);
 }
 
 int kitty_decode_merge(const kitty_layout* L, const kitty_cache* C, void* out, int32_t n_splits, int32_t out_dtype,
@@ -281,9 +317,31 @@ int kitty_decode_attention(const kitty_layout* L, const kitty_cache* C, const vo
                            void* hip_stream) {
   if (!out || (out_dtype != 0 && out_dtype != 1)) return KITTY_ERR_INVALID_ARG;
   bool merged = false;
-  int rc = launch_split(L, C, q, sm_scale, n_splits, workspace, workspace_bytes, out, out_dtype, hip_stream, &merged);
+  int rc = launch_split(L, C, q, sm_scale, n_splits, workspace, workspace_bytes, out, out_dtype, hip_stream, &merged, nullptr);
   if (rc || merged) return rc;
   return kitty_decode_merge(L, C, out, n_splits, out_dtype, workspace, workspace_bytes, hip_stream);
+}
+
+int kitty_decode_step(const kitty_layout* L, const kitty_cache* C, const void* k_new, const void* v_new,
+                      const int32_t* fresh_page_ids, const void* q, void* out, float sm_scale, int32_t n_splits,
+                      int32_t out_dtype, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int rc = check_layout(L);
+  if (rc) return rc;
+  rc = check_cache(L, C);
+  if (rc) return rc;
+  if (L->residual_window != G) return KITTY_ERR_UNSUPPORTED;
+  if (!k_new || !v_new || !fresh_page_ids || !C->page_pool || !C->page_table) return KITTY_ERR_INVALID_ARG;
+  if (reinterpret_cast<uintptr_t>(k_new) % 16 || reinterpret_cast<uintptr_t>(v_new) % 16) return KITTY_ERR_INVALID_ARG;
+  if (!out || (out_dtype != 0 && out_dtype != 1) || n_splits < 0) return KITTY_ERR_INVALID_ARG;
+  int32_t ns, mp;
+  plan_splits(L, C->batch, C->max_pages, n_splits, &ns, &mp);
+  if (ns != 1) {   // several ranges per sequence: a flushed page would have to cross blocks; take the two-call path
+    rc = kitty_append_token(L, C, k_new, v_new, fresh_page_ids, hip_stream);
+    if (rc) return rc;
+    return kitty_decode_attention(L, C, q, out, sm_scale, n_splits, out_dtype, workspace, workspace_bytes, hip_stream);
+  }
+  const StepArgs step{k_new, v_new, fresh_page_ids};
+  return launch_split(L, C, q, sm_scale, n_splits, workspace, workspace_bytes, out, out_dtype, hip_stream, nullptr, &step);
 }
 
 const char* kitty_strerror(int code) {

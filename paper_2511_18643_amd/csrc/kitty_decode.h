@@ -12,8 +12,10 @@
 #pragma once
 #include <climits>
 #include <cstddef>
+#include <type_traits>
 
 #include "kitty_common.h"
+#include "kitty_quant.h"
 
 namespace kitty {
 
@@ -37,6 +39,17 @@ struct DecodeParams {
   int32_t batch, max_pages, n_q_heads, n_kv_heads, gqa;
   int32_t n_splits, min_pages, has_window, out_dtype;
   int32_t direct_out;    // split kernel with n_splits == 1: normalise and store `out` itself, no partials
+  // fused step (append, then attention, one launch; only with one range per sequence and kv-head)
+  const uint16_t* k_new;
+  const uint16_t* v_new;
+  const int32_t* fresh_page_ids;
+  uint8_t* pool_w;
+  int32_t* page_table_w;
+  int32_t* n_pages_w;
+  uint16_t* resid_k_w;
+  uint16_t* resid_v_w;
+  int32_t* n_resid_w;
+  int32_t n_pool_pages, rank_metric;
 };
 
 // Page ranges of one sequence: with np pages and a window of r rows, the sequence uses
@@ -203,10 +216,11 @@ struct MergeScratch {
   float l[2 * NW][4 * HPL];
 };
 
-template <int NB16, int HPL, int NW>
+template <int NB16, int HPL, int NW, bool FUSED>
 union __attribute__((aligned(16))) DecodeSmem {
   WaveScratch<NB16, HPL> w[NW];
   MergeScratch<HPL, NW> mg;
+  typename std::conditional<FUSED, QuantSmem, int>::type quant;   // the fused step may flush a window first
 };
 
 // Running state of one wavefront on the packed-page path and the work done per page.
@@ -450,13 +464,19 @@ struct PageWorker {
 template <int NB16, int HPL>
 constexpr int decode_waves_per_simd() { return 2; }
 
-template <int NB16, int HPL, int NW>
+//
+// FUSED: the block first performs this (sequence, kv-head)'s share of kitty_append_token (flush a full window
+// into the fresh page, store the new token), then attends over the result; needs one range per (sequence,
+// kv-head), i.e. grid.x == 1 and direct_out.  The new token's row is taken from k_new / v_new directly, a
+// freshly written record is fenced before it is read back, and the sequence state is advanced by the block of
+// the sequence that finishes last (ticket in bits 8.. of n_resid, as in append_token_kernel).
+template <int NB16, int HPL, int NW, bool FUSED>
 __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void decode_split_kernel(DecodeParams p) {
   using R = Rec<NB16>;
   constexpr int RPH = 4 / HPL;
   constexpr int NH = 4 * HPL;              // heads handled by the block
 
-  __shared__ DecodeSmem<NB16, HPL, NW> smem;
+  __shared__ DecodeSmem<NB16, HPL, NW, FUSED> smem;
 
   const int slot = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x;
@@ -464,10 +484,47 @@ __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void
   const int l = tid & 63, j = l & 15, gi = l >> 4;
   const int g = p.gqa;
 
-  const int np = min(p.n_pages[b], p.max_pages);
-  const int r = p.has_window ? min(p.n_resid[b], G) : 0;
+  int np = min(p.n_pages[b], p.max_pages);
+  int r = p.has_window ? min(p.n_resid[b] & ((1 << TICKET_SHIFT) - 1), G) : 0;
+  // fused append: state before the step, what the step does to it
+  const int nr_old = r, np_old = np;
+  int newrow = -1;              // window row of the token appended by this step (its data comes from k_new/v_new)
+  int32_t fresh_pid = -1;       // page written by this step's flush (not yet in the page table)
+  bool ok = true, flush = false;
+  const uint16_t* knew_h = nullptr;
+  const uint16_t* vnew_h = nullptr;
+  if constexpr (FUSED) {
+    const int32_t pid = p.fresh_page_ids[b];
+    flush = nr_old >= G;
+    ok = !flush || (np_old < p.max_pages && pid >= 0 && pid < p.n_pool_pages);
+    uint16_t* wkw = p.resid_k_w + ((size_t)b * p.n_kv_heads + h) * (size_t)(G * D);
+    uint16_t* wvw = p.resid_v_w + ((size_t)b * p.n_kv_heads + h) * (size_t)(G * D);
+    knew_h = p.k_new + ((size_t)b * p.n_kv_heads + h) * D;
+    vnew_h = p.v_new + ((size_t)b * p.n_kv_heads + h) * D;
+    if (ok) {
+      if (flush) {
+        uint8_t* rec = p.pool_w + ((size_t)pid * p.n_kv_heads + h) * (size_t)R::bytes;
+        quantize_page<NB16>(smem.quant, wkw, wvw, D, rec, p.rank_metric);
+        __threadfence();          // the record is read back by this block's wavefronts
+        __syncthreads();
+        fresh_pid = pid;
+        np = np_old + 1;
+        r = 1;
+        newrow = 0;
+      } else {
+        r = nr_old + 1;
+        newrow = nr_old;
+      }
+      if (tid < 32) {             // keep the token for the following steps
+        const int part = tid & 15;
+        const uint16_t* src = (tid < 16 ? knew_h : vnew_h) + part * 8;
+        uint16_t* dst = (tid < 16 ? wkw : wvw) + (size_t)newrow * D + part * 8;
+        *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
+      }
+    }
+  }
   const int sb = active_splits(np, r, p.n_splits, p.min_pages);
-  if (slot >= sb) {
+  if (slot >= sb) {   // nothing to attend over (never the case in a fused step that appended a token)
     if (p.direct_out && slot == 0) {   // empty sequence: the result is defined as zeros
       for (int o = tid; o < g * D; o += 64 * NW) {
         const size_t oi = ((size_t)b * p.n_q_heads + (size_t)h * g) * D + o;
@@ -487,10 +544,12 @@ __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void
     const int32_t* pt = p.page_table + (size_t)b * p.max_pages;
     const size_t rec_stride = (size_t)p.n_kv_heads * R::bytes;
     const uint8_t* pool_h = p.pool + (size_t)h * R::bytes;
-    auto rec_of = [&](int idx) { return pool_h + (size_t)pt[idx] * rec_stride; };
+    auto rec_of = [&](int idx) {
+      const int32_t id = (FUSED && idx == np_old && fresh_pid >= 0) ? fresh_pid : pt[idx];
+      return pool_h + (size_t)id * rec_stride;
+    };
 
     // one register buffer: each piece of the next page is requested when the current page no longer needs it.
-    // The first page is requested before anything else so that its latency overlaps the set-up below.
     PageRegs<NB16> pg{};
     int idx = p0 + w;
     uint4 m0 = make_uint4(0, 0, 0, 0);
@@ -546,7 +605,8 @@ __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int row = min(t0 + 4 * i + gi, t1 - 1);
-      vrow[i] = *reinterpret_cast<const uint4*>(wv + (size_t)row * D + 8 * j);
+      const uint16_t* vr = (FUSED && row == newrow) ? vnew_h : wv + (size_t)row * D;
+      vrow[i] = *reinterpret_cast<const uint4*>(vr + 8 * j);
     }
     // A operand: query rows; row hd*RPH carries head hd, the other rows are zero
     const int arow_head = j / RPH;
@@ -563,10 +623,11 @@ __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void
     for (int tt = 0; tt < 2; ++tt) {
       const int t = t0 + 16 * tt + j;
       const int trow = min(t, t1 - 1);
+      const uint16_t* kr = (FUSED && trow == newrow) ? knew_h : wk + (size_t)trow * D;
       v4f c = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int mm = 0; mm < 4; ++mm) {
-        const uint4 raw = *reinterpret_cast<const uint4*>(wk + (size_t)trow * D + 32 * mm + 8 * gi);
+        const uint4 raw = *reinterpret_cast<const uint4*>(kr + 32 * mm + 8 * gi);
         c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aq[mm], __builtin_bit_cast(v8bf, raw), c, 0, 0, 0);
       }
 #pragma unroll
@@ -661,6 +722,25 @@ __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void
     } else {
       part[hd * WS_STRIDE + d] = a;
       if (d == 0) { part[hd * WS_STRIDE + D] = M; part[hd * WS_STRIDE + D + 1] = L; }
+    }
+  }
+  if constexpr (FUSED) {
+    __syncthreads();
+    if (tid == 0) {
+      const int old = atomicAdd(&p.n_resid_w[b], 1 << TICKET_SHIFT);
+      if ((old >> TICKET_SHIFT) == p.n_kv_heads - 1) {   // every block of this sequence is done with the old state
+        int new_nr = nr_old;
+        if (ok) {
+          if (flush) {
+            p.page_table_w[(size_t)b * p.max_pages + np_old] = fresh_pid;
+            p.n_pages_w[b] = np_old + 1;
+            new_nr = 1;
+          } else {
+            new_nr = nr_old + 1;
+          }
+        }
+        atomicExch(&p.n_resid_w[b], new_nr);
+      }
     }
   }
 }

@@ -21,7 +21,7 @@ ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = -1, -2, -3, -4
 EXPORTS = (
     "kitty_page_bytes", "kitty_page_payload_bytes", "kitty_decode_plan", "kitty_decode_workspace_bytes",
     "kitty_quantize_pages", "kitty_append_token", "kitty_decode_attention", "kitty_decode_split",
-    "kitty_decode_merge", "kitty_strerror",
+    "kitty_decode_merge", "kitty_decode_step", "kitty_strerror",
 )
 
 
@@ -72,6 +72,8 @@ def lib() -> C.CDLL:
         L.kitty_decode_split.argtypes = [LP, CP, vp, C.c_float, i32, vp, sz, vp]
         L.kitty_decode_merge.restype = C.c_int
         L.kitty_decode_merge.argtypes = [LP, CP, vp, i32, i32, vp, sz, vp]
+        L.kitty_decode_step.restype = C.c_int
+        L.kitty_decode_step.argtypes = [LP, CP, vp, vp, vp, vp, vp, C.c_float, i32, i32, vp, sz, vp]
         L.kitty_strerror.restype = C.c_char_p
         L.kitty_strerror.argtypes = [C.c_int]
         _lib = L
@@ -166,6 +168,17 @@ def kitty_decode_attention(layout: KittyLayout, cache: Cache, q, out, sm_scale: 
                                       out_dtype, _ptr(workspace), workspace.numel() * workspace.element_size(),
                                       _stream(stream))
     _check(rc, "kitty_decode_attention")
+
+
+def kitty_decode_step(layout: KittyLayout, cache: Cache, k_new, v_new, fresh_page_ids, q, out, sm_scale: float,
+                      workspace, n_splits: int = 0, stream=None) -> None:
+    """kitty_append_token + kitty_decode_attention in one call (one launch when the plan has one range)."""
+    cs = cache.struct()
+    out_dtype = 0 if out.dtype == torch.bfloat16 else 1
+    rc = lib().kitty_decode_step(C.byref(layout), C.byref(cs), _ptr(k_new), _ptr(v_new), _ptr(fresh_page_ids),
+                                 _ptr(q), _ptr(out), sm_scale, n_splits, out_dtype, _ptr(workspace),
+                                 workspace.numel() * workspace.element_size(), _stream(stream))
+    _check(rc, "kitty_decode_step")
 
 
 def kitty_decode_split(layout: KittyLayout, cache: Cache, q, sm_scale: float, workspace, n_splits: int = 0,

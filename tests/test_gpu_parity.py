@@ -248,3 +248,41 @@ def test_c3_full_size_sampled():
 
 def test_c4_full_size_sampled():
     _full_size_case("c4", 1, [(0, 0), (7, 5)], 1e-3)
+
+
+# ------------------------------------------------------------------ fused step (append + attention in one call)
+@pytest.mark.parametrize("max_pages,n_splits", [(4, 0), (40, 1), (4, 2)])
+def test_decode_step_matches_append_then_attention(max_pages, n_splits):
+    """kitty_decode_step against the oracle's append followed by its attention, across flush boundaries.
+    (4, 0): one launch, 4-wavefront blocks; (40, 1): one launch, 8-wavefront blocks; (4, 2): two-call path."""
+    import torch
+    from paper_2511_18643_amd import kitty
+    w = synth.scaled(synth.WORKLOADS["c2"], batch=4, n_q_heads=8, n_kv_heads=2, context=0)
+    start = [0, 127, 128, 2 * 128 + 100]
+    k0, v0 = H.gen_sequences(w, start)
+    oc = H.oracle_cache(w, start, k0, v0, max_pages)
+    layout, gc = H.gpu_cache(w, start, k0, v0, max_pages)
+    ns, _ = kitty.kitty_decode_plan(layout, 4, max_pages, n_splits)
+    assert ns == (2 if n_splits == 2 else 1)
+    ws = kitty.new_workspace(layout, 4, max_pages, n_splits)
+    out = torch.empty((4, 8, 128), dtype=torch.float32, device="cuda")
+    for step in range(1, 140):
+        kn, vn = synth.new_token(w, step)
+        q = synth.query(w, step)
+        fresh = np.array([b * max_pages + int(oc.n_pages[b]) for b in range(4)], np.int32)
+        oc.append_token(kn, vn, fresh)
+        kitty.kitty_decode_step(layout, gc, H.bf16_tensor(kn), H.bf16_tensor(vn), torch.from_numpy(fresh).cuda(),
+                                H.bf16_tensor(q), out, w.sm_scale, ws, n_splits)
+        if step in (1, 2, 28, 29, 127, 128, 129, 130, 139):
+            torch.cuda.synchronize()
+            assert np.array_equal(gc.n_pages.cpu().numpy(), oc.n_pages), step
+            assert np.array_equal(gc.n_resid.cpu().numpy(), oc.n_resid), step
+            assert np.array_equal(gc.page_table.cpu().numpy()[:, :max_pages], oc.page_table), step
+            check_pool(w, None, oc, gc)
+            for b in range(4):
+                rr = int(oc.n_resid[b])
+                gk = gc.resid_k[b, :, :rr].view(torch.int16).cpu().numpy().view(np.uint16)
+                assert np.array_equal(gk, oc.resid_k[b, :, :rr]), (step, b)
+            want = oc.decode_attention(q, w.sm_scale)
+            got = out.cpu().numpy()
+            assert np.abs(got - want).max() <= TOL_FP32, step
