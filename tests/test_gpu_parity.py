@@ -286,3 +286,43 @@ def test_decode_step_matches_append_then_attention(max_pages, n_splits):
             want = oc.decode_attention(q, w.sm_scale)
             got = out.cpu().numpy()
             assert np.abs(got - want).max() <= TOL_FP32, step
+
+
+def test_variable_length_decode_loop_c5_shape():
+    """Config-5-shaped loop at reduced scale: variable-length batch (seeded uniform lengths), prefill through
+    kitty_quantize_pages, then decode steps (append with flushes at different steps per sequence + attention),
+    two "layers" sharing nothing.  State, flushed records and outputs are checked against the oracle."""
+    import torch
+    from paper_2511_18643_amd import kitty
+    rng = np.random.default_rng(55)
+    B = 6
+    lengths = [int(x) for x in rng.integers(1024, 4096, size=B)]
+    lengths[0] = 1024; lengths[1] = 4095          # the ends of the range, one flush almost due
+    max_pages = 4096 // 128 + 2
+    for layer in range(2):
+        w = synth.scaled(synth.WORKLOADS["c2"], batch=B, n_q_heads=8, n_kv_heads=2, context=0, seed=500 + layer)
+        k0, v0 = H.gen_sequences(w, lengths)
+        oc = H.oracle_cache(w, lengths, k0, v0, max_pages)
+        layout, gc = H.gpu_cache(w, lengths, k0, v0, max_pages)
+        check_pool(w, None, oc, gc)
+        ws = kitty.new_workspace(layout, B, max_pages)
+        out = torch.empty((B, 8, 128), dtype=torch.float32, device="cuda")
+        flushed_total = 0
+        for step in range(1, 131):
+            kn, vn = synth.new_token(w, step)
+            q = synth.query(w, step)
+            fresh = np.array([b * max_pages + int(oc.n_pages[b]) for b in range(B)], np.int32)
+            flushed_total += oc.append_token(kn, vn, fresh)
+            kitty.kitty_decode_step(layout, gc, H.bf16_tensor(kn), H.bf16_tensor(vn), torch.from_numpy(fresh).cuda(),
+                                    H.bf16_tensor(q), out, w.sm_scale, ws)
+            if step % 43 == 0 or step in (1, 2, 130):
+                torch.cuda.synchronize()
+                assert np.array_equal(gc.n_pages.cpu().numpy(), oc.n_pages), (layer, step)
+                assert np.array_equal(gc.n_resid.cpu().numpy(), oc.n_resid), (layer, step)
+                want = oc.decode_attention(q, w.sm_scale)
+                assert np.abs(out.cpu().numpy() - want).max() <= TOL_FP32, (layer, step)
+        # a window holding r0 rows flushes floor((r0 + n - 1) / 128) times during n appends
+        assert flushed_total == sum((w.pages_and_resid(n)[1] + 130 - 1) // 128 for n in lengths)
+        torch.cuda.synchronize()
+        check_pool(w, None, oc, gc)
+        assert np.array_equal(gc.page_table.cpu().numpy()[:, :max_pages], oc.page_table)
