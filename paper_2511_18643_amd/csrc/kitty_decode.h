@@ -201,9 +201,9 @@ __device__ __forceinline__ void wave_lds_fence() {
 template <int NB16, int HPL>
 struct WaveScratch {
   uint32_t nbuf[4 * HPL][D];                     // integer image (raw bits) of q*s per (head, channel), for the boost gather
-  uint8_t abuf[16][144];                         // rows (head, term) x channel
-  uint8_t bbuf[16][16 * (NB16 ? NB16 : 1) + 16];  // rows (head, term) x boost slot
-  uint8_t pbuf[16][144];                         // rows (head, term) x position
+  uint8_t abuf[16 * HPL][144];                         // rows (head, term) x channel; one 16-row matrix per pass
+  uint8_t bbuf[16 * HPL][16 * (NB16 ? NB16 : 1) + 16];  // rows (head, term) x boost slot
+  uint8_t pbuf[16 * HPL][144];                         // rows (head, term) x position
   float pw[32][8];                               // window path: softmax weights [token][head]
   uint8_t meta[4][256];                          // k_scale, k_zero, v_scale, v_zero of the page being processed
   uint8_t zero[16];
@@ -228,28 +228,46 @@ union __attribute__((aligned(16))) DecodeSmem {
 // or positions 8j..8j+7 (V side) of heads gi*HPL + e; in the matrix role it is row/column j of
 // k-block gi.  Both roles put head gi*HPL + e in lane group gi, so no cross-group traffic is needed.
 //
-// With three byte terms (HPL == 1) the code planes are unpacked with masks only (unpack16_w), which
+// With three byte terms the code planes are unpacked with masks only (unpack16_w), which
 // leaves elements 4..7 of a word multiplied by 4 and elements 8..11 by 16.  The compact lane owns
 // elements 8*(j&1)..8*(j&1)+7, i.e. its first four values have weight wA and its last four wB with
 // (wA, wB) = (1, 4) for even j and (16, 1) for odd j; it divides its values by that weight before
 // taking the integer image, and keeps sums and maxima of unweighted values by recombining two halves.
+// Groups of eight query heads (HPL == 2) carry two terms (16-bit images, plain unpack); see THIRD_PASS.
 template <int NB16, int HPL>
 struct PageWorker {
-  static constexpr int TR = HPL == 1 ? 3 : 2;     // byte terms per value
-  static constexpr int RPH = 4 / HPL;             // matrix rows per head
-  static constexpr bool WEIGHTED = HPL == 1;      // mask-only unpack (needs the precision of three terms)
+  // Eight-head groups: a third byte term needs 24 matrix rows, i.e. a second MFMA pass over the same code
+  // operand.  Measured on the 128k-context workload it costs 20 % of the kernel's throughput (the matrix
+  // pipe and the register file become the limiters) for a maximum error of 1e-4 instead of 8e-4, both within
+  // the 2e-3 bound; it is therefore compiled out.
+  static constexpr bool THIRD_PASS = false;
+  static constexpr int TR = (HPL == 1 || THIRD_PASS) ? 3 : 2;     // byte terms per value
+  static constexpr bool WEIGHTED = TR == 3;       // mask-only unpack (relies on the precision of three terms)
+  static constexpr bool TWO_PASS = HPL == 2 && THIRD_PASS;
   static constexpr float NLIM = TR == 3 ? 1048000.0f : 32000.0f;   // bound of the integer images
+
+  // Matrix row of term t of head hd.  Four heads: rows 4hd + t of one matrix.  Eight heads: terms 0, 1 in
+  // rows 2hd + t of the first matrix, term 2 in row 4(hd/2) + hd%2 of a second matrix (rows 16..31) that a
+  // second MFMA pass multiplies with the same code operand; either way the terms of heads gi*HPL + e come
+  // out in lane group gi.
+  static __device__ __forceinline__ int term_row(int hd, int t) {
+    if constexpr (HPL == 1) return 4 * hd + t;
+    else return t < 2 ? 2 * hd + t : 16 + 4 * (hd >> 1) + (hd & 1);   // t == 2 only with the second pass
+  }
 
   WaveScratch<NB16, HPL>& ws;
   const int j, gi;
-  const uint8_t* a_ptr;      // A operand of the logits: row j, k-block gi
+  const uint8_t* a_ptr;      // A operand of the logits: row j, k-block gi (second matrix 16 rows further)
   const uint8_t* p_ptr;      // A operand of the Value sum
   const uint8_t* b_ptr[4];   // boost rows for tile kb (zeros unless gi == kb)
   LaneOffsets lo;            // byte offsets of the lane into a record
   float wA, wB, oA, oB;      // weights of the lane's two halves and their log2
-  float qv[HPL][8];          // q * sm_scale * log2(e) (divided by the weight if WEIGHTED), compact layout
+  float qv[HPL][8];          // q * sm_scale * log2(e) divided by the weight, compact layout
   float m_run[HPL], l_run[HPL], z_run[HPL];
   float acc[HPL][8];         // channel 16*Td + j
+
+  static constexpr int A_PASS = 16 * 144;                           // bytes between the two matrices
+  static constexpr int B_PASS = 16 * (16 * (NB16 ? NB16 : 1) + 16);
 
   __device__ __forceinline__ PageWorker(WaveScratch<NB16, HPL>& ws_, int l)
       : ws(ws_), j(l & 15), gi(l >> 4), lo(lane_offsets<NB16>(l)) {
@@ -310,9 +328,7 @@ struct PageWorker {
         bsA = fmaf(qv[e][k], kz[k], bsA);
         bsB = fmaf(qv[e][k + 4], kz[k + 4], bsB);
       }
-      float amax, bsum;
-      if constexpr (WEIGHTED) { amax = fmaxf(amaxA * wA, amaxB * wB); bsum = fmaf(bsA, wA, bsB * wB); }
-      else { amax = fmaxf(amaxA, amaxB); bsum = bsA + bsB; }
+      float amax = fmaxf(amaxA * wA, amaxB * wB), bsum = fmaf(bsA, wA, bsB * wB);   // wA = wB = 1 if not WEIGHTED
       amax = fmaxf(row_max_nonneg(amax), 1e-30f);
       bias[e] = row_sum(bsum);
       const float alpha = NLIM * __builtin_amdgcn_rcpf(amax);
@@ -324,7 +340,7 @@ struct PageWorker {
       split_terms<TR>(u, tw);
       const int hd = gi * HPL + e;
 #pragma unroll
-      for (int t = 0; t < TR; ++t) *reinterpret_cast<uint2*>(&ws.abuf[hd * RPH + t][8 * j]) = tw[t];
+      for (int t = 0; t < TR; ++t) *reinterpret_cast<uint2*>(&ws.abuf[term_row(hd, t)][8 * j]) = tw[t];
       if constexpr (NB16 > 0) {
         *reinterpret_cast<uint4*>(&ws.nbuf[hd][8 * j]) = make_uint4(u[0], u[1], u[2], u[3]);
         *reinterpret_cast<uint4*>(&ws.nbuf[hd][8 * j + 4]) = make_uint4(u[4], u[5], u[6], u[7]);
@@ -343,10 +359,10 @@ struct PageWorker {
         for (int e = 0; e < HPL; ++e) {
           const int hd = gi * HPL + e;
           uint32_t nn = ws.nbuf[hd][ch];
-          if constexpr (WEIGHTED) nn = ((nn - 0x4b400000u) << sh) + 0x4b400000u;   // undo the division: exact multiple
-          ws.bbuf[hd * RPH + 0][16 * s + j] = (uint8_t)nn;
-          ws.bbuf[hd * RPH + 1][16 * s + j] = (uint8_t)((nn + T1_ADD) >> 8);
-          if constexpr (TR == 3) ws.bbuf[hd * RPH + 2][16 * s + j] = (uint8_t)((nn + T2_ADD) >> 16);
+          nn = ((nn - 0x4b400000u) << sh) + 0x4b400000u;   // undo the division: exact multiple
+          ws.bbuf[term_row(hd, 0)][16 * s + j] = (uint8_t)nn;
+          ws.bbuf[term_row(hd, 1)][16 * s + j] = (uint8_t)((nn + T1_ADD) >> 8);
+          if constexpr (TR == 3) ws.bbuf[term_row(hd, 2)][16 * s + j] = (uint8_t)((nn + T2_ADD) >> 16);
         }
       }
       wave_lds_fence();
@@ -354,29 +370,47 @@ struct PageWorker {
     // ================= C: logits for 128 tokens x heads on the int8 matrix cores =================
     const v4i a0 = *reinterpret_cast<const v4i*>(a_ptr);
     const v4i a1 = *reinterpret_cast<const v4i*>(a_ptr + 64);
-    v4i dq[8];
+    v4i a0x = {0, 0, 0, 0}, a1x = {0, 0, 0, 0};
+    if constexpr (TWO_PASS) {
+      a0x = *reinterpret_cast<const v4i*>(a_ptr + A_PASS);
+      a1x = *reinterpret_cast<const v4i*>(a_ptr + A_PASS + 64);
+    }
+    v4i dq[8], dqx[TWO_PASS ? 8 : 1];
 #pragma unroll
     for (int T = 0; T < 8; ++T) {
       const uint4 ld = pg.kd[T >> 1];
       const uint32_t w0 = (T & 1) ? ld.z : ld.x, w1 = (T & 1) ? ld.w : ld.y;
+      const v4i b0 = unpack(w0), b1 = unpack(w1);
       v4i c = {0, 0, 0, 0};
-      c = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0, unpack(w0), c, 0, 0, 0);
-      c = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1, unpack(w1), c, 0, 0, 0);
+      c = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0, b0, c, 0, 0, 0);
+      c = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1, b1, c, 0, 0, 0);
       dq[T] = c;
+      if constexpr (TWO_PASS) {
+        v4i cx = {0, 0, 0, 0};
+        cx = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0x, b0, cx, 0, 0, 0);
+        cx = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1x, b1, cx, 0, 0, 0);
+        dqx[T] = cx;
+      }
     }
     if constexpr (NB16 > 0) {
 #pragma unroll
       for (int s = 0; s < NB16; ++s) {
         // tile 4u+kb of the boost plane lives in the lanes of k-block kb: feed A only to that block
-        v4i ab[4];
+        v4i ab[4], abx[TWO_PASS ? 4 : 1];
 #pragma unroll
-        for (int kb = 0; kb < 4; ++kb) ab[kb] = *reinterpret_cast<const v4i*>(b_ptr[kb] + (gi == kb ? 16 * s : 0));
+        for (int kb = 0; kb < 4; ++kb) {
+          ab[kb] = *reinterpret_cast<const v4i*>(b_ptr[kb] + (gi == kb ? 16 * s : 0));
+          if constexpr (TWO_PASS) abx[kb] = *reinterpret_cast<const v4i*>(b_ptr[kb] + (gi == kb ? B_PASS + 16 * s : 0));
+        }
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
           const v4i bb = unpack16_x4(u ? pg.kb[s].y : pg.kb[s].x);
 #pragma unroll
-          for (int kb = 0; kb < 4; ++kb)
+          for (int kb = 0; kb < 4; ++kb) {
             dq[4 * u + kb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ab[kb], bb, dq[4 * u + kb], 0, 0, 0);
+            if constexpr (TWO_PASS)
+              dqx[4 * u + kb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(abx[kb], bb, dqx[4 * u + kb], 0, 0, 0);
+          }
         }
       }
     }
@@ -392,7 +426,8 @@ struct PageWorker {
       int nl[8], mxi = INT_MIN;
 #pragma unroll
       for (int T = 0; T < 8; ++T) {
-        if constexpr (TR == 3) nl[T] = join_terms(dq[T][0], dq[T][1], dq[T][2]);
+        if constexpr (HPL == 1) nl[T] = join_terms(dq[T][0], dq[T][1], dq[T][2]);
+        else if constexpr (TWO_PASS) nl[T] = join_terms(dq[T][2 * e], dq[T][2 * e + 1], dqx[T][e]);
         else nl[T] = join_terms(dq[T][2 * e], dq[T][2 * e + 1]);
         mxi = max(mxi, nl[T]);
       }
@@ -412,9 +447,7 @@ struct PageWorker {
         ps[T] = pa * vs[T]; ps[T + 4] = pb * vs[T + 4];
         pmA = fmaxf(pmA, ps[T]); pmB = fmaxf(pmB, ps[T + 4]);
       }
-      float psum, zsum, pmax;
-      if constexpr (WEIGHTED) { psum = fmaf(psA, wA, psB * wB); zsum = fmaf(zsA, wA, zsB * wB); pmax = fmaxf(pmA * wA, pmB * wB); }
-      else { psum = psA + psB; zsum = zsA + zsB; pmax = fmaxf(pmA, pmB); }
+      float psum = fmaf(psA, wA, psB * wB), zsum = fmaf(zsA, wA, zsB * wB), pmax = fmaxf(pmA * wA, pmB * wB);
       l_run[e] = fmaf(l_run[e], corr[e], psum);
       z_run[e] = fmaf(z_run[e], corr[e], zsum);
       pmax = fmaxf(row_max_nonneg(pmax), 1e-30f);
@@ -427,23 +460,34 @@ struct PageWorker {
       split_terms<TR>(u, tw);
       const int hd = gi * HPL + e;
 #pragma unroll
-      for (int t = 0; t < TR; ++t) *reinterpret_cast<uint2*>(&ws.pbuf[hd * RPH + t][8 * j]) = tw[t];
+      for (int t = 0; t < TR; ++t) *reinterpret_cast<uint2*>(&ws.pbuf[term_row(hd, t)][8 * j]) = tw[t];
     }
     wave_lds_fence();
     // ================= E: weighted Value sum on the int8 matrix cores =================
     const v4i pa0 = *reinterpret_cast<const v4i*>(p_ptr);
     const v4i pa1 = *reinterpret_cast<const v4i*>(p_ptr + 64);
+    v4i pa0x = {0, 0, 0, 0}, pa1x = {0, 0, 0, 0};
+    if constexpr (TWO_PASS) {
+      pa0x = *reinterpret_cast<const v4i*>(p_ptr + A_PASS);
+      pa1x = *reinterpret_cast<const v4i*>(p_ptr + A_PASS + 64);
+    }
 #pragma unroll
     for (int Td = 0; Td < 8; ++Td) {
       const uint4 ld = pg.vd[Td >> 1];
       const uint32_t w0 = (Td & 1) ? ld.z : ld.x, w1 = (Td & 1) ? ld.w : ld.y;
-      v4i c = {0, 0, 0, 0};
-      c = __builtin_amdgcn_mfma_i32_16x16x64_i8(pa0, unpack(w0), c, 0, 0, 0);
-      c = __builtin_amdgcn_mfma_i32_16x16x64_i8(pa1, unpack(w1), c, 0, 0, 0);
+      const v4i b0 = unpack(w0), b1 = unpack(w1);
+      v4i c = {0, 0, 0, 0}, cx = {0, 0, 0, 0};
+      c = __builtin_amdgcn_mfma_i32_16x16x64_i8(pa0, b0, c, 0, 0, 0);
+      c = __builtin_amdgcn_mfma_i32_16x16x64_i8(pa1, b1, c, 0, 0, 0);
+      if constexpr (TWO_PASS) {
+        cx = __builtin_amdgcn_mfma_i32_16x16x64_i8(pa0x, b0, cx, 0, 0, 0);
+        cx = __builtin_amdgcn_mfma_i32_16x16x64_i8(pa1x, b1, cx, 0, 0, 0);
+      }
 #pragma unroll
       for (int e = 0; e < HPL; ++e) {
         int ne;
-        if constexpr (TR == 3) ne = join_terms(c[0], c[1], c[2]);
+        if constexpr (HPL == 1) ne = join_terms(c[0], c[1], c[2]);
+        else if constexpr (TWO_PASS) ne = join_terms(c[2 * e], c[2 * e + 1], cx[e]);
         else ne = join_terms(c[2 * e], c[2 * e + 1]);
         acc[e][Td] = fmaf(acc[e][Td], corr[e], (float)ne * inv_beta[e]);
       }
