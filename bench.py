@@ -45,6 +45,8 @@ def parse():
                     help="untimed launches of the streaming kernel before the warm-up steps (clocks and TLBs settle)")
     ap.add_argument("--two-calls", action="store_true",
                     help="step = kitty_append_token + kitty_decode_attention instead of the single kitty_decode_step call")
+    ap.add_argument("--n-boost", type=int, default=-1,
+                    help="override the workload's boosted-channel count (0, 16, 32, 64 or 128): the variant sweep")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-pairs", type=int, default=0, help="(sequence, kv-head) pairs in the oracle sample (0 = auto)")
     return ap.parse_args()
@@ -68,6 +70,22 @@ def recorded_traffic(workload):
     return None
 
 
+def gpu_clocks(busy):
+    """Clock speeds rocm-smi reports while `busy()` keeps the GPU loaded (a child process; None if unusable)."""
+    import subprocess
+    try:
+        pr = subprocess.Popen(["rocm-smi", "-d", "0", "--showclocks", "--json"], stdout=subprocess.PIPE,
+                              stderr=subprocess.DEVNULL, text=True)
+        t0 = time.perf_counter()
+        while pr.poll() is None and time.perf_counter() - t0 < 20.0:
+            busy()
+        txt = pr.communicate(timeout=5)[0]
+        card = next(iter(json.loads(txt).values()))
+        return {k.split()[0]: v.strip("()") for k, v in card.items() if "clock speed" in k}
+    except Exception:
+        return None
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -81,6 +99,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda"
     w = synth.WORKLOADS[args.workload]
+    if args.n_boost >= 0:
+        w = synth.scaled(w, n_boost=args.n_boost)
     layout = kitty.make_layout(w.n_q_heads, w.n_kv_heads, w.n_boost, w.residual_window, w.rank_metric)
     payload = kitty.kitty_page_payload_bytes(layout)
     rec_bytes = kitty.kitty_page_bytes(layout)
@@ -223,6 +243,22 @@ def main():
     torch.cuda.synchronize()
     kern_ms = ev0.elapsed_time(ev1) / n_kern
     kern_gbps = kbytes / n_kern / (kern_ms * 1e-3) / 1e9
+    # spread of single launches (each bracketed by its own event pair; includes ~2 us of event overhead)
+    pairs_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(100)]
+    for i, (a, b_) in enumerate(pairs_ev):
+        a.record()
+        kitty.kitty_decode_split(layout, caches[i % n_copies], qs[i % n_rot], w.sm_scale, ws, args.n_splits)
+        b_.record()
+    torch.cuda.synchronize()
+    single = np.sort(np.array([a.elapsed_time(b_) for a, b_ in pairs_ev]))
+    spread = {"p10_ms": round(float(single[10]), 5), "median_ms": round(float(single[50]), 5),
+              "p90_ms": round(float(single[90]), 5)}
+
+    def busy():
+        for i in range(16):
+            kitty.kitty_decode_split(layout, caches[i % n_copies], qs[0], w.sm_scale, ws, args.n_splits)
+        torch.cuda.synchronize()
+    clocks = gpu_clocks(busy)
 
     # ---- page quantizer on its own (prefill rate), for the record ---------------------------------
     ev0.record()
@@ -329,13 +365,15 @@ def main():
         "decode_tokens_per_s": round(tokens_per_s, 1),
         "roofline": {
             "bound": "hbm", "kernel": "decode_split_kernel", "achieved": round(kern_gbps, 1), "peak": HBM_PEAK_GBPS,
-            "unit": "GB/s", "frac": round(kern_gbps / HBM_PEAK_GBPS, 4), "traffic": recorded_traffic(w.name),
+            "unit": "GB/s", "frac": round(kern_gbps / HBM_PEAK_GBPS, 4), "traffic": recorded_traffic(w.name) if args.n_boost < 0 else None,
             "avg_launch_ms": round(kern_ms, 5), "algorithmic_bytes_per_launch": int(kbytes / n_kern),
+            "single_launch": spread,
         },
         "cpu_baseline": cpu,
         "max_abs_err_vs_oracle_sample": max_err,
         "quantize_pages": {"pages": quant_pages, "ms": round(quant_ms, 4),
                            "input_gbps": round(quant_pages * 65536 / (quant_ms * 1e-3) / 1e9, 1)},
+        "clocks_under_load": clocks,
         "setup_s": {"generate": round(gen_s, 1), "prefill_quantize_all_copies": round(quant_s, 2)},
     }
     print(json.dumps(res))

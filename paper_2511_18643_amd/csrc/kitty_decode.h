@@ -619,10 +619,17 @@ __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void
       load_v<NB16>(pg, rec, pw.lo);
       pw.stage_meta(m0);
       wave_lds_fence();
+      // The two wavefronts that share a SIMD take the higher issue priority in turn, page by page: with equal
+      // priorities the older one wins every conflict and ends its (equal) share of the pages ~6 % earlier,
+      // leaving the block to wait for the younger one.
+      int turn = w / 4;
       for (; idx < p1; idx += NW) {
         const bool has_nx = idx + NW < p1;
+        if (turn & 1) __builtin_amdgcn_s_setprio(1); else __builtin_amdgcn_s_setprio(0);
+        ++turn;
         pw.process(pg, has_nx ? rec_of(idx + NW) : pool_h, has_nx);
       }
+      __builtin_amdgcn_s_setprio(0);
     }
   }
 
