@@ -16,6 +16,10 @@ What it follows (arXiv 2511.18643):
   * Sec. 3.2, Eq. (1)   attention = softmax(Q K^T / sqrt(d)) (then times V)
   * Sec. 4.3            insert new token -> attention -> quantize+pack when the buffer of G
                         full-precision tokens is full (at most once every G steps)
+  * Fig. 1, Sec. 3.1,   the full scheme (`KittyUnitOracle`): Sink of S initial tokens kept in full
+    Sec. 4.3 step (1)   precision for K and V; Key Q-Buffer; Value Local window of the R newest tokens
+                        whose evicted token enters the Value Q-Buffer, so Value pages form R tokens
+                        later than Key pages
 
 Readings taken where the paper is silent (each is listed in the design notes too):
   * quantizer formula: asymmetric min/max, scale = fp16((mx-mn)/qmax), zero = fp16(mn),
@@ -455,6 +459,91 @@ class KittyCacheOracle:
             else:
                 out[b, hq] = softmax_attention(bf16_bits_to_f32(q_bits[b, hq]), k, v, sm_scale)
         return out
+
+
+class KittyUnitOracle:
+    """The complete cache of ONE (sequence, kv-head) unit, buffer by buffer as Fig. 1 and Sec. 4.3 name them.
+
+    Key side:   Sink (first S tokens, full precision) | quantized pages | Q-Buffer (< = G tokens, full precision)
+    Value side: Sink | quantized pages | Q-Buffer (<= G) | Local (the R newest tokens)
+    Step (1) insert:  Sink if it is not full; else K -> Key Q-Buffer, V -> Local, and when Local already
+                      holds R tokens its oldest one moves to the Value Q-Buffer first.
+    Step (2) attention over everything held, quantized parts dequantized per Alg. 1.
+    Step (3) a Q-Buffer holding G tokens is quantized into one page and emptied.
+    With S = 0 and R = 0 this is the single-window machine of `KittyCacheOracle` for one unit.
+    Pages are kept as KPage / VPage objects: nothing here depends on the byte layout of a record.
+    """
+
+    def __init__(self, n_boost, sink=32, local=PAGE_SIZE, rank_metric=0, group=PAGE_SIZE):
+        self.n_boost, self.S, self.R, self.G, self.metric = n_boost, sink, local, group, rank_metric
+        self.sink_k, self.sink_v = [], []          # rows of bf16 bit patterns
+        self.k_pages, self.k_qbuf = [], []
+        self.v_pages, self.v_qbuf, self.v_local = [], [], []
+        self.k_flushes = self.v_flushes = 0
+
+    def insert(self, k_bits, v_bits):              # step (1)
+        if len(self.sink_k) < self.S:
+            self.sink_k.append(np.array(k_bits, np.uint16))
+            self.sink_v.append(np.array(v_bits, np.uint16))
+            return
+        assert len(self.k_qbuf) < self.G and len(self.v_qbuf) < self.G   # guaranteed by step (3)
+        self.k_qbuf.append(np.array(k_bits, np.uint16))
+        if self.R == 0:
+            self.v_qbuf.append(np.array(v_bits, np.uint16))
+            return
+        if len(self.v_local) == self.R:            # keep the window at R tokens: oldest one leaves
+            self.v_qbuf.append(self.v_local.pop(0))
+        self.v_local.append(np.array(v_bits, np.uint16))
+
+    def quantize_if_full(self):                    # step (3)
+        if len(self.k_qbuf) == self.G:
+            self.k_pages.append(quantize_k_page(bf16_bits_to_f32(np.stack(self.k_qbuf)), self.n_boost, self.metric))
+            self.k_qbuf = []
+            self.k_flushes += 1
+        if len(self.v_qbuf) == self.G:
+            self.v_pages.append(quantize_v_page(bf16_bits_to_f32(np.stack(self.v_qbuf))))
+            self.v_qbuf = []
+            self.v_flushes += 1
+
+    def n_tokens(self):
+        nk = len(self.sink_k) + self.G * len(self.k_pages) + len(self.k_qbuf)
+        nv = len(self.sink_v) + self.G * len(self.v_pages) + len(self.v_qbuf) + len(self.v_local)
+        assert nk == nv
+        return nk
+
+    def keys(self):
+        rows = [bf16_bits_to_f32(np.stack(self.sink_k))] if self.sink_k else []
+        rows += [dequant_k(kp) for kp in self.k_pages]
+        if self.k_qbuf:
+            rows.append(bf16_bits_to_f32(np.stack(self.k_qbuf)))
+        return np.concatenate(rows, axis=0) if rows else np.zeros((0, HEAD_DIM), np.float32)
+
+    def values(self):
+        rows = [bf16_bits_to_f32(np.stack(self.sink_v))] if self.sink_v else []
+        rows += [dequant_v(vp) for vp in self.v_pages]
+        for part in (self.v_qbuf, self.v_local):
+            if part:
+                rows.append(bf16_bits_to_f32(np.stack(part)))
+        return np.concatenate(rows, axis=0) if rows else np.zeros((0, HEAD_DIM), np.float32)
+
+    def attention(self, q_bits, sm_scale):         # step (2); q_bits: uint16 [g][D] -> float64 [g][D]
+        k, v = self.keys(), self.values()
+        q_bits = np.atleast_2d(q_bits)
+        if k.shape[0] == 0:
+            return np.zeros((q_bits.shape[0], HEAD_DIM), np.float64)
+        return np.stack([softmax_attention(bf16_bits_to_f32(qr), k, v, sm_scale) for qr in q_bits])
+
+    def step(self, k_bits, v_bits, q_bits, sm_scale):
+        self.insert(k_bits, v_bits)
+        out = self.attention(q_bits, sm_scale)
+        self.quantize_if_full()
+        return out
+
+    def prefill(self, k_bits, v_bits):
+        """State after the given tokens went through steps (1) and (3) one at a time (no attention)."""
+        for kr, vr in zip(k_bits, v_bits):
+            self.insert(kr, vr)
+            self.quantize_if_full()
 
 
 def merge_partials(ms, ls, accs):

@@ -461,3 +461,100 @@ def test_empty_sequence_gives_zeros():
     c = ko.KittyCacheOracle(1, 1, 2, 16, 128, 2, 2, 0)
     out = c.decode_attention(np.zeros((1, 2, 128), np.uint16), 1.0)
     assert np.all(out == 0)
+
+
+# ------------------------------------------------------------------ full scheme: Sink, Q-Buffers, Value Local window
+def _unit_tokens(n, seed):
+    r = np.random.default_rng(seed)
+    k = r.standard_normal((n, 128)).astype(np.float32)
+    k[:, [5, 50, 99]] *= 6.0
+    v = r.standard_normal((n, 128)).astype(np.float32)
+    return ko.f32_to_bf16_bits(k), ko.f32_to_bf16_bits(v)
+
+
+@pytest.mark.parametrize("S,R", [(32, 128), (0, 128), (32, 0), (7, 128)])
+def test_unit_precision_map_closed_form(S, R):
+    """Which tokens are full precision at time n follows in closed form from Fig. 1 and Sec. 4.3:
+    Keys: the first S and everything after the last complete group of G behind the Sink (a group completed at
+    this very step is still in the Q-Buffer during attention).  Values: the same rule applied to the tokens that
+    have left the Local window of the R newest.  Quantized tokens equal the page quantizer run on their group."""
+    G = 128
+    n_total = S + 3 * G + 41
+    kb, vb = _unit_tokens(n_total, 11)
+    u = ko.KittyUnitOracle(16, sink=S, local=R)
+    checked = 0
+    for n in range(1, n_total + 1):
+        u.insert(kb[n - 1], vb[n - 1])
+        if n in (1, S, S + 1, S + G, S + G + 1, S + G + R, S + G + R + 1, S + 2 * G + 5, n_total) and n >= 1:
+            assert u.n_tokens() == n
+            K, V = u.keys(), u.values()
+            post = n - S
+            nk = max((post - 1) // G, 0) if post > 0 else 0
+            ev = max(post - R, 0)
+            nv = max((ev - 1) // G, 0) if ev > 0 else 0
+            for t in range(n):
+                if t < S or t >= S + G * nk:
+                    assert np.array_equal(K[t], ko.bf16_bits_to_f32(kb[t]))
+                if t < S or t >= S + G * nv:
+                    assert np.array_equal(V[t], ko.bf16_bits_to_f32(vb[t]))
+            for i in range(nk):
+                ref = ko.dequant_k(ko.quantize_k_page(ko.bf16_bits_to_f32(kb[S + G * i:S + G * (i + 1)]), 16, 0))
+                assert np.array_equal(K[S + G * i:S + G * (i + 1)], ref)
+            for i in range(nv):
+                ref = ko.dequant_v(ko.quantize_v_page(ko.bf16_bits_to_f32(vb[S + G * i:S + G * (i + 1)])))
+                assert np.array_equal(V[S + G * i:S + G * (i + 1)], ref)
+            if R == G and post > G:
+                assert nv == nk - 1          # Value pages form R tokens after Key pages
+            checked += 1
+        u.quantize_if_full()
+        assert len(u.k_qbuf) < G and len(u.v_qbuf) < G and len(u.v_local) <= max(R, 0)
+    assert checked >= 6
+    assert u.k_flushes == (n_total - S) // G and u.v_flushes == max(n_total - S - R, 0) // G   # once per G steps
+
+
+def test_unit_without_sink_and_local_is_the_single_window_machine():
+    """S = 0, R = 0: the unit oracle and the batch oracle (one residual window) describe the same cache."""
+    n = 2 * 128 + 17
+    kb, vb = _unit_tokens(n, 5)
+    q = ko.f32_to_bf16_bits(np.random.default_rng(6).standard_normal((1, 128)).astype(np.float32))
+    u = ko.KittyUnitOracle(16, sink=0, local=0)
+    c = ko.KittyCacheOracle(1, 1, 1, 16, 128, 4, 4)
+    for t in range(n):
+        c.append_token(kb[t][None, None], vb[t][None, None], np.array([c.n_pages[0]]))
+        got = u.step(kb[t], vb[t], q, 0.09)
+        if t % 37 == 0 or t == n - 1:
+            want = c.decode_attention(q[None], 0.09)[0]
+            assert np.allclose(got, want, rtol=0, atol=1e-12)
+
+
+def test_unit_sink_only_is_plain_attention():
+    """While everything still sits in the Sink (or the full-precision buffers) attention is the textbook one."""
+    kb, vb = _unit_tokens(100, 9)
+    q = ko.f32_to_bf16_bits(np.random.default_rng(10).standard_normal((2, 128)).astype(np.float32))
+    u = ko.KittyUnitOracle(16, sink=32, local=128)
+    u.prefill(kb, vb)
+    got = u.attention(q, 0.1)
+    K, V, Q = (ko.bf16_bits_to_f32(x).astype(np.float64) for x in (kb, vb, q))
+    lg = np.float64(np.float32(0.1)) * (Q @ K.T)
+    p = np.exp(lg - lg.max(axis=1, keepdims=True))
+    p /= p.sum(axis=1, keepdims=True)
+    assert np.allclose(got, p @ V, rtol=0, atol=1e-12)
+
+
+def test_unit_sink_recovers_accuracy_on_sink_heavy_attention():
+    """Sec. 3.1's observation in miniature: when the first tokens draw most of the attention weight, keeping
+    them in full precision removes most of the 2-bit error."""
+    n = 32 + 3 * 128 + 1
+    r = np.random.default_rng(21)
+    k = r.standard_normal((n, 128)).astype(np.float32)
+    v = r.standard_normal((n, 128)).astype(np.float32)
+    qf = r.standard_normal(128).astype(np.float32)
+    k[:32] += 0.35 * qf                              # the initial tokens line up with the query
+    kb, vb, q = ko.f32_to_bf16_bits(k), ko.f32_to_bf16_bits(v), ko.f32_to_bf16_bits(qf[None])
+    exact = ko.softmax_attention(ko.bf16_bits_to_f32(q[0]), ko.bf16_bits_to_f32(kb), ko.bf16_bits_to_f32(vb), 0.0884)
+    errs = {}
+    for S in (0, 32):
+        u = ko.KittyUnitOracle(0, sink=S, local=0)
+        u.prefill(kb, vb)
+        errs[S] = np.abs(u.attention(q, 0.0884)[0] - exact).max()
+    assert errs[32] < 0.5 * errs[0]
