@@ -47,14 +47,22 @@ def parse():
                     help="step = kitty_append_token + kitty_decode_attention instead of the single kitty_decode_step call")
     ap.add_argument("--n-boost", type=int, default=-1,
                     help="override the workload's boosted-channel count (0, 16, 32, 64 or 128): the variant sweep")
+    ap.add_argument("--sink-tokens", type=int, default=0,
+                    help="keep this many initial tokens in full precision (the paper's Sink; parity covered by the tests, "
+                         "the CPU baseline leg is skipped)")
+    ap.add_argument("--v-local", type=int, default=0, choices=[0, 128],
+                    help="128: Values of the newest page are read from the bf16 Local window")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-pairs", type=int, default=0, help="(sequence, kv-head) pairs in the oracle sample (0 = auto)")
     return ap.parse_args()
 
 
-def step_bytes(payload, n_pages, n_resid, w):
-    """Algorithmic bytes of one decode_attention call: records + window rows + q + out."""
-    per_pair = n_pages * payload + n_resid * 128 * 2 * 2
+def step_bytes(payload, n_pages, n_resid, w, sink=0, v_local=0):
+    """Algorithmic bytes of one decode_attention call: records + full-precision rows + q + out.  With the Value
+    Local window the newest page's Values are 128 bf16 rows instead of its 2-bit plane and per-token metadata."""
+    per_pair = n_pages * payload + (n_resid + sink) * 128 * 2 * 2
+    if v_local and n_pages:
+        per_pair += 128 * 128 * 2 - (4096 + 512)
     return w.batch * w.n_kv_heads * per_pair + 2 * w.batch * w.n_q_heads * 128 * 2
 
 
@@ -101,7 +109,12 @@ def main():
     w = synth.WORKLOADS[args.workload]
     if args.n_boost >= 0:
         w = synth.scaled(w, n_boost=args.n_boost)
-    layout = kitty.make_layout(w.n_q_heads, w.n_kv_heads, w.n_boost, w.residual_window, w.rank_metric)
+    S, VL = args.sink_tokens, args.v_local
+    full_scheme = bool(S or VL)
+    if full_scheme:
+        args.no_cpu_baseline = True
+    layout = kitty.make_layout(w.n_q_heads, w.n_kv_heads, w.n_boost, w.residual_window, w.rank_metric,
+                               sink_tokens=S, v_local=VL)
     payload = kitty.kitty_page_payload_bytes(layout)
     rec_bytes = kitty.kitty_page_bytes(layout)
     n_pages0, r0 = w.pages_and_resid()                      # c3: 255 pages + 128 window rows
@@ -145,7 +158,16 @@ def main():
         cache.n_pages.fill_(n_pages0)
         for b in range(B):
             cache.resid_k[b] = kt[b % nsrc, :, n_pages0 * 128:]
-            cache.resid_v[b] = vt[b % nsrc, :, n_pages0 * 128:]
+            if VL:      # the window's half, and the bf16 Value rows of the newest page in the other half
+                cache.resid_v[b, :, n_pages0 & 1] = vt[b % nsrc, :, n_pages0 * 128:]
+                cache.resid_v[b, :, (n_pages0 - 1) & 1] = vt[b % nsrc, :, (n_pages0 - 1) * 128:n_pages0 * 128]
+            else:
+                cache.resid_v[b] = vt[b % nsrc, :, n_pages0 * 128:]
+            if S:       # Sink rows: any tokens of the right distribution (the timed path only reads them)
+                cache.sink_k[b] = kt[b % nsrc, :, :S]
+                cache.sink_v[b] = vt[b % nsrc, :, :S]
+        if S:
+            cache.n_sink.fill_(S)
         cache.n_resid.fill_(r_init)
         caches.append(cache)
         states.append([n_pages0, r_init])
@@ -205,7 +227,7 @@ def main():
             launch_step(c, i % n_rot)
         if flushed:      # the id was consumed: point at the next free slot for the flush 128 steps from now
             fresh[c].copy_(torch.arange(B, dtype=torch.int32, device=dev) * max_pages + st[0])
-        return step_bytes(payload, st[0], st[1], w)
+        return step_bytes(payload, st[0], st[1], w, S, VL)
 
     # bring the GPU to its steady state first (the first ~100 ms after set-up run ~8 % slower); these launches
     # do not touch the sequence state
@@ -238,7 +260,7 @@ def main():
     for i in range(n_kern):
         c = i % n_copies
         kitty.kitty_decode_split(layout, caches[c], qs[i % n_rot], w.sm_scale, ws, args.n_splits)
-        kbytes += step_bytes(payload, states[c][0], states[c][1], w)
+        kbytes += step_bytes(payload, states[c][0], states[c][1], w, S, VL)
     ev1.record()
     torch.cuda.synchronize()
     kern_ms = ev0.elapsed_time(ev1) / n_kern
@@ -356,7 +378,8 @@ def main():
         "data": "synthetic",
         "config": {
             "workload": f"{w.name}: batch {B}, {w.n_q_heads}q/{hkv}kv heads, head_dim 128, context {w.context} "
-                        f"({n_pages0} pages + 128-token bf16 window at the first timed step), n_boost {w.n_boost}, "
+                        f"({n_pages0} pages + 128-token bf16 window at the first timed step"
+                        f"{f' + {S}-token Sink' if S else ''}{', Values of the newest page in the bf16 Local window' if VL else ''}), n_boost {w.n_boost}, "
                         f"step = append_token + decode_attention ({'two calls' if args.two_calls else 'kitty_decode_step'}, {args.launch} launch)",
             "n_splits": ns, "min_pages_per_split": pps, "cache_copies": n_copies, "record_bytes": rec_bytes,
             "payload_bytes_per_page": payload, "distinct_source_sequences": nsrc,
@@ -365,7 +388,7 @@ def main():
         "decode_tokens_per_s": round(tokens_per_s, 1),
         "roofline": {
             "bound": "hbm", "kernel": "decode_split_kernel", "achieved": round(kern_gbps, 1), "peak": HBM_PEAK_GBPS,
-            "unit": "GB/s", "frac": round(kern_gbps / HBM_PEAK_GBPS, 4), "traffic": recorded_traffic(w.name) if args.n_boost < 0 else None,
+            "unit": "GB/s", "frac": round(kern_gbps / HBM_PEAK_GBPS, 4), "traffic": recorded_traffic(w.name) if args.n_boost < 0 and not full_scheme else None,
             "avg_launch_ms": round(kern_ms, 5), "algorithmic_bytes_per_launch": int(kbytes / n_kern),
             "single_launch": spread,
         },

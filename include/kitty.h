@@ -41,6 +41,9 @@ typedef struct kitty_layout {
   int32_t n_q_heads;       /* query heads                                                                */
   int32_t n_kv_heads;      /* KV heads; n_q_heads / n_kv_heads must be 1, 2, 4 or 8                      */
   int32_t rank_metric;     /* channel ranking: 0 = mean |x| over the page (Eq. 2), 1 = max - min         */
+  int32_t sink_tokens;     /* S: initial tokens kept in full precision for K and V (Fig. 1, Sec. 3.1): 0..128 */
+  int32_t v_local;         /* Value Local window (Fig. 1, Sec. 4.3 step 1): 0 = off, 128 = the Values of the newest
+                              page are read in full precision until the next page forms; needs R = 128       */
 } kitty_layout;
 
 /* One batch's cache.  All pointers are device pointers.
@@ -50,8 +53,12 @@ typedef struct kitty_cache {
   int32_t* page_table;   /* [batch][max_pages] physical page ids in token order                          */
   int32_t* n_pages;      /* [batch] packed pages of each sequence, 0..max_pages                          */
   void*    resid_k;      /* bf16 [batch][n_kv_heads][R][D] newest tokens not yet in a page; NULL if R=0  */
-  void*    resid_v;      /* same for Values                                                              */
+  void*    resid_v;      /* same for Values; with v_local: bf16 [batch][n_kv_heads][2][R][D], the rows of page i
+                            (and, before that, of the tokens that will form it) in half i & 1             */
   int32_t* n_resid;      /* [batch] valid rows of the window, 0..R; NULL if R=0                          */
+  void*    sink_k;       /* bf16 [batch][n_kv_heads][S][D] first S tokens of every sequence; NULL if S=0 */
+  void*    sink_v;       /* same for Values                                                              */
+  int32_t* n_sink;       /* [batch] valid Sink rows, 0..S; NULL if S=0                                   */
   int32_t  batch;
   int32_t  max_pages;    /* row length of page_table                                                     */
   int32_t  n_pool_pages;
@@ -102,19 +109,26 @@ int kitty_quantize_pages(const kitty_layout* layout, const void* k_src, const vo
 /* Insert one new token per sequence (Sec. 4.3 steps 1 and 3, seen from the following step).
  *   k_new, v_new     device bf16 [batch][n_kv_heads][D].
  *   fresh_page_ids   device int32 [batch]; entry b is consumed only if sequence b flushes.
- * For each sequence b: if n_resid[b] == R the window is first quantized into page
+ * For each sequence b: while n_sink[b] < S the token is stored in the Sink and nothing else changes.
+ * Otherwise: if n_resid[b] == R the window is first quantized into page
  * fresh_page_ids[b], that id is appended to the page table, and the window restarts empty; then the
  * new token is stored in the window.  Attention therefore always sees the newest token in full
  * precision, and a sequence flushes once every G appends.  If a flush is due but the page table
  * is full or the fresh id is outside the pool, that sequence is left unchanged.
+ * With v_local the Value rows of the tokens that will form page i are stored in half i & 1 of resid_v; a
+ * flush quantizes Keys and Values of the page together, and the bf16 Value rows stay in their half, where
+ * attention reads them instead of the record's Value plane until page i+1 forms.  This holds the same tokens
+ * in full precision as a Local window of the R newest tokens in front of a Value buffer of G tokens (Sec. 4.3
+ * step 1), and per-token Value codes do not depend on when they are computed.
  * Requires residual_window == page_size. */
 int kitty_append_token(const kitty_layout* layout, const kitty_cache* cache, const void* k_new,
                        const void* v_new, const int32_t* fresh_page_ids, void* hip_stream);
 
 /* Decode attention for one new query token per sequence (Sec. 4.3 step 2; Eq. 1), read directly
  * from the packed records and the bf16 window:
- *   out[b][hq] = softmax(sm_scale * q[b][hq] . K^T) V   over pages in page-table order, then the
- * window rows 0..n_resid-1, with kv-head = hq / (n_q_heads/n_kv_heads).
+ *   out[b][hq] = softmax(sm_scale * q[b][hq] . K^T) V   over the Sink rows 0..n_sink-1, the pages in
+ * page-table order, then the window rows 0..n_resid-1, with kv-head = hq / (n_q_heads/n_kv_heads).  With
+ * v_local the Values of the last page are taken from half (n_pages-1) & 1 of resid_v.
  *   q          device bf16 [batch][n_q_heads][D], 16-byte aligned.
  *   out        device, same shape; bf16 if out_dtype == 0, fp32 if out_dtype == 1.
  *   n_splits   0 = automatic; otherwise page ranges per (sequence, kv-head).

@@ -20,6 +20,9 @@ int check_layout(const kitty_layout* L) {
   if (nb16 != 0 && nb16 != 1 && nb16 != 2 && nb16 != 4 && nb16 != 8) return KITTY_ERR_UNSUPPORTED;
   const int g = L->n_q_heads / L->n_kv_heads;
   if (g != 1 && g != 2 && g != 4 && g != 8) return KITTY_ERR_UNSUPPORTED;
+  if (L->sink_tokens < 0 || L->v_local < 0) return KITTY_ERR_INVALID_ARG;
+  if (L->sink_tokens > G) return KITTY_ERR_UNSUPPORTED;
+  if (L->v_local != 0 && (L->v_local != G || L->residual_window != G)) return KITTY_ERR_UNSUPPORTED;
   return KITTY_OK;
 }
 
@@ -32,6 +35,11 @@ int check_cache(const kitty_layout* L, const kitty_cache* C) {
   if (L->residual_window > 0) {
     if (!C->resid_k || !C->resid_v || !C->n_resid) return KITTY_ERR_INVALID_ARG;
     if (reinterpret_cast<uintptr_t>(C->resid_k) % 16 != 0 || reinterpret_cast<uintptr_t>(C->resid_v) % 16 != 0)
+      return KITTY_ERR_INVALID_ARG;
+  }
+  if (L->sink_tokens > 0) {
+    if (!C->sink_k || !C->sink_v || !C->n_sink) return KITTY_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(C->sink_k) % 16 != 0 || reinterpret_cast<uintptr_t>(C->sink_v) % 16 != 0)
       return KITTY_ERR_INVALID_ARG;
   }
   return KITTY_OK;
@@ -108,6 +116,13 @@ int fill_decode_params(const kitty_layout* L, const kitty_cache* C, int32_t n_sp
   P->resid_k = static_cast<const uint16_t*>(C->resid_k);
   P->resid_v = static_cast<const uint16_t*>(C->resid_v);
   P->n_resid = C->n_resid;
+  P->sink_k = static_cast<const uint16_t*>(C->sink_k);
+  P->sink_v = static_cast<const uint16_t*>(C->sink_v);
+  P->n_sink = C->n_sink;
+  P->sink_cap = L->sink_tokens;
+  P->v_local = L->v_local ? 1 : 0;
+  P->sink_k_w = P->sink_v_w = nullptr;
+  P->n_sink_w = nullptr;
   P->q = nullptr;
   P->ws = const_cast<float*>(static_cast<const float*>(ws));
   P->out = nullptr;
@@ -216,6 +231,11 @@ int kitty_append_token(const kitty_layout* L, const kitty_cache* C, const void* 
   P.resid_k = static_cast<uint16_t*>(C->resid_k);
   P.resid_v = static_cast<uint16_t*>(C->resid_v);
   P.n_resid = C->n_resid;
+  P.sink_k = static_cast<uint16_t*>(C->sink_k);
+  P.sink_v = static_cast<uint16_t*>(C->sink_v);
+  P.n_sink = C->n_sink;
+  P.sink_cap = L->sink_tokens;
+  P.v_local = L->v_local ? 1 : 0;
   P.k_new = static_cast<const uint16_t*>(k_new);
   P.v_new = static_cast<const uint16_t*>(v_new);
   P.fresh_page_ids = fresh_page_ids;
@@ -266,6 +286,9 @@ int launch_split(const kitty_layout* L, const kitty_cache* C, const void* q, flo
     P.resid_k_w = static_cast<uint16_t*>(C->resid_k);
     P.resid_v_w = static_cast<uint16_t*>(C->resid_v);
     P.n_resid_w = C->n_resid;
+    P.sink_k_w = static_cast<uint16_t*>(C->sink_k);
+    P.sink_v_w = static_cast<uint16_t*>(C->sink_v);
+    P.n_sink_w = C->n_sink;
   }
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   const dim3 grid(P.n_splits, L->n_kv_heads, C->batch);
@@ -348,7 +371,7 @@ const char* kitty_strerror(int code) {
   switch (code) {
     case KITTY_OK: return "ok";
     case KITTY_ERR_INVALID_ARG: return "invalid argument (null pointer, bad alignment or inconsistent sizes)";
-    case KITTY_ERR_UNSUPPORTED: return "unsupported size (head_dim, page_size, residual window, boost count or GQA group)";
+    case KITTY_ERR_UNSUPPORTED: return "unsupported size (head_dim, page_size, residual window, Sink, Local window, boost count or GQA group)";
     case KITTY_ERR_WORKSPACE: return "workspace too small";
     case KITTY_ERR_HIP: return "HIP launch failed";
   }

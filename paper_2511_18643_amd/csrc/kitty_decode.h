@@ -32,6 +32,9 @@ struct DecodeParams {
   const uint16_t* resid_k;
   const uint16_t* resid_v;
   const int32_t* n_resid;
+  const uint16_t* sink_k;   // bf16 [batch][n_kv_heads][sink_cap][D], the first tokens of every sequence (Fig. 1: Sink)
+  const uint16_t* sink_v;
+  const int32_t* n_sink;
   const uint16_t* q;
   float* ws;
   void* out;
@@ -39,6 +42,8 @@ struct DecodeParams {
   int32_t batch, max_pages, n_q_heads, n_kv_heads, gqa;
   int32_t n_splits, min_pages, has_window, out_dtype;
   int32_t direct_out;    // split kernel with n_splits == 1: normalise and store `out` itself, no partials
+  int32_t sink_cap;      // S (0 = no Sink)
+  int32_t v_local;       // 1: the Values of the newest page are read from the bf16 Local window, not from its record
   // fused step (append, then attention, one launch; only with one range per sequence and kv-head)
   const uint16_t* k_new;
   const uint16_t* v_new;
@@ -49,12 +54,15 @@ struct DecodeParams {
   uint16_t* resid_k_w;
   uint16_t* resid_v_w;
   int32_t* n_resid_w;
+  uint16_t* sink_k_w;
+  uint16_t* sink_v_w;
+  int32_t* n_sink_w;
   int32_t n_pool_pages, rank_metric;
 };
 
-// Page ranges of one sequence: with np pages and a window of r rows, the sequence uses
-// Sb = min(n_splits, max(1, np / min_pages)) ranges (one if it only has a window, none if it is empty);
-// range s covers pages [s*np/Sb, (s+1)*np/Sb) and window rows [s*r/Sb, (s+1)*r/Sb).
+// Page ranges of one sequence: with np pages and r full-precision rows (Sink + window), the sequence uses
+// Sb = min(n_splits, max(1, np / min_pages)) ranges (one if it only has such rows, none if it is empty);
+// range s covers pages [s*np/Sb, (s+1)*np/Sb) and full-precision rows [s*r/Sb, (s+1)*r/Sb).
 __device__ __forceinline__ int active_splits(int np, int r, int n_splits, int min_pages) {
   if (np <= 0) return r > 0 ? 1 : 0;
   return min(n_splits, max(1, np / min_pages));
@@ -204,7 +212,8 @@ struct WaveScratch {
   uint8_t abuf[16 * HPL][144];                         // rows (head, term) x channel; one 16-row matrix per pass
   uint8_t bbuf[16 * HPL][16 * (NB16 ? NB16 : 1) + 16];  // rows (head, term) x boost slot
   uint8_t pbuf[16 * HPL][144];                         // rows (head, term) x position
-  float pw[32][8];                               // window path: softmax weights [token][head]
+  float pw[32][8];                               // full-precision rows: softmax weights [row][head]
+  float pcorr[8];                                // same path: rescale factor of the running sums per head
   uint8_t meta[4][256];                          // k_scale, k_zero, v_scale, v_zero of the page being processed
   uint8_t zero[16];
 };
@@ -306,16 +315,14 @@ struct PageWorker {
     *reinterpret_cast<uint4*>(&ws.meta[gi][16 * j]) = meta;
   }
 
-  // Processes the page held in `pg` (its fp16 arrays already staged in LDS).  The pieces of the wavefront's
-  // next page (record `rec_nx`, if `has_nx`) are requested into the same registers as soon as they are dead.
-  __device__ __forceinline__ void process(PageRegs<NB16>& pg, const uint8_t* rec_nx, bool has_nx) {
-    uint4 meta_nx = make_uint4(0, 0, 0, 0);
-    if (has_nx) meta_nx = load_meta<NB16>(rec_nx, lo);
+  // Phases A-C: integer logits of the 128 tokens of the page in `pg` (k_scale, k_zero staged in LDS).
+  // The logit of head gi*HPL + e and token 16T + j is inv_alpha[e] * join(dq[T]...) + bias[e] (log2 domain).
+  __device__ __forceinline__ void logits(const PageRegs<NB16>& pg, v4i (&dq)[8], v4i (&dqx)[TWO_PASS ? 8 : 1],
+                                         float (&inv_alpha)[HPL], float (&bias)[HPL]) {
     // ================= A: integer image of q*s, bias q.z =================
     float ks[8], kz[8];
     f16x8_to_f32(*reinterpret_cast<const uint4*>(&ws.meta[0][16 * j]), ks);
     f16x8_to_f32(*reinterpret_cast<const uint4*>(&ws.meta[1][16 * j]), kz);
-    float inv_alpha[HPL], bias[HPL];
 #pragma unroll
     for (int e = 0; e < HPL; ++e) {
       float qs[8], amaxA = 0.f, amaxB = 0.f, bsA = 0.f, bsB = 0.f;
@@ -375,7 +382,6 @@ struct PageWorker {
       a0x = *reinterpret_cast<const v4i*>(a_ptr + A_PASS);
       a1x = *reinterpret_cast<const v4i*>(a_ptr + A_PASS + 64);
     }
-    v4i dq[8], dqx[TWO_PASS ? 8 : 1];
 #pragma unroll
     for (int T = 0; T < 8; ++T) {
       const uint4 ld = pg.kd[T >> 1];
@@ -414,6 +420,35 @@ struct PageWorker {
         }
       }
     }
+  }
+
+  __device__ __forceinline__ int joined(const v4i& c, const v4i& cx, int e) const {
+    if constexpr (HPL == 1) return join_terms(c[0], c[1], c[2]);
+    else if constexpr (TWO_PASS) return join_terms(c[2 * e], c[2 * e + 1], cx[e]);
+    else return join_terms(c[2 * e], c[2 * e + 1]);
+  }
+
+  // Logits only (log2 domain, float) of the page in `pg`, stored as x[token][head]: used for the newest page
+  // when its Values are still read in full precision (they are then handled with the other bf16 rows).
+  __device__ __forceinline__ void logits_to(const PageRegs<NB16>& pg, float (*x)[4 * HPL]) {
+    v4i dq[8], dqx[TWO_PASS ? 8 : 1];
+    float inv_alpha[HPL], bias[HPL];
+    logits(pg, dq, dqx, inv_alpha, bias);
+#pragma unroll
+    for (int e = 0; e < HPL; ++e)
+#pragma unroll
+      for (int T = 0; T < 8; ++T)
+        x[16 * T + j][gi * HPL + e] = fmaf((float)joined(dq[T], dqx[TWO_PASS ? T : 0], e), inv_alpha[e], bias[e]);
+  }
+
+  // Processes the page held in `pg` (its fp16 arrays already staged in LDS).  The pieces of the wavefront's
+  // next page (record `rec_nx`, if `has_nx`) are requested into the same registers as soon as they are dead.
+  __device__ __forceinline__ void process(PageRegs<NB16>& pg, const uint8_t* rec_nx, bool has_nx) {
+    uint4 meta_nx = make_uint4(0, 0, 0, 0);
+    if (has_nx) meta_nx = load_meta<NB16>(rec_nx, lo);
+    v4i dq[8], dqx[TWO_PASS ? 8 : 1];
+    float inv_alpha[HPL], bias[HPL];
+    logits(pg, dq, dqx, inv_alpha, bias);
     if (has_nx) load_k<NB16>(pg, rec_nx, lo);   // the Key planes of this page are in the matrix pipeline now
     // ================= D: online softmax; lane (j, gi) owns token 16T + j of heads gi*HPL + e ==========
     float vs[8], vz[8];
@@ -527,47 +562,63 @@ __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: page ids stay in scalar registers
   const int l = tid & 63, j = l & 15, gi = l >> 4;
   const int g = p.gqa;
+  const size_t pair = (size_t)b * p.n_kv_heads + h;
 
   int np = min(p.n_pages[b], p.max_pages);
   int r = p.has_window ? min(p.n_resid[b] & ((1 << TICKET_SHIFT) - 1), G) : 0;
+  int ns = p.sink_cap ? min(p.n_sink[b], p.sink_cap) : 0;
   // fused append: state before the step, what the step does to it
-  const int nr_old = r, np_old = np;
+  const int nr_old = r, np_old = np, ns_old = ns;
   int newrow = -1;              // window row of the token appended by this step (its data comes from k_new/v_new)
+  int newsink = -1;             // or its Sink row
   int32_t fresh_pid = -1;       // page written by this step's flush (not yet in the page table)
   bool ok = true, flush = false;
   const uint16_t* knew_h = nullptr;
   const uint16_t* vnew_h = nullptr;
   if constexpr (FUSED) {
     const int32_t pid = p.fresh_page_ids[b];
-    flush = nr_old >= G;
-    ok = !flush || (np_old < p.max_pages && pid >= 0 && pid < p.n_pool_pages);
-    uint16_t* wkw = p.resid_k_w + ((size_t)b * p.n_kv_heads + h) * (size_t)(G * D);
-    uint16_t* wvw = p.resid_v_w + ((size_t)b * p.n_kv_heads + h) * (size_t)(G * D);
-    knew_h = p.k_new + ((size_t)b * p.n_kv_heads + h) * D;
-    vnew_h = p.v_new + ((size_t)b * p.n_kv_heads + h) * D;
-    if (ok) {
-      if (flush) {
-        uint8_t* rec = p.pool_w + ((size_t)pid * p.n_kv_heads + h) * (size_t)R::bytes;
-        quantize_page<NB16>(smem.quant, wkw, wvw, D, rec, p.rank_metric);
-        __threadfence();          // the record is read back by this block's wavefronts
-        __syncthreads();
-        fresh_pid = pid;
-        np = np_old + 1;
-        r = 1;
-        newrow = 0;
-      } else {
-        r = nr_old + 1;
-        newrow = nr_old;
-      }
-      if (tid < 32) {             // keep the token for the following steps
+    knew_h = p.k_new + pair * D;
+    vnew_h = p.v_new + pair * D;
+    if (ns_old < p.sink_cap) {    // the Sink is not full: the token goes there and nothing else changes
+      if (tid < 32) {
         const int part = tid & 15;
         const uint16_t* src = (tid < 16 ? knew_h : vnew_h) + part * 8;
-        uint16_t* dst = (tid < 16 ? wkw : wvw) + (size_t)newrow * D + part * 8;
+        uint16_t* dst = (tid < 16 ? p.sink_k_w : p.sink_v_w) + (pair * p.sink_cap + ns_old) * D + part * 8;
         *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
+      }
+      newsink = ns_old;
+      ns = ns_old + 1;
+    } else {
+      flush = nr_old >= G;
+      ok = !flush || (np_old < p.max_pages && pid >= 0 && pid < p.n_pool_pages);
+      uint16_t* wkw = p.resid_k_w + pair * (size_t)(G * D);
+      if (ok) {
+        if (flush) {
+          uint8_t* rec = p.pool_w + ((size_t)pid * p.n_kv_heads + h) * (size_t)R::bytes;
+          const uint16_t* wv_old = p.resid_v_w + resid_v_offset(b, h, p.n_kv_heads, p.v_local, np_old);
+          quantize_page<NB16>(smem.quant, wkw, wv_old, D, rec, p.rank_metric);
+          __threadfence();          // the record is read back by this block's wavefronts
+          __syncthreads();
+          fresh_pid = pid;
+          np = np_old + 1;
+          r = 1;
+          newrow = 0;
+        } else {
+          r = nr_old + 1;
+          newrow = nr_old;
+        }
+        if (tid < 32) {             // keep the token for the following steps
+          const int part = tid & 15;
+          uint16_t* wvw = p.resid_v_w + resid_v_offset(b, h, p.n_kv_heads, p.v_local, np);
+          const uint16_t* src = (tid < 16 ? knew_h : vnew_h) + part * 8;
+          uint16_t* dst = (tid < 16 ? wkw : wvw) + (size_t)newrow * D + part * 8;
+          *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
+        }
       }
     }
   }
-  const int sb = active_splits(np, r, p.n_splits, p.min_pages);
+  const int nfp = ns + r;       // rows read in full precision for both Keys and Values: Sink, then window
+  const int sb = active_splits(np, nfp, p.n_splits, p.min_pages);
   if (slot >= sb) {   // nothing to attend over (never the case in a fused step that appended a token)
     if (p.direct_out && slot == 0) {   // empty sequence: the result is defined as zeros
       for (int o = tid; o < g * D; o += 64 * NW) {
@@ -579,8 +630,16 @@ __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void
     return;
   }
   const int p0 = (int)((long long)slot * np / sb), p1 = (int)((long long)(slot + 1) * np / sb);
+  // Local window of the Values (Fig. 1): the newest page's Values are still read from their bf16 rows; its
+  // Keys are read from the record, and the logits are handed to the full-precision path below.
+  const bool lag_here = p.v_local && np >= 1 && slot == sb - 1;   // the last range holds the newest page
+  const int p1q = p1 - (lag_here ? 1 : 0);                        // pages [p0, p1q) are read from records entirely
 
   WaveScratch<NB16, HPL>& ws = smem.w[w];
+  // logits of the newest page, [token][head]: kept in the (by then idle) gather table of the wavefront that
+  // computes them, which is the one whose turn the page is
+  float (*lagx)[NH] = reinterpret_cast<float (*)[NH]>(&smem.w[lag_here ? (p1q - p0) % NW : 0].nbuf[0][0]);
+  static_assert(sizeof(ws.nbuf) == sizeof(float) * G * NH, "lagx aliases nbuf");
   const size_t qrow = ((size_t)b * p.n_q_heads + (size_t)h * g);
   PageWorker<NB16, HPL> pw(ws, l);
 
@@ -623,19 +682,23 @@ __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void
       // priorities the older one wins every conflict and ends its (equal) share of the pages ~6 % earlier,
       // leaving the block to wait for the younger one.
       int turn = w / 4;
-      for (; idx < p1; idx += NW) {
+      for (; idx < p1q; idx += NW) {
         const bool has_nx = idx + NW < p1;
         if (turn & 1) __builtin_amdgcn_s_setprio(1); else __builtin_amdgcn_s_setprio(0);
         ++turn;
         pw.process(pg, has_nx ? rec_of(idx + NW) : pool_h, has_nx);
       }
       __builtin_amdgcn_s_setprio(0);
+      if (lag_here && idx == p1q) pw.logits_to(pg, lagx);   // this wavefront holds the newest page
     }
   }
+  if (lag_here) __syncthreads();   // lagx is complete (the condition is the same for the whole block)
 
-  // ================= residual window: bf16 rows, spread over the ranges of the sequence =================
-  // range `slot` of `sb` takes window rows [slot*r/sb, (slot+1)*r/sb); its four wavefronts split them evenly
-  // (at most 32 rows each since the window holds 128).
+  // ================= rows read in full precision, spread over the ranges and wavefronts =================
+  // Range `slot` of `sb` takes rows [slot*nfp/sb, (slot+1)*nfp/sb) of the list (Sink rows, then window rows); the
+  // last range also takes the G Value rows of the newest page when the Local window is on (their logits are in
+  // lagx).  The block's list is cut into NW near-equal runs, one per wavefront, walked in chunks of 32 rows
+  // with an online softmax.
   float accw[NH][8];        // channels 8j..8j+7 of every head (after the cross-group sum)
   float mw[HPL], lw[HPL];
 #pragma unroll
@@ -644,21 +707,39 @@ __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void
     for (int k = 0; k < 8; ++k) accw[hh][k] = 0.f;
 #pragma unroll
   for (int e = 0; e < HPL; ++e) { mw[e] = -INFINITY; lw[e] = 0.f; }
-  const int wr0 = (int)((long long)slot * r / sb), wr1 = (int)((long long)(slot + 1) * r / sb);
-  const int per = (wr1 - wr0 + NW - 1) / NW;
-  const int t0 = wr0 + w * per, t1 = min(t0 + per, wr1);
+  const int wr0 = (int)((long long)slot * nfp / sb), wr1 = (int)((long long)(slot + 1) * nfp / sb);
+  const int nkv = wr1 - wr0;                       // rows of this block with bf16 Keys and Values
+  const int nrows = nkv + (lag_here ? G : 0);
+  const int per = (nrows + NW - 1) / NW;
+  const int t0 = w * per, t1 = min(t0 + per, nrows);
   if (t0 < t1) {
-    const uint16_t* wk = p.resid_k + ((size_t)b * p.n_kv_heads + h) * (size_t)(G * D);
-    const uint16_t* wv = p.resid_v + ((size_t)b * p.n_kv_heads + h) * (size_t)(G * D);
-    // Value rows t0 + 4i + gi (i < 8), channels 8j..8j+7: requested first, used last.  Rows past the slice are
-    // clamped to its last row (their weight is zero; uninitialised rows are never touched).
-    uint4 vrow[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int row = min(t0 + 4 * i + gi, t1 - 1);
-      const uint16_t* vr = (FUSED && row == newrow) ? vnew_h : wv + (size_t)row * D;
-      vrow[i] = *reinterpret_cast<const uint4*>(vr + 8 * j);
-    }
+    const uint16_t* wk = p.resid_k + pair * (size_t)(G * D);
+    const uint16_t* wv = p.resid_v + resid_v_offset(b, h, p.n_kv_heads, p.v_local, np);
+    const uint16_t* lagv = p.resid_v + resid_v_offset(b, h, p.n_kv_heads, p.v_local, np - 1);
+    const uint16_t* sk = p.sink_k + pair * (size_t)p.sink_cap * D;
+    const uint16_t* sv = p.sink_v + pair * (size_t)p.sink_cap * D;
+    const uint16_t* qdummy = p.q + qrow * D;       // any readable row: Key operand of rows whose logits come from lagx
+    // row i of the block's list -> its Key row, Value row, and index into lagx (or -1)
+    auto row_ptrs = [&](int i, const uint16_t*& kp, const uint16_t*& vp, int& li) {
+      if (i < nkv) {
+        const int f = wr0 + i;
+        li = -1;
+        if (f < ns) {
+          const bool fresh = FUSED && f == newsink;
+          kp = fresh ? knew_h : sk + (size_t)f * D;
+          vp = fresh ? vnew_h : sv + (size_t)f * D;
+        } else {
+          const int t = f - ns;
+          const bool fresh = FUSED && t == newrow;
+          kp = fresh ? knew_h : wk + (size_t)t * D;
+          vp = fresh ? vnew_h : wv + (size_t)t * D;
+        }
+      } else {
+        li = i - nkv;
+        kp = qdummy;
+        vp = lagv + (size_t)li * D;
+      }
+    };
     // A operand: query rows; row hd*RPH carries head hd, the other rows are zero
     const int arow_head = j / RPH;
     const bool arow_live = (j % RPH) == 0 && arow_head < g;
@@ -669,50 +750,82 @@ __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void
       if (arow_live) raw = *reinterpret_cast<const uint4*>(p.q + (qrow + arow_head) * D + 32 * mm + 8 * gi);
       aq[mm] = __builtin_bit_cast(v8bf, raw);
     }
-    float x[HPL][2];
+    for (int c0 = t0; c0 < t1; c0 += 32) {
+      // Value rows c0 + 4i + gi (i < 8), channels 8j..8j+7: requested first, used last.  Rows past the run are
+      // clamped to its last row (their weight is zero; uninitialised rows are never touched).
+      uint4 vrow[8];
 #pragma unroll
-    for (int tt = 0; tt < 2; ++tt) {
-      const int t = t0 + 16 * tt + j;
-      const int trow = min(t, t1 - 1);
-      const uint16_t* kr = (FUSED && trow == newrow) ? knew_h : wk + (size_t)trow * D;
-      v4f c = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int mm = 0; mm < 4; ++mm) {
-        const uint4 raw = *reinterpret_cast<const uint4*>(kr + 32 * mm + 8 * gi);
-        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aq[mm], __builtin_bit_cast(v8bf, raw), c, 0, 0, 0);
+      for (int i = 0; i < 8; ++i) {
+        const uint16_t *kp, *vp;
+        int li;
+        row_ptrs(min(c0 + 4 * i + gi, t1 - 1), kp, vp, li);
+        vrow[i] = *reinterpret_cast<const uint4*>(vp + 8 * j);
       }
+      float x[HPL][2];
 #pragma unroll
-      for (int e = 0; e < HPL; ++e) x[e][tt] = t < t1 ? c[e * RPH] * p.qk_scale_log2 : -INFINITY;
-    }
+      for (int tt = 0; tt < 2; ++tt) {
+        const int t = c0 + 16 * tt + j;
+        const uint16_t *kr, *vp;
+        int li;
+        row_ptrs(min(t, t1 - 1), kr, vp, li);
+        v4f c = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int e = 0; e < HPL; ++e) {
-      const float mx = row_max(fmaxf(x[e][0], x[e][1]));
-      mw[e] = mx;
-      const float pa = __builtin_amdgcn_exp2f(x[e][0] - mx), pb = __builtin_amdgcn_exp2f(x[e][1] - mx);
-      lw[e] = pa + pb;
-      ws.pw[j][gi * HPL + e] = pa;
-      ws.pw[16 + j][gi * HPL + e] = pb;
-    }
-    wave_lds_fence();
+        for (int mm = 0; mm < 4; ++mm) {
+          const uint4 raw = *reinterpret_cast<const uint4*>(kr + 32 * mm + 8 * gi);
+          c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aq[mm], __builtin_bit_cast(v8bf, raw), c, 0, 0, 0);
+        }
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int tl = 4 * i + gi;          // row within the wavefront's slice (weight 0 beyond it)
-      float ph[NH];
-#pragma unroll
-      for (int q4 = 0; q4 < NH / 4; ++q4) {
-        const float4 f = *reinterpret_cast<const float4*>(&ws.pw[tl][4 * q4]);
-        ph[4 * q4] = f.x; ph[4 * q4 + 1] = f.y; ph[4 * q4 + 2] = f.z; ph[4 * q4 + 3] = f.w;
-      }
-      const uint32_t vw[4] = {vrow[i].x, vrow[i].y, vrow[i].z, vrow[i].w};
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const float v0 = __uint_as_float(vw[k] << 16), v1 = __uint_as_float(vw[k] & 0xffff0000u);
-#pragma unroll
-        for (int hh = 0; hh < NH; ++hh) {
-          accw[hh][2 * k] = fmaf(ph[hh], v0, accw[hh][2 * k]);
-          accw[hh][2 * k + 1] = fmaf(ph[hh], v1, accw[hh][2 * k + 1]);
+        for (int e = 0; e < HPL; ++e) {
+          const float xl = lagx[max(li, 0)][gi * HPL + e];
+          const float xv = li >= 0 ? xl : c[e * RPH] * p.qk_scale_log2;
+          x[e][tt] = t < t1 ? xv : -INFINITY;
         }
       }
+#pragma unroll
+      for (int e = 0; e < HPL; ++e) {
+        const float m_new = fmaxf(mw[e], row_max(fmaxf(x[e][0], x[e][1])));   // finite: the chunk has a valid row
+        const float corr = __builtin_amdgcn_exp2f(mw[e] - m_new);              // 0 on the first chunk
+        mw[e] = m_new;
+        const float pa = __builtin_amdgcn_exp2f(x[e][0] - m_new), pb = __builtin_amdgcn_exp2f(x[e][1] - m_new);
+        lw[e] = fmaf(lw[e], corr, pa + pb);
+        ws.pw[j][gi * HPL + e] = pa;
+        ws.pw[16 + j][gi * HPL + e] = pb;
+        if (j == 0) ws.pcorr[gi * HPL + e] = corr;
+      }
+      wave_lds_fence();
+      {
+        float cr[NH];
+#pragma unroll
+        for (int q4 = 0; q4 < NH / 4; ++q4) {
+          const float4 f = *reinterpret_cast<const float4*>(&ws.pcorr[4 * q4]);
+          cr[4 * q4] = f.x; cr[4 * q4 + 1] = f.y; cr[4 * q4 + 2] = f.z; cr[4 * q4 + 3] = f.w;
+        }
+#pragma unroll
+        for (int hh = 0; hh < NH; ++hh)
+#pragma unroll
+          for (int k = 0; k < 8; ++k) accw[hh][k] *= cr[hh];
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int tl = 4 * i + gi;          // row within the chunk (weight 0 beyond the run)
+        float ph[NH];
+#pragma unroll
+        for (int q4 = 0; q4 < NH / 4; ++q4) {
+          const float4 f = *reinterpret_cast<const float4*>(&ws.pw[tl][4 * q4]);
+          ph[4 * q4] = f.x; ph[4 * q4 + 1] = f.y; ph[4 * q4 + 2] = f.z; ph[4 * q4 + 3] = f.w;
+        }
+        const uint32_t vw[4] = {vrow[i].x, vrow[i].y, vrow[i].z, vrow[i].w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const float v0 = __uint_as_float(vw[k] << 16), v1 = __uint_as_float(vw[k] & 0xffff0000u);
+#pragma unroll
+          for (int hh = 0; hh < NH; ++hh) {
+            accw[hh][2 * k] = fmaf(ph[hh], v0, accw[hh][2 * k]);
+            accw[hh][2 * k + 1] = fmaf(ph[hh], v1, accw[hh][2 * k + 1]);
+          }
+        }
+      }
+      wave_lds_fence();   // the next chunk overwrites pw
     }
     // sum over the four lane groups (rows 4i + gi): two butterfly steps across groups
 #pragma unroll
@@ -781,7 +894,9 @@ __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void
       const int old = atomicAdd(&p.n_resid_w[b], 1 << TICKET_SHIFT);
       if ((old >> TICKET_SHIFT) == p.n_kv_heads - 1) {   // every block of this sequence is done with the old state
         int new_nr = nr_old;
-        if (ok) {
+        if (newsink >= 0) {
+          p.n_sink_w[b] = ns_old + 1;
+        } else if (ok) {
           if (flush) {
             p.page_table_w[(size_t)b * p.max_pages + np_old] = fresh_pid;
             p.n_pages_w[b] = np_old + 1;
@@ -814,7 +929,7 @@ __global__ __launch_bounds__(128) void decode_merge_kernel(DecodeParams p) {
       av[s] = in ? base[s * slot_stride + d] : 0.f;
     }
     const int np = min(p.n_pages[b], p.max_pages);
-    const int r = p.has_window ? min(p.n_resid[b], G) : 0;
+    const int r = (p.has_window ? min(p.n_resid[b], G) : 0) + (p.sink_cap ? min(p.n_sink[b], p.sink_cap) : 0);
     const int sb = active_splits(np, r, p.n_splits, p.min_pages);
     float M = -INFINITY;
 #pragma unroll
@@ -829,7 +944,7 @@ __global__ __launch_bounds__(128) void decode_merge_kernel(DecodeParams p) {
     }
   } else {
     const int np = min(p.n_pages[b], p.max_pages);
-    const int r = p.has_window ? min(p.n_resid[b], G) : 0;
+    const int r = (p.has_window ? min(p.n_resid[b], G) : 0) + (p.sink_cap ? min(p.n_sink[b], p.sink_cap) : 0);
     const int sb = active_splits(np, r, p.n_splits, p.min_pages);
     float M = -INFINITY;
     for (int s = 0; s < sb; ++s) M = fmaxf(M, base[s * slot_stride + D]);

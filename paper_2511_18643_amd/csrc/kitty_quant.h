@@ -242,16 +242,30 @@ struct AppendParams {
   uint16_t* resid_k;
   uint16_t* resid_v;
   int32_t* n_resid;
+  uint16_t* sink_k;
+  uint16_t* sink_v;
+  int32_t* n_sink;
   const uint16_t* k_new;
   const uint16_t* v_new;
   const int32_t* fresh_page_ids;
   int32_t batch, max_pages, n_pool_pages, n_kv_heads, rank_metric;
+  int32_t sink_cap;   // S: tokens the Sink holds (0 = none)
+  int32_t v_local;    // 1: Value rows live in two halves of G rows, page i's rows in half i & 1
 };
 
-// Grid (n_kv_heads, batch).  Reads the sequence state, flushes a full window into a page, stores the new
-// token.  Every head's block must see the old state, so the state is advanced by the block of a sequence
-// that finishes last: blocks take a ticket in bits 8.. of n_resid[b] (the row count needs bits 0..7) once
-// they are done, and the holder of the last ticket writes the new state, which also clears the tickets.
+// Value rows of the window of (sequence b, kv-head h).  With the Local window the buffer has two halves of G
+// rows: the rows of page i (while they are still needed in full precision) and of the tokens that will form
+// page i sit in half i & 1, so the half of the page being filled alternates and the previous one stays readable.
+__device__ __forceinline__ size_t resid_v_offset(int b, int h, int n_kv_heads, int v_local, int page) {
+  const size_t pair = (size_t)b * n_kv_heads + h;
+  return v_local ? (pair * 2 + (size_t)(page & 1)) * (size_t)(G * D) : pair * (size_t)(G * D);
+}
+
+// Grid (n_kv_heads, batch).  Reads the sequence state, then either stores the new token in the Sink (while
+// it is not full), or flushes a full window into a page and stores the new token in the window.  Every head's
+// block must see the old state, so the state is advanced by the block of a sequence that finishes last: blocks
+// take a ticket in bits 8.. of n_resid[b] (the row count needs bits 0..7) once they are done, and the holder
+// of the last ticket writes the new state, which also clears the tickets.
 constexpr int TICKET_SHIFT = 8;
 
 template <int NB16>
@@ -260,23 +274,34 @@ __global__ __launch_bounds__(256) void append_token_kernel(AppendParams p) {
   const int h = blockIdx.x, b = blockIdx.y;
   const int nr = p.n_resid[b] & ((1 << TICKET_SHIFT) - 1);
   const int np = p.n_pages[b];
+  const int ns = p.sink_cap ? p.n_sink[b] : 0;
+  const bool to_sink = ns < p.sink_cap;
   const int32_t pid = p.fresh_page_ids[b];
-  uint16_t* wk = p.resid_k + ((size_t)b * p.n_kv_heads + h) * (size_t)(G * D);
-  uint16_t* wv = p.resid_v + ((size_t)b * p.n_kv_heads + h) * (size_t)(G * D);
-  const bool flush = nr >= G;
+  const size_t pair = (size_t)b * p.n_kv_heads + h;
+  uint16_t* wk = p.resid_k + pair * (size_t)(G * D);
+  const bool flush = !to_sink && nr >= G;
   // a flush that cannot happen (page table full, id outside the pool) leaves the sequence unchanged
   const bool ok = !flush || (np >= 0 && np < p.max_pages && pid >= 0 && pid < p.n_pool_pages);
   const int tid = threadIdx.x;
-  if (ok) {
+  if (to_sink) {
+    if (tid < 32) {
+      const int part = tid & 15;
+      const uint16_t* src = (tid < 16 ? p.k_new : p.v_new) + pair * D + part * 8;
+      uint16_t* dst = (tid < 16 ? p.sink_k : p.sink_v) + (pair * p.sink_cap + ns) * D + part * 8;
+      *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
+    }
+  } else if (ok) {
     int slot = nr;
+    uint16_t* wv = p.resid_v + resid_v_offset(b, h, p.n_kv_heads, p.v_local, np);
     if (flush) {
       uint8_t* rec = p.pool + ((size_t)pid * p.n_kv_heads + h) * (size_t)Rec<NB16>::bytes;
       quantize_page<NB16>(smem, wk, wv, D, rec, p.rank_metric);
       slot = 0;
+      wv = p.resid_v + resid_v_offset(b, h, p.n_kv_heads, p.v_local, np + 1);
     }
     if (tid < 32) {
       const int part = tid & 15;
-      const uint16_t* src = (tid < 16 ? p.k_new : p.v_new) + ((size_t)b * p.n_kv_heads + h) * D + part * 8;
+      const uint16_t* src = (tid < 16 ? p.k_new : p.v_new) + pair * D + part * 8;
       uint16_t* dst = (tid < 16 ? wk : wv) + (size_t)slot * D + part * 8;
       *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
     }
@@ -286,7 +311,9 @@ __global__ __launch_bounds__(256) void append_token_kernel(AppendParams p) {
     const int old = atomicAdd(&p.n_resid[b], 1 << TICKET_SHIFT);
     if ((old >> TICKET_SHIFT) == p.n_kv_heads - 1) {   // every block of this sequence has read the state
       int new_nr = nr;
-      if (ok) {
+      if (to_sink) {
+        p.n_sink[b] = ns + 1;
+      } else if (ok) {
         if (flush) {
           p.page_table[(size_t)b * p.max_pages + np] = pid;
           p.n_pages[b] = np + 1;

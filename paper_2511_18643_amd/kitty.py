@@ -27,12 +27,13 @@ EXPORTS = (
 
 class KittyLayout(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("head_dim", "page_size", "v_group", "n_boost", "residual_window",
-                                         "n_q_heads", "n_kv_heads", "rank_metric")]
+                                         "n_q_heads", "n_kv_heads", "rank_metric", "sink_tokens", "v_local")]
 
 
 class KittyCache(C.Structure):
     _fields_ = [("page_pool", C.c_void_p), ("page_table", C.c_void_p), ("n_pages", C.c_void_p),
                 ("resid_k", C.c_void_p), ("resid_v", C.c_void_p), ("n_resid", C.c_void_p),
+                ("sink_k", C.c_void_p), ("sink_v", C.c_void_p), ("n_sink", C.c_void_p),
                 ("batch", C.c_int32), ("max_pages", C.c_int32), ("n_pool_pages", C.c_int32)]
 
 
@@ -81,8 +82,10 @@ def lib() -> C.CDLL:
 
 
 def make_layout(n_q_heads: int, n_kv_heads: int, n_boost: int = 16, residual_window: int = 128,
-                rank_metric: int = 0, head_dim: int = 128, page_size: int = 128, v_group: int = 128) -> KittyLayout:
-    return KittyLayout(head_dim, page_size, v_group, n_boost, residual_window, n_q_heads, n_kv_heads, rank_metric)
+                rank_metric: int = 0, head_dim: int = 128, page_size: int = 128, v_group: int = 128,
+                sink_tokens: int = 0, v_local: int = 0) -> KittyLayout:
+    return KittyLayout(head_dim, page_size, v_group, n_boost, residual_window, n_q_heads, n_kv_heads, rank_metric,
+                       sink_tokens, v_local)
 
 
 def _ptr(t) -> int | None:
@@ -133,14 +136,22 @@ class Cache:
         self.n_pages = torch.zeros((batch,), dtype=torch.int32, device=device)
         if r:
             self.resid_k = torch.zeros((batch, hkv, r, layout.head_dim), dtype=torch.bfloat16, device=device)
-            self.resid_v = torch.zeros_like(self.resid_k)
+            halves = (2,) if layout.v_local else ()
+            self.resid_v = torch.zeros((batch, hkv) + halves + (r, layout.head_dim), dtype=torch.bfloat16, device=device)
             self.n_resid = torch.zeros((batch,), dtype=torch.int32, device=device)
         else:
             self.resid_k = self.resid_v = self.n_resid = None
+        if layout.sink_tokens:
+            self.sink_k = torch.zeros((batch, hkv, layout.sink_tokens, layout.head_dim), dtype=torch.bfloat16, device=device)
+            self.sink_v = torch.zeros_like(self.sink_k)
+            self.n_sink = torch.zeros((batch,), dtype=torch.int32, device=device)
+        else:
+            self.sink_k = self.sink_v = self.n_sink = None
 
     def struct(self) -> KittyCache:
         return KittyCache(_ptr(self.pool), _ptr(self.page_table), _ptr(self.n_pages), _ptr(self.resid_k),
-                          _ptr(self.resid_v), _ptr(self.n_resid), self.batch, self.max_pages, self.n_pool_pages)
+                          _ptr(self.resid_v), _ptr(self.n_resid), _ptr(self.sink_k), _ptr(self.sink_v),
+                          _ptr(self.n_sink), self.batch, self.max_pages, self.n_pool_pages)
 
 
 def kitty_quantize_pages(layout: KittyLayout, k_src, v_src, page_stride: int, head_stride: int, token_stride: int,

@@ -90,3 +90,86 @@ def gpu_decode(layout, c, q_bits, sm_scale, n_splits=0, fp32=True):
     kitty.kitty_decode_attention(layout, c, q, out, sm_scale, ws, n_splits)
     torch.cuda.synchronize()
     return out.float().cpu().numpy()
+
+
+# ---------------------------------------------------------------------------------------------------
+# Full scheme (Sink + Value Local window): the oracle side is one KittyUnitOracle per (sequence, kv-head)
+# ---------------------------------------------------------------------------------------------------
+def unit_oracles(w, lengths, k, v, sink, local):
+    """Units fed token by token (steps 1 and 3 of the pipeline) with the first lengths[b] tokens, left in the
+    state attention sees right after the last insert (step 3 of that last step still pending).  Without a
+    residual window the cache is static and every token behind the Sink has been quantized."""
+    units = {}
+    for b in range(w.batch):
+        for h in range(w.n_kv_heads):
+            u = ko.KittyUnitOracle(w.n_boost, sink=sink, local=local, rank_metric=w.rank_metric)
+            n = lengths[b]
+            if n and w.residual_window == 0:       # static cache: everything behind the Sink is in pages
+                u.prefill(k[b, h, :n], v[b, h, :n])
+            elif n:
+                u.prefill(k[b, h, :n - 1], v[b, h, :n - 1])
+                u.insert(k[b, h, n - 1], v[b, h, n - 1])
+            units[(b, h)] = u
+    return units
+
+
+def units_attention(w, units, q_bits, sm_scale):
+    g = w.gqa
+    out = np.zeros((w.batch, w.n_q_heads, 128), np.float64)
+    for (b, h), u in units.items():
+        out[b, h * g:(h + 1) * g] = u.attention(q_bits[b, h * g:(h + 1) * g], sm_scale)
+    return out
+
+
+def gpu_full_cache(w, lengths, k, v, max_pages, sink, v_local, poison=True):
+    """Prefilled cache with a Sink of `sink` tokens and (v_local = 128) the Value Local window: the first tokens
+    go to the Sink, whole pages behind it through kitty_quantize_pages, the tail to the window; the bf16 Value
+    rows of the newest page are placed in their half of resid_v."""
+    import torch
+    from paper_2511_18643_amd import kitty
+    layout = kitty.make_layout(w.n_q_heads, w.n_kv_heads, w.n_boost, w.residual_window, w.rank_metric,
+                               sink_tokens=sink, v_local=v_local)
+    c = kitty.Cache(layout, w.batch, max_pages, w.batch * max_pages)
+    if poison:
+        c.pool.fill_(0xA5)
+    kt, vt = bf16_tensor(k), bf16_tensor(v)
+    lmax = k.shape[2]
+    offs, ids, npg, nres, nsk = [], [], [], [], []
+    for b in range(w.batch):
+        n = lengths[b]
+        s = min(n, sink)
+        post = n - s
+        if w.residual_window:
+            n_pages = max((post + 127) // 128 - 1, 0)
+        else:
+            assert post % 128 == 0
+            n_pages = post // 128
+        r = post - n_pages * 128
+        if s:
+            c.sink_k[b, :, :s] = kt[b, :, :s]
+            c.sink_v[b, :, :s] = vt[b, :, :s]
+        for i in range(n_pages):
+            offs.append(b * w.n_kv_heads * lmax * 128 + (s + i * 128) * 128)
+            ids.append(b * max_pages + i)
+        c.page_table[b, :n_pages] = torch.arange(n_pages, dtype=torch.int32, device="cuda") + b * max_pages
+        t0 = s + n_pages * 128
+        if r:
+            c.resid_k[b, :, :r] = kt[b, :, t0:t0 + r]
+            if v_local:
+                c.resid_v[b, :, n_pages & 1, :r] = vt[b, :, t0:t0 + r]
+            else:
+                c.resid_v[b, :, :r] = vt[b, :, t0:t0 + r]
+        if v_local and n_pages:
+            c.resid_v[b, :, (n_pages - 1) & 1] = vt[b, :, t0 - 128:t0]
+        npg.append(n_pages); nres.append(r); nsk.append(s)
+    c.n_pages.copy_(torch.tensor(npg, dtype=torch.int32))
+    if c.n_resid is not None:
+        c.n_resid.copy_(torch.tensor(nres, dtype=torch.int32))
+    if c.n_sink is not None:
+        c.n_sink.copy_(torch.tensor(nsk, dtype=torch.int32))
+    if ids:
+        kitty.kitty_quantize_pages(layout, kt, vt, 128 * 128, lmax * 128, 128,
+                                   torch.tensor(ids, dtype=torch.int32, device="cuda"), len(ids), c.pool, c.n_pool_pages,
+                                   src_page_offsets=torch.tensor(offs, dtype=torch.int64, device="cuda"))
+    torch.cuda.synchronize()
+    return layout, c
