@@ -31,9 +31,11 @@ HBM_PEAK_GBPS = 8000.0
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--steps", type=int, default=0, help="timed steps (default 200; 256 for c5)")
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4"])
+    ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4", "c5"],
+                    help="c5 = the 36-layer variable-length decode loop (a step = one token for every sequence through all layers)")
+    ap.add_argument("--layers", type=int, default=0, help="c5 only: number of layers (default 36)")
     ap.add_argument("--copies", type=int, default=0, help="cache copies to rotate over (0 = enough for >= 1.2 GB)")
     ap.add_argument("--n-splits", type=int, default=0)
     ap.add_argument("--src-seqs", type=int, default=2, help="distinct synthetic sequences tiled over the batch")
@@ -52,6 +54,7 @@ def parse():
                          "the CPU baseline leg is skipped)")
     ap.add_argument("--v-local", type=int, default=0, choices=[0, 128],
                     help="128: Values of the newest page are read from the bf16 Local window")
+    ap.add_argument("--no-seq-order", action="store_true", help="c5 only: dispatch sequences in batch order instead of longest first")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-pairs", type=int, default=0, help="(sequence, kv-head) pairs in the oracle sample (0 = auto)")
     return ap.parse_args()
@@ -94,6 +97,222 @@ def gpu_clocks(busy):
         return None
 
 
+def run_c5(args):
+    """Config 5: `layers` attention layers of a Qwen3-8B-shaped model, batch 128 with seeded lengths uniform in
+    [1024, 32768]; prefill through kitty_quantize_pages, then `steps` decode steps, each appending one token per
+    sequence and attending in every layer (kitty_decode_step: one launch per layer).  Every layer has its own
+    cache (pool, page table, windows); the caches are filled from two synthetic source sequences, shifted by one
+    page per layer.  Page ids are handed out per sequence from a contiguous run, as a serving engine's allocator
+    would: fresh id = run base + pages so far, computed on the device once per step."""
+    import torch
+    from paper_2511_18643_amd import kitty, synth
+    from tests import helpers as H
+    dev = "cuda"
+    w = synth.WORKLOADS["c5"]
+    layers = args.layers or synth.C5_LAYERS
+    steps = args.steps or synth.C5_STEPS
+    B, hkv, hq = w.batch, w.n_kv_heads, w.n_q_heads
+    layout = kitty.make_layout(hq, hkv, w.n_boost, w.residual_window, w.rank_metric)
+    payload, rec_bytes = kitty.kitty_page_payload_bytes(layout), kitty.kitty_page_bytes(layout)
+    lengths = synth.sequence_lengths(w)
+    total = args.warmup + steps
+    np0 = [(n + 127) // 128 - 1 for n in lengths]
+    r0 = [n - 128 * p for n, p in zip(lengths, np0)]
+    np_end = [(n + total + 127) // 128 - 1 for n in lengths]
+    max_pages = max(np_end) + 1
+    base = np.concatenate([[0], np.cumsum([p + 1 for p in np_end])]).astype(np.int64)   # one spare page per run
+    n_pool = int(base[-1])
+
+    t0 = time.time()
+    nsrc = 2
+    Ls = max(lengths) + 128 * layers
+    ksrc = np.zeros((nsrc, hkv, Ls, 128), np.uint16)
+    vsrc = np.zeros_like(ksrc)
+    for sb in range(nsrc):
+        for h in range(hkv):
+            ksrc[sb, h], vsrc[sb, h] = synth.kv_block(w, sb, h, Ls)
+    kt, vt = H.bf16_tensor(ksrc, dev), H.bf16_tensor(vsrc, dev)
+    gen_s = time.time() - t0
+
+    tq0 = time.time()
+    ids = torch.tensor([base[b] + i for b in range(B) for i in range(np0[b])], dtype=torch.int32, device=dev)
+    pt = torch.zeros((B, max_pages), dtype=torch.int32)
+    for b in range(B):
+        pt[b, :np0[b]] = torch.arange(np0[b], dtype=torch.int32) + int(base[b])
+    caches = []
+    for layer in range(layers):
+        c = kitty.Cache(layout, B, max_pages, n_pool, device=dev)
+        offs = torch.tensor([(b % nsrc) * hkv * Ls * 128 + (layer + i) * 128 * 128 for b in range(B) for i in range(np0[b])],
+                            dtype=torch.int64, device=dev)
+        kitty.kitty_quantize_pages(layout, kt, vt, 128 * 128, Ls * 128, 128, ids, ids.numel(), c.pool, n_pool,
+                                   src_page_offsets=offs)
+        c.page_table.copy_(pt)
+        c.n_pages.copy_(torch.tensor(np0, dtype=torch.int32))
+        c.n_resid.copy_(torch.tensor(r0, dtype=torch.int32))
+        for b in range(B):
+            a = (layer + np0[b]) * 128
+            c.resid_k[b, :, :r0[b]] = kt[b % nsrc, :, a:a + r0[b]]
+            c.resid_v[b, :, :r0[b]] = vt[b % nsrc, :, a:a + r0[b]]
+        caches.append(c)
+    # dispatch order: longest sequences first (every sequence grows by one token per step, so the order holds)
+    if not args.no_seq_order:
+        order = torch.argsort(caches[0].n_pages * 128 + caches[0].n_resid, descending=True).to(torch.int32)
+        for c in caches:
+            c.seq_order = order
+    torch.cuda.synchronize()
+    prefill_s = time.time() - tq0
+
+    ns, pps = kitty.kitty_decode_plan(layout, B, max_pages, args.n_splits)
+    ws = kitty.new_workspace(layout, B, max_pages, args.n_splits, device=dev)
+    n_rot = 4
+    qs = [H.bf16_tensor(synth.query(w, s), dev) for s in range(n_rot)]
+    new_np = [synth.new_token(w, s) for s in range(n_rot)]
+    newt = [tuple(H.bf16_tensor(x, dev) for x in kv) for kv in new_np]
+    out = torch.empty((B, hq, 128), dtype=torch.bfloat16, device=dev)
+    base_t = torch.tensor(base[:-1], dtype=torch.int32, device=dev)
+    fresh = torch.empty((B,), dtype=torch.int32, device=dev)
+
+    def launch_step(j):
+        torch.add(base_t, caches[0].n_pages, out=fresh)      # next free page of every sequence's run
+        kn, vn = newt[j]
+        for c in caches:
+            if args.two_calls:
+                kitty.kitty_append_token(layout, c, kn, vn, fresh)
+                kitty.kitty_decode_attention(layout, c, qs[j], out, w.sm_scale, ws, args.n_splits)
+            else:
+                kitty.kitty_decode_step(layout, c, kn, vn, fresh, qs[j], out, w.sm_scale, ws, args.n_splits)
+
+    graphs = None
+    if args.launch == "graph":      # one graph per input variant: 1 + layers kernel nodes each
+        snap = [(c.n_pages.clone(), c.n_resid.clone(), c.resid_k.clone(), c.resid_v.clone(), c.page_table.clone()) for c in caches]
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            launch_step(0)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graphs = []
+        for j in range(n_rot):
+            gph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gph):
+                launch_step(j)
+            graphs.append(gph)
+        torch.cuda.synchronize()
+        for c, (a, b_, k_, v_, p_) in zip(caches, snap):
+            c.n_pages.copy_(a); c.n_resid.copy_(b_); c.resid_k.copy_(k_); c.resid_v.copy_(v_); c.page_table.copy_(p_)
+        torch.cuda.synchronize()
+
+    st_np, st_r = list(np0), list(r0)
+
+    def do_step(i):
+        nbytes = 0
+        for b in range(B):
+            if st_r[b] == 128:
+                st_np[b] += 1
+                st_r[b] = 0
+            st_r[b] += 1
+            nbytes += st_np[b] * payload + st_r[b] * 512
+        if graphs is not None:
+            graphs[i % n_rot].replay()
+        else:
+            launch_step(i % n_rot)
+        return layers * (hkv * nbytes + 2 * B * hq * 256)
+
+    t_pre = time.perf_counter()
+    while (time.perf_counter() - t_pre) * 1e3 < args.prewarm_ms:
+        for c in caches[:4]:
+            kitty.kitty_decode_split(layout, c, qs[0], w.sm_scale, ws, args.n_splits)
+        torch.cuda.synchronize()
+    for i in range(args.warmup):
+        do_step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    total_bytes = 0
+    for i in range(args.warmup, total):
+        total_bytes += do_step(i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    # ---- the streaming kernel alone on the final state, HIP events on the launch stream ------------
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    kbytes = hkv * sum(p * payload + r * 512 for p, r in zip(st_np, st_r)) + 2 * B * hq * 256
+    for c in caches[:2]:
+        kitty.kitty_decode_split(layout, c, qs[0], w.sm_scale, ws, args.n_splits)
+    torch.cuda.synchronize()
+    reps = 3
+    ev0.record()
+    for _ in range(reps):
+        for c in caches:
+            kitty.kitty_decode_split(layout, c, qs[0], w.sm_scale, ws, args.n_splits)
+    ev1.record()
+    torch.cuda.synchronize()
+    kern_ms = ev0.elapsed_time(ev1) / (reps * layers)
+    kern_gbps = kbytes / (kern_ms * 1e-3) / 1e9
+
+    # ---- CPU oracle on a sample of layer 0: rebuilt from the inputs, appended tokens replayed ----------
+    cpu, max_err = None, None
+    if not args.no_cpu_baseline:
+        from oracle import kitty_oracle as ko
+        order = np.argsort(lengths)
+        sample_b = [int(x) for x in order[::max(len(order) // 32, 1)]] + [int(order[-1])]   # every 4th length + the longest
+        sample = [(b, h) for b in sample_b for h in (0, hkv - 1)]
+        g = w.gqa
+        out32 = torch.empty((B, hq, 128), dtype=torch.float32, device=dev)
+        kitty.kitty_decode_attention(layout, caches[0], qs[0], out32, w.sm_scale, ws, args.n_splits)
+        torch.cuda.synchronize()
+        got = out32.cpu().numpy()
+        qbits = synth.query(w, 0)
+        wall, cpu_used, sample_bytes, worst = 0.0, 0.0, 0, 0.0
+        for b, h in sample:
+            sb = b % nsrc
+            oc = ko.KittyCacheOracle(1, 1, g, w.n_boost, 128, max_pages, max_pages, w.rank_metric)
+            n_p = np0[b]
+            oc.quantize_pages(ksrc[sb, h, 0:n_p * 128].reshape(n_p, 1, 128, 128),
+                              vsrc[sb, h, 0:n_p * 128].reshape(n_p, 1, 128, 128), list(range(n_p)))
+            oc.page_table[0] = np.arange(max_pages); oc.n_pages[0] = n_p; oc.n_resid[0] = r0[b]
+            oc.resid_k[0, 0, :r0[b]] = ksrc[sb, h, n_p * 128:n_p * 128 + r0[b]]
+            oc.resid_v[0, 0, :r0[b]] = vsrc[sb, h, n_p * 128:n_p * 128 + r0[b]]
+            for i in range(total):
+                kn, vn = new_np[i % n_rot]
+                oc.append_token(kn[b:b + 1, h:h + 1], vn[b:b + 1, h:h + 1], np.array([oc.n_pages[0]]))
+            c0, w0 = time.process_time(), time.perf_counter()
+            want = oc.decode_attention(qbits[b:b + 1, h * g:(h + 1) * g], w.sm_scale)[0]
+            wall += time.perf_counter() - w0
+            cpu_used += time.process_time() - c0
+            worst = max(worst, float(np.abs(got[b, h * g:(h + 1) * g] - want).max()))
+            sample_bytes += int(oc.n_pages[0]) * payload + int(oc.n_resid[0]) * 512 + 2 * g * 256
+        max_err = worst
+        cpu = {"value": round(sample_bytes / wall / 1e9, 4), "unit": "GB/s",
+               "cores": max(1, int(round(cpu_used / max(wall, 1e-9)))), "kind": "oracle",
+               "sample": f"layer 0, {len(sample)} (sequence, kv-head) pairs (every fourth sequence by length, and the longest; "
+                         f"first and last kv-head) after the decode loop, all {g} query heads each, {wall:.1f} s wall "
+                         f"(decode attention only)"}
+
+    res = {
+        "metric": "decode_attn_effective_hbm_gbps", "value": round(total_bytes / dt / 1e9, 1), "unit": "GB/s",
+        "n_gpus": 1, "steps": steps, "warmup": args.warmup, "ms_per_step": round(dt / steps * 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "config": {
+            "workload": f"c5: {layers} layers, batch {B}, {hq}q/{hkv}kv heads, head_dim 128, lengths uniform in [1024, 32768] "
+                        f"(seeded; mean {np.mean(lengths):.0f}), n_boost {w.n_boost}, step = one token per sequence through "
+                        f"all layers ({'append_token + decode_attention' if args.two_calls else 'kitty_decode_step'} per layer, "
+                        f"{args.launch} launch)",
+            "n_splits": ns, "min_pages_per_split": pps, "record_bytes": rec_bytes, "payload_bytes_per_page": payload,
+            "cache_bytes_resident": int(layers * n_pool * hkv * rec_bytes), "distinct_source_sequences": nsrc,
+            "dispatch_order": "batch order" if args.no_seq_order else "longest sequence first (seq_order)",
+        },
+        "pct_of_hbm_peak": round(100.0 * total_bytes / dt / 1e9 / HBM_PEAK_GBPS, 2),
+        "decode_tokens_per_s": round(B * steps / dt, 1),
+        "roofline": {"bound": "hbm", "kernel": "decode_split_kernel", "achieved": round(kern_gbps, 1), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(kern_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "avg_launch_ms": round(kern_ms, 5), "algorithmic_bytes_per_launch": int(kbytes)},
+        "cpu_baseline": cpu,
+        "max_abs_err_vs_oracle_sample": max_err,
+        "setup_s": {"generate": round(gen_s, 1), "prefill_quantize_all_layers": round(prefill_s, 2)},
+    }
+    print(json.dumps(res))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -106,6 +325,9 @@ def main():
     kitty.lib()      # fails loudly if libkitty.so is missing
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda"
+    if args.workload == "c5":
+        return run_c5(args)
+    args.steps = args.steps or 200
     w = synth.WORKLOADS[args.workload]
     if args.n_boost >= 0:
         w = synth.scaled(w, n_boost=args.n_boost)

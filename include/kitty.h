@@ -59,6 +59,10 @@ typedef struct kitty_cache {
   void*    sink_k;       /* bf16 [batch][n_kv_heads][S][D] first S tokens of every sequence; NULL if S=0 */
   void*    sink_v;       /* same for Values                                                              */
   int32_t* n_sink;       /* [batch] valid Sink rows, 0..S; NULL if S=0                                   */
+  const int32_t* seq_order; /* optional [batch] permutation of 0..batch-1, or NULL (identity): the decode kernels
+                            dispatch their workgroups sequence by sequence in this order, so listing the longest
+                            sequences first shortens the tail of a variable-length batch.  Results do not depend on
+                            it; entries outside [0, batch) are skipped, repeated entries are the caller's error   */
   int32_t  batch;
   int32_t  max_pages;    /* row length of page_table                                                     */
   int32_t  n_pool_pages;

@@ -119,6 +119,7 @@ int fill_decode_params(const kitty_layout* L, const kitty_cache* C, int32_t n_sp
   P->sink_k = static_cast<const uint16_t*>(C->sink_k);
   P->sink_v = static_cast<const uint16_t*>(C->sink_v);
   P->n_sink = C->n_sink;
+  P->seq_order = C->seq_order;
   P->sink_cap = L->sink_tokens;
   P->v_local = L->v_local ? 1 : 0;
   P->sink_k_w = P->sink_v_w = nullptr;

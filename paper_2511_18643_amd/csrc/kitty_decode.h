@@ -35,6 +35,7 @@ struct DecodeParams {
   const uint16_t* sink_k;   // bf16 [batch][n_kv_heads][sink_cap][D], the first tokens of every sequence (Fig. 1: Sink)
   const uint16_t* sink_v;
   const int32_t* n_sink;
+  const int32_t* seq_order;  // optional permutation: block z serves sequence seq_order[z]
   const uint16_t* q;
   float* ws;
   void* out;
@@ -557,7 +558,9 @@ __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void
 
   __shared__ DecodeSmem<NB16, HPL, NW, FUSED> smem;
 
-  const int slot = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int slot = blockIdx.x, h = blockIdx.y;
+  const int b = p.seq_order ? p.seq_order[blockIdx.z] : (int)blockIdx.z;
+  if ((unsigned)b >= (unsigned)p.batch) return;   // not a sequence of this batch (same for the whole block)
   const int tid = threadIdx.x;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: page ids stay in scalar registers
   const int l = tid & 63, j = l & 15, gi = l >> 4;

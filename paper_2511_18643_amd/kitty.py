@@ -33,7 +33,7 @@ class KittyLayout(C.Structure):
 class KittyCache(C.Structure):
     _fields_ = [("page_pool", C.c_void_p), ("page_table", C.c_void_p), ("n_pages", C.c_void_p),
                 ("resid_k", C.c_void_p), ("resid_v", C.c_void_p), ("n_resid", C.c_void_p),
-                ("sink_k", C.c_void_p), ("sink_v", C.c_void_p), ("n_sink", C.c_void_p),
+                ("sink_k", C.c_void_p), ("sink_v", C.c_void_p), ("n_sink", C.c_void_p), ("seq_order", C.c_void_p),
                 ("batch", C.c_int32), ("max_pages", C.c_int32), ("n_pool_pages", C.c_int32)]
 
 
@@ -130,6 +130,7 @@ class Cache:
         if rb == 0:
             raise KittyError(ERR_UNSUPPORTED, "kitty_page_bytes")
         self.record_bytes = rb
+        self.seq_order = None      # optional int32 [batch] permutation: dispatch order of the decode kernels
         hkv, r = layout.n_kv_heads, layout.residual_window
         self.pool = torch.zeros((max(n_pool_pages, 1), hkv, rb), dtype=torch.uint8, device=device)
         self.page_table = torch.zeros((batch, max(max_pages, 1)), dtype=torch.int32, device=device)
@@ -151,7 +152,7 @@ class Cache:
     def struct(self) -> KittyCache:
         return KittyCache(_ptr(self.pool), _ptr(self.page_table), _ptr(self.n_pages), _ptr(self.resid_k),
                           _ptr(self.resid_v), _ptr(self.n_resid), _ptr(self.sink_k), _ptr(self.sink_v),
-                          _ptr(self.n_sink), self.batch, self.max_pages, self.n_pool_pages)
+                          _ptr(self.n_sink), _ptr(self.seq_order), self.batch, self.max_pages, self.n_pool_pages)
 
 
 def kitty_quantize_pages(layout: KittyLayout, k_src, v_src, page_stride: int, head_stride: int, token_stride: int,

@@ -60,7 +60,18 @@ WORKLOADS = {
     # Llama-3-70B-shaped layer, 128k context, 25 % boost, outlier set changes page to page
     "c4": Workload("c4", 8, 64, 8, 131072, 32, 128, 0, INV_SQRT_D, 1.0, 8, 8.0, 0.1,
                    varying_outliers=True, seed=404),
+    # Qwen3-8B-shaped decode loop: 36 layers of this shape, variable-length batch (see sequence_lengths)
+    "c5": Workload("c5", 128, 32, 8, 0, 16, 128, 0, INV_SQRT_D, 1.0, 6, 8.0, 0.1, seed=505),
 }
+
+C5_LAYERS = 36
+C5_STEPS = 256
+
+
+def sequence_lengths(w: Workload, lo: int = 1024, hi: int = 32768) -> list:
+    """Seeded context lengths of a variable-length batch, uniform in [lo, hi]."""
+    r = _rng(w.seed, 993)
+    return [int(x) for x in r.integers(lo, hi + 1, size=w.batch)]
 
 
 def to_bf16_bits(x: np.ndarray) -> np.ndarray:

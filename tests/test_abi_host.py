@@ -80,16 +80,16 @@ def test_invalid_arguments_return_codes_without_touching_a_gpu():
     # misaligned source, stride not a multiple of 8
     assert lib.kitty_quantize_pages(C.byref(lay), 0x1008, 0x2000, 16384, 16384, 128, None, 0x3000, 1, 0x4000, 1, None) == kitty.ERR_INVALID_ARG
     assert lib.kitty_quantize_pages(C.byref(lay), 0x1000, 0x2000, 16384, 16384, 132, None, 0x3000, 1, 0x4000, 1, None) == kitty.ERR_INVALID_ARG
-    cache = kitty.KittyCache(None, None, None, None, None, None, None, None, None, 4, 8, 32)
+    cache = kitty.KittyCache(None, None, None, None, None, None, None, None, None, None, 4, 8, 32)
     assert lib.kitty_decode_attention(C.byref(lay), C.byref(cache), None, None, 1.0, 0, 0, None, 0, None) == kitty.ERR_INVALID_ARG
     assert lib.kitty_append_token(C.byref(lay), None, None, None, None, None) == kitty.ERR_INVALID_ARG
     assert lib.kitty_decode_split(C.byref(lay), C.byref(cache), None, 1.0, 0, None, 0, None) == kitty.ERR_INVALID_ARG
     # a complete-looking cache with a workspace that is too small
-    cache = kitty.KittyCache(0x10000, 0x20000, 0x30000, 0x40000, 0x50000, 0x60000, None, None, None, 4, 8, 32)
+    cache = kitty.KittyCache(0x10000, 0x20000, 0x30000, 0x40000, 0x50000, 0x60000, None, None, None, None, 4, 8, 32)
     assert lib.kitty_decode_split(C.byref(lay), C.byref(cache), 0x70000, 1.0, 0, 0x80000, 64, None) == kitty.ERR_WORKSPACE
     assert lib.kitty_decode_merge(C.byref(lay), C.byref(cache), 0x70000, 0, 5, 0x80000, 1 << 30, None) == kitty.ERR_INVALID_ARG
     lay0 = kitty.make_layout(32, 8, 16, residual_window=0)
-    cache0 = kitty.KittyCache(0x10000, 0x20000, 0x30000, None, None, None, None, None, None, 4, 8, 32)
+    cache0 = kitty.KittyCache(0x10000, 0x20000, 0x30000, None, None, None, None, None, None, None, 4, 8, 32)
     assert lib.kitty_append_token(C.byref(lay0), C.byref(cache0), 0x1000, 0x2000, 0x3000, None) == kitty.ERR_UNSUPPORTED
     # a Sink in the layout needs the Sink buffers in the cache
     lay_s = kitty.make_layout(32, 8, 16, sink_tokens=32)

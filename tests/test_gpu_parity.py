@@ -326,3 +326,48 @@ def test_variable_length_decode_loop_c5_shape():
         torch.cuda.synchronize()
         check_pool(w, None, oc, gc)
         assert np.array_equal(gc.page_table.cpu().numpy()[:, :max_pages], oc.page_table)
+
+
+def test_seq_order_changes_dispatch_not_results():
+    """seq_order only permutes which workgroup serves which sequence: outputs and the appended state are
+    bit-identical to the identity order; entries outside the batch are skipped."""
+    import torch
+    from paper_2511_18643_amd import kitty
+    w = synth.scaled(synth.WORKLOADS["c2"], batch=5, n_q_heads=8, n_kv_heads=2, context=0)
+    lengths = [128 * 3 + 5, 0, 128 * 20 + 128, 77, 128 * 7 + 1]
+    k, v = H.gen_sequences(w, lengths)
+    max_pages = 24
+    q = H.bf16_tensor(synth.query(w))
+    kn, vn = (H.bf16_tensor(x) for x in synth.new_token(w, 1))
+    results = []
+    for order in (None, [2, 4, 0, 3, 1]):
+        layout, gc = H.gpu_cache(w, lengths, k, v, max_pages)
+        if order is not None:
+            gc.seq_order = torch.tensor(order, dtype=torch.int32, device="cuda")
+        ws = kitty.new_workspace(layout, 5, max_pages)
+        outs = []
+        for ns in (0, 3):
+            out = torch.full((5, 8, 128), float("nan"), dtype=torch.float32, device="cuda")
+            kitty.kitty_decode_attention(layout, gc, q, out, w.sm_scale, kitty.new_workspace(layout, 5, max_pages, ns), ns)
+            outs.append(out.cpu().numpy())
+        fresh = torch.tensor([b * max_pages + (n + 127) // 128 - 1 if n else b * max_pages for b, n in enumerate(lengths)],
+                             dtype=torch.int32, device="cuda")
+        out = torch.empty((5, 8, 128), dtype=torch.float32, device="cuda")
+        kitty.kitty_decode_step(layout, gc, kn, vn, fresh, q, out, w.sm_scale, ws)
+        torch.cuda.synchronize()
+        outs.append(out.cpu().numpy())
+        results.append((outs, gc.n_pages.cpu().numpy(), gc.n_resid.cpu().numpy(), gc.pool.cpu().numpy()))
+    (o0, np0, nr0, pool0), (o1, np1, nr1, pool1) = results
+    for a, b in zip(o0, o1):
+        assert np.array_equal(a, b)
+    assert np.array_equal(np0, np1) and np.array_equal(nr0, nr1) and np.array_equal(pool0, pool1)
+    assert list(nr0) == [6, 1, 1, 78, 2] and list(np0) == [3, 0, 21, 0, 7]
+    # an order that names sequence 3 never and holds an entry outside the batch
+    layout, gc = H.gpu_cache(w, lengths, k, v, max_pages)
+    gc.seq_order = torch.tensor([2, 0, 99, 1, 4], dtype=torch.int32, device="cuda")
+    out = torch.full((5, 8, 128), float("nan"), dtype=torch.float32, device="cuda")
+    kitty.kitty_decode_attention(layout, gc, q, out, w.sm_scale, kitty.new_workspace(layout, 5, max_pages))
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert np.isnan(got[3]).all()
+    assert np.array_equal(got[[0, 1, 2, 4]], o0[0][[0, 1, 2, 4]])
