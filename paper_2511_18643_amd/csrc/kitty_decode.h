@@ -94,26 +94,42 @@ __device__ __forceinline__ LaneOffsets lane_offsets(int l) {
 
 // A page is fetched in three pieces: the lane's 16 bytes of fp16 arrays, the Key planes (+ channel list), the
 // Value plane.  Each piece of the next page is requested as soon as the registers of the current one are dead.
+// Records are addressed through a buffer resource (base = the record, size = its bytes): the loads take the
+// scalar descriptor, one 32-bit lane offset and a constant, so no vector address arithmetic is needed, and a
+// descriptor of size 0 ("no next page") makes every load return zeros without touching memory.
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+typedef unsigned int v2u __attribute__((ext_vector_type(2)));
+using RecRef = __amdgpu_buffer_rsrc_t;
 template <int NB16>
-__device__ __forceinline__ uint4 load_meta(const uint8_t* __restrict__ rec, const LaneOffsets& o) {
-  return *reinterpret_cast<const uint4*>(rec + o.meta);
+__device__ __forceinline__ RecRef rec_ref(const uint8_t* rec, bool present) {
+  // word 3 of a gfx9-family raw buffer descriptor: 32-bit data format, no swizzle, range-checked by byte offset
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(rec), 0, present ? Rec<NB16>::bytes : 0, 0x00020000);
+}
+__device__ __forceinline__ uint4 buf_load16(RecRef r, uint32_t voff, int soff) {
+  const v4u v = __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0);
+  return make_uint4(v.x, v.y, v.z, v.w);
 }
 template <int NB16>
-__device__ __forceinline__ void load_k(PageRegs<NB16>& r, const uint8_t* __restrict__ rec, const LaneOffsets& o) {
+__device__ __forceinline__ uint4 load_meta(RecRef rec, const LaneOffsets& o) {
+  return buf_load16(rec, o.meta, 0);
+}
+template <int NB16>
+__device__ __forceinline__ void load_k(PageRegs<NB16>& r, RecRef rec, const LaneOffsets& o) {
   using R = Rec<NB16>;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) r.kd[i] = *reinterpret_cast<const uint4*>(rec + R::kd + 1024 * i + o.o16);
+  for (int i = 0; i < 4; ++i) r.kd[i] = buf_load16(rec, o.o16, R::kd + 1024 * i);
 #pragma unroll
   for (int s = 0; s < NB16; ++s) {
-    r.kb[s] = *reinterpret_cast<const uint2*>(rec + R::kb + 512 * s + o.o8);
-    r.chv[s] = rec[R::ch + 16 * s + o.j];
+    const v2u v = __builtin_amdgcn_raw_buffer_load_b64(rec, o.o8, R::kb + 512 * s, 0);
+    r.kb[s] = make_uint2(v.x, v.y);
+    r.chv[s] = __builtin_amdgcn_raw_buffer_load_b8(rec, o.j, R::ch + 16 * s, 0);
   }
 }
 template <int NB16>
-__device__ __forceinline__ void load_v(PageRegs<NB16>& r, const uint8_t* __restrict__ rec, const LaneOffsets& o) {
+__device__ __forceinline__ void load_v(PageRegs<NB16>& r, RecRef rec, const LaneOffsets& o) {
   using R = Rec<NB16>;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) r.vd[i] = *reinterpret_cast<const uint4*>(rec + R::vd + 1024 * i + o.o16);
+  for (int i = 0; i < 4; ++i) r.vd[i] = buf_load16(rec, o.o16, R::vd + 1024 * i);
 }
 
 // sixteen 2-bit elements -> four registers of four int8 each (elements 4v..4v+3 in register v)
@@ -197,6 +213,14 @@ __device__ __forceinline__ void f16x8_to_f32(const uint4& v, float (&f)[8]) {
   }
 }
 
+// x = x * a + b written over x.  The compiler otherwise accumulates into the register of b (the two-operand
+// form) and copies the result back for the next loop iteration, one move per running sum and page.  The operands
+// are results of ordinary vector instructions (never of a matrix instruction, whose hazards the assembler does
+// not track through inline code).
+__device__ __forceinline__ void fma_in_place(float& x, float a, float b) {
+  asm("v_fma_f32 %0, %0, %1, %2" : "+v"(x) : "v"(a), "v"(b));
+}
+
 __device__ __forceinline__ void wave_lds_fence() {
   // LDS traffic of one wavefront is processed in order; this only stops the compiler from moving
   // a lane's read above another lane's write.
@@ -274,7 +298,8 @@ struct PageWorker {
   float wA, wB, oA, oB;      // weights of the lane's two halves and their log2
   float qv[HPL][8];          // q * sm_scale * log2(e) divided by the weight, compact layout
   float m_run[HPL], l_run[HPL], z_run[HPL];
-  float acc[HPL][8];         // channel 16*Td + j
+  float acc[HPL][8];         // channel 16*Td + j, in units of acc_unit (the fixed-point step of the last page's p*s)
+  float acc_unit[HPL];
 
   static constexpr int A_PASS = 16 * 144;                           // bytes between the two matrices
   static constexpr int B_PASS = 16 * (16 * (NB16 ? NB16 : 1) + 16);
@@ -292,7 +317,7 @@ struct PageWorker {
     oB = WEIGHTED ? (odd ? 0.f : 2.f) : 0.f;
 #pragma unroll
     for (int e = 0; e < HPL; ++e) {
-      m_run[e] = -INFINITY; l_run[e] = 0.f; z_run[e] = 0.f;
+      m_run[e] = -INFINITY; l_run[e] = 0.f; z_run[e] = 0.f; acc_unit[e] = 1.f;
 #pragma unroll
       for (int k = 0; k < 8; ++k) acc[e][k] = 0.f;
     }
@@ -443,8 +468,9 @@ struct PageWorker {
   }
 
   // Processes the page held in `pg` (its fp16 arrays already staged in LDS).  The pieces of the wavefront's
-  // next page (record `rec_nx`, if `has_nx`) are requested into the same registers as soon as they are dead.
-  __device__ __forceinline__ void process(PageRegs<NB16>& pg, const uint8_t* rec_nx, bool has_nx) {
+  // next page (record `rec_nx`; an empty reference if there is none) are requested into the same registers as
+  // soon as they are dead.
+  __device__ __forceinline__ void process(PageRegs<NB16>& pg, RecRef rec_nx, bool has_nx) {
     uint4 meta_nx = make_uint4(0, 0, 0, 0);
     if (has_nx) meta_nx = load_meta<NB16>(rec_nx, lo);
     v4i dq[8], dqx[TWO_PASS ? 8 : 1];
@@ -455,7 +481,7 @@ struct PageWorker {
     float vs[8], vz[8];
     f16x8_to_f32(*reinterpret_cast<const uint4*>(&ws.meta[2][16 * j]), vs);
     f16x8_to_f32(*reinterpret_cast<const uint4*>(&ws.meta[3][16 * j]), vz);
-    float corr[HPL], inv_beta[HPL];
+    float corr[HPL], rescale[HPL];
 #pragma unroll
     for (int e = 0; e < HPL; ++e) {
       // logits are inv_alpha * nl + bias with inv_alpha > 0: take the maximum on the integers
@@ -484,11 +510,14 @@ struct PageWorker {
         pmA = fmaxf(pmA, ps[T]); pmB = fmaxf(pmB, ps[T + 4]);
       }
       float psum = fmaf(psA, wA, psB * wB), zsum = fmaf(zsA, wA, zsB * wB), pmax = fmaxf(pmA * wA, pmB * wB);
-      l_run[e] = fmaf(l_run[e], corr[e], psum);
-      z_run[e] = fmaf(z_run[e], corr[e], zsum);
-      pmax = fmaxf(row_max_nonneg(pmax), 1e-30f);
+      fma_in_place(l_run[e], corr[e], psum);
+      fma_in_place(z_run[e], corr[e], zsum);
+      // (the floor keeps the running sums, which are held in units of pmax / NLIM, far from overflow; a page
+      // whose weights are all below it contributes less than 1e-12 of the total)
+      pmax = fmaxf(row_max_nonneg(pmax), 1e-12f);
       const float beta = NLIM * __builtin_amdgcn_rcpf(pmax);
-      inv_beta[e] = pmax * (1.0f / NLIM);
+      rescale[e] = corr[e] * acc_unit[e] * beta;       // old unit -> new unit, and the softmax correction
+      acc_unit[e] = pmax * (1.0f / NLIM);
       uint32_t u[8];
 #pragma unroll
       for (int T = 0; T < 8; ++T) u[T] = __float_as_uint(fmaf(ps[T], beta, MAGIC));
@@ -525,7 +554,7 @@ struct PageWorker {
         if constexpr (HPL == 1) ne = join_terms(c[0], c[1], c[2]);
         else if constexpr (TWO_PASS) ne = join_terms(c[2 * e], c[2 * e + 1], cx[e]);
         else ne = join_terms(c[2 * e], c[2 * e + 1]);
-        acc[e][Td] = fmaf(acc[e][Td], corr[e], (float)ne * inv_beta[e]);
+        fma_in_place(acc[e][Td], rescale[e], (float)ne);
       }
     }
     if (has_nx) {
@@ -549,7 +578,8 @@ constexpr int decode_waves_per_simd() { return 2; }
 // into the fresh page, store the new token), then attends over the result; needs one range per (sequence,
 // kv-head), i.e. grid.x == 1 and direct_out.  The new token's row is taken from k_new / v_new directly, a
 // freshly written record is fenced before it is read back, and the sequence state is advanced by the block of
-// the sequence that finishes last (ticket in bits 8.. of n_resid, as in append_token_kernel).
+// the sequence that is last to have read the old state (ticket in bits 8.. of n_resid, as in append_token_kernel;
+// the ticket is taken right after the state has been read and looked at only at the end).
 template <int NB16, int HPL, int NW, bool FUSED>
 __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void decode_split_kernel(DecodeParams p) {
   using R = Rec<NB16>;
@@ -578,6 +608,10 @@ __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void
   bool ok = true, flush = false;
   const uint16_t* knew_h = nullptr;
   const uint16_t* vnew_h = nullptr;
+  // the new token's copy into the cache (threads 0..31 hold 16 bytes each): fetched here, stored at the end of
+  // the kernel, so that nobody waits for the round trip; attention reads the token from k_new / v_new itself
+  uint4 keep_val = make_uint4(0, 0, 0, 0);
+  uint16_t* keep_dst = nullptr;
   if constexpr (FUSED) {
     const int32_t pid = p.fresh_page_ids[b];
     knew_h = p.k_new + pair * D;
@@ -585,9 +619,8 @@ __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void
     if (ns_old < p.sink_cap) {    // the Sink is not full: the token goes there and nothing else changes
       if (tid < 32) {
         const int part = tid & 15;
-        const uint16_t* src = (tid < 16 ? knew_h : vnew_h) + part * 8;
-        uint16_t* dst = (tid < 16 ? p.sink_k_w : p.sink_v_w) + (pair * p.sink_cap + ns_old) * D + part * 8;
-        *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
+        keep_val = *reinterpret_cast<const uint4*>((tid < 16 ? knew_h : vnew_h) + part * 8);
+        keep_dst = (tid < 16 ? p.sink_k_w : p.sink_v_w) + (pair * p.sink_cap + ns_old) * D + part * 8;
       }
       newsink = ns_old;
       ns = ns_old + 1;
@@ -613,12 +646,19 @@ __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void
         if (tid < 32) {             // keep the token for the following steps
           const int part = tid & 15;
           uint16_t* wvw = p.resid_v_w + resid_v_offset(b, h, p.n_kv_heads, p.v_local, np);
-          const uint16_t* src = (tid < 16 ? knew_h : vnew_h) + part * 8;
-          uint16_t* dst = (tid < 16 ? wkw : wvw) + (size_t)newrow * D + part * 8;
-          *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
+          keep_val = *reinterpret_cast<const uint4*>((tid < 16 ? knew_h : vnew_h) + part * 8);
+          keep_dst = (tid < 16 ? wkw : wvw) + (size_t)newrow * D + part * 8;
         }
       }
     }
+  }
+  // Every block of the sequence has to see the old state, so the state is advanced by the block that is last to
+  // have read it: a ticket is taken here (its answer is not needed before the end of the kernel, which hides
+  // the round trip of the atomic), and the holder of the last ticket stores the new state when it is done.
+  int ticket = 0;
+  if constexpr (FUSED) {
+    __syncthreads();            // all wavefronts of this block have read the state (they branched on it above)
+    if (tid == 0) ticket = atomicAdd(&p.n_resid_w[b], 1 << TICKET_SHIFT);
   }
   const int nfp = ns + r;       // rows read in full precision for both Keys and Values: Sink, then window
   const int sb = active_splits(np, nfp, p.n_splits, p.min_pages);
@@ -650,11 +690,18 @@ __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void
     const int32_t* pt = p.page_table + (size_t)b * p.max_pages;
     const size_t rec_stride = (size_t)p.n_kv_heads * R::bytes;
     const uint8_t* pool_h = p.pool + (size_t)h * R::bytes;
-    auto rec_of = [&](int idx) {
-      const int32_t id = (FUSED && idx == np_old && fresh_pid >= 0) ? fresh_pid : pt[idx];
+    // Page ids of this wavefront's pages: lane k of `ids` holds the id of its k-th page (64 at a time), so the
+    // loop takes them from a register with v_readlane instead of waiting for a scalar load per page.
+    auto load_ids = [&](int first) {
+      const int i = p0 + w + NW * (first + l);
+      return i < p1 ? pt[i] : 0;
+    };
+    int32_t ids = load_ids(0);
+    auto rec_at = [&](int k, int idx) {     // record of the wavefront's k-th page, which is page idx of the sequence
+      const int32_t got = __builtin_amdgcn_readlane(ids, k & 63);
+      const int32_t id = (FUSED && idx == np_old && fresh_pid >= 0) ? fresh_pid : got;
       return pool_h + (size_t)id * rec_stride;
     };
-
     // one register buffer: each piece of the next page is requested when the current page no longer needs it.
     PageRegs<NB16> pg{};
     int idx = p0 + w;
@@ -675,7 +722,7 @@ __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void
       pw.set_q(e, raw, p.qk_scale_log2, live);
     }
     if (idx < p1) {
-      const uint8_t* rec = rec_of(idx);
+      const RecRef rec = rec_ref<NB16>(rec_at(0, idx), true);
       m0 = load_meta<NB16>(rec, pw.lo);
       load_k<NB16>(pg, rec, pw.lo);
       load_v<NB16>(pg, rec, pw.lo);
@@ -685,11 +732,14 @@ __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void
       // priorities the older one wins every conflict and ends its (equal) share of the pages ~6 % earlier,
       // leaving the block to wait for the younger one.
       int turn = w / 4;
+      int k = 0;
       for (; idx < p1q; idx += NW) {
         const bool has_nx = idx + NW < p1;
         if (turn & 1) __builtin_amdgcn_s_setprio(1); else __builtin_amdgcn_s_setprio(0);
         ++turn;
-        pw.process(pg, has_nx ? rec_of(idx + NW) : pool_h, has_nx);
+        ++k;
+        if ((k & 63) == 0) ids = load_ids(k);
+        pw.process(pg, rec_ref<NB16>(has_nx ? rec_at(k, idx + NW) : pool_h, true), has_nx);
       }
       __builtin_amdgcn_s_setprio(0);
       if (lag_here && idx == p1q) pw.logits_to(pg, lagx);   // this wavefront holds the newest page
@@ -852,7 +902,7 @@ __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void
   for (int e = 0; e < HPL; ++e) {
     const int hd = gi * HPL + e;
 #pragma unroll
-    for (int Td = 0; Td < 8; ++Td) mg.acc[w][hd][16 * Td + j] = pw.acc[e][Td] + zsum[e];
+    for (int Td = 0; Td < 8; ++Td) mg.acc[w][hd][16 * Td + j] = fmaf(pw.acc[e][Td], pw.acc_unit[e], zsum[e]);
     if (j == 0) { mg.m[w][hd] = pw.m_run[e]; mg.l[w][hd] = lsum[e]; mg.m[NW + w][hd] = mw[e]; mg.l[NW + w][hd] = lwsum[e]; }
   }
 #pragma unroll
@@ -892,10 +942,9 @@ __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void
     }
   }
   if constexpr (FUSED) {
-    __syncthreads();
+    if (keep_dst) *reinterpret_cast<uint4*>(keep_dst) = keep_val;
     if (tid == 0) {
-      const int old = atomicAdd(&p.n_resid_w[b], 1 << TICKET_SHIFT);
-      if ((old >> TICKET_SHIFT) == p.n_kv_heads - 1) {   // every block of this sequence is done with the old state
+      if ((ticket >> TICKET_SHIFT) == p.n_kv_heads - 1) {   // every block of this sequence has read the old state
         int new_nr = nr_old;
         if (newsink >= 0) {
           p.n_sink_w[b] = ns_old + 1;
