@@ -25,13 +25,35 @@ __device__ __forceinline__ float tile_elem(const QuantSmem& s, int t, int c) {
 
 // code = clamp(rint((x - zero) * inv), 0, qmax), inv = 1/scale rounded once (IEEE), 0 for a zero scale.
 // fp32 subtract and multiply, ties to even; with inv == 0 every code is 0.
-__device__ __forceinline__ uint32_t qcode(float x, float inv, float z, float qmax) {
-  const float r = rintf(__fmul_rn(__fsub_rn(x, z), inv));
-  return (uint32_t)fminf(fmaxf(r, 0.0f), qmax);
+// qcode_bits returns the raw bits of clamp((x - zero) * inv, 0, qmax) + 1.5 * 2^23: the addition rounds to
+// the nearest integer, ties to even, and leaves that integer in the low byte (clamping first gives the same
+// integer as rounding first, because the bounds are integers).
+__device__ __forceinline__ uint32_t qcode_bits(float x, float inv, float z, float qmax) {
+  const float f = __builtin_amdgcn_fmed3f(__fmul_rn(__fsub_rn(x, z), inv), 0.0f, qmax);
+  return __float_as_uint(__fadd_rn(f, 12582912.0f));
 }
-__device__ __forceinline__ float inv_scale(float s) { return s > 0.0f ? __fdiv_rn(1.0f, s) : 0.0f; }
 
-__device__ __forceinline__ int elem_shift(int a) { return 8 * (a & 3) + 2 * (a >> 2); }
+// Sixteen codes on their way into one packed word.  Register v collects the low bytes of elements 4v..4v+3
+// (three byte permutes per four codes); the word takes the low two bits of every byte of register v at bit
+// offset 2v (low plane), or bits 2..3 (high plane of 4-bit codes).
+struct Pack16 {
+  uint32_t u[16];
+  __device__ __forceinline__ void put(int a, uint32_t bits) { u[a] = bits; }
+  __device__ __forceinline__ uint32_t bytes(int v) const {
+    const uint32_t lo = __builtin_amdgcn_perm(u[4 * v + 1], u[4 * v], 0x0c0c0400u);
+    const uint32_t hi = __builtin_amdgcn_perm(u[4 * v + 3], u[4 * v + 2], 0x0c0c0400u);
+    return __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+  }
+  __device__ __forceinline__ uint32_t low() const {
+    constexpr uint32_t m = 0x03030303u;
+    return (bytes(0) & m) | ((bytes(1) & m) << 2) | ((bytes(2) & m) << 4) | ((bytes(3) & m) << 6);
+  }
+  __device__ __forceinline__ uint32_t high() const {
+    constexpr uint32_t m = 0x0c0c0c0cu;
+    return ((bytes(0) & m) >> 2) | (bytes(1) & m) | ((bytes(2) & m) << 2) | ((bytes(3) & m) << 4);
+  }
+};
+__device__ __forceinline__ float inv_scale(float s) { return s > 0.0f ? __fdiv_rn(1.0f, s) : 0.0f; }
 
 // src: bf16 rows of 128 channels, row t at src + t*token_stride (elements), 16-byte aligned.
 __device__ __forceinline__ void load_tile(QuantSmem& s, const uint16_t* __restrict__ src, int64_t token_stride, int tid) {
@@ -123,15 +145,15 @@ __device__ void quantize_page(QuantSmem& s, const uint16_t* __restrict__ ksrc, c
 #pragma unroll
       for (int tsel = 0; tsel < 2; ++tsel) {
         const int t = 32 * q + 16 * tsel + (lane & 15);
-        uint32_t word = 0;
+        Pack16 pk;
 #pragma unroll
         for (int a2 = 0; a2 < 8; ++a2) {
           const uint32_t two = s.tile[t * 65 + 8 * cb + a2];
           const float x0 = __uint_as_float(two << 16), x1 = __uint_as_float(two & 0xffff0000u);
-          word |= (qcode(x0, inv[2 * a2], zr[2 * a2], qm[2 * a2]) & 3u) << elem_shift(2 * a2);
-          word |= (qcode(x1, inv[2 * a2 + 1], zr[2 * a2 + 1], qm[2 * a2 + 1]) & 3u) << elem_shift(2 * a2 + 1);
+          pk.put(2 * a2, qcode_bits(x0, inv[2 * a2], zr[2 * a2], qm[2 * a2]));
+          pk.put(2 * a2 + 1, qcode_bits(x1, inv[2 * a2 + 1], zr[2 * a2 + 1], qm[2 * a2 + 1]));
         }
-        w[2 * tsel + csel] = word;
+        w[2 * tsel + csel] = pk.low();
       }
     }
     reinterpret_cast<uint4*>(rec + R::kd)[64 * q + lane] = make_uint4(w[0], w[1], w[2], w[3]);
@@ -141,13 +163,13 @@ __device__ void quantize_page(QuantSmem& s, const uint16_t* __restrict__ ksrc, c
       for (int idx = tid; idx < 128 * NB16; idx += 256) {
         const int sblk = idx >> 7, u = (idx >> 6) & 1, lane = idx & 63;
         const int t = 16 * (4 * u + (lane >> 4)) + (lane & 15);
-        uint32_t word = 0;
+        Pack16 pk;
 #pragma unroll
         for (int a = 0; a < 16; ++a) {
           const int ch = s.chl[16 * sblk + a];
-          word |= (qcode(tile_elem(s, t, ch), s.inv[ch], s.zr[ch], 15.0f) >> 2) << elem_shift(a);
+          pk.put(a, qcode_bits(tile_elem(s, t, ch), s.inv[ch], s.zr[ch], 15.0f));
         }
-        *reinterpret_cast<uint32_t*>(rec + R::kb + 512 * sblk + 8 * lane + 4 * u) = word;
+        *reinterpret_cast<uint32_t*>(rec + R::kb + 512 * sblk + 8 * lane + 4 * u) = pk.high();
       }
     }
   }
@@ -199,14 +221,14 @@ __device__ void quantize_page(QuantSmem& s, const uint16_t* __restrict__ ksrc, c
 #pragma unroll
       for (int dsel = 0; dsel < 2; ++dsel) {
         const int d = 32 * q + 16 * dsel + (lane & 15);
-        uint32_t word = 0;
+        Pack16 pk;
 #pragma unroll
         for (int a = 0; a < 16; ++a) {
           const int p = 16 * wv + a;
           const int t = 16 * (p & 7) + (p >> 3);
-          word |= qcode(tile_elem(s, t, d), inv[a], zr[a], 3.0f) << elem_shift(a);
+          pk.put(a, qcode_bits(tile_elem(s, t, d), inv[a], zr[a], 3.0f));
         }
-        w[2 * dsel + vsel] = word;
+        w[2 * dsel + vsel] = pk.low();
       }
     }
     reinterpret_cast<uint4*>(rec + R::vd)[64 * q + lane] = make_uint4(w[0], w[1], w[2], w[3]);
