@@ -371,3 +371,36 @@ def test_seq_order_changes_dispatch_not_results():
     got = out.cpu().numpy()
     assert np.isnan(got[3]).all()
     assert np.array_equal(got[[0, 1, 2, 4]], o0[0][[0, 1, 2, 4]])
+
+
+def test_quantize_pages_reads_projection_layout_in_place():
+    """Prefill without a repacking copy: K/V as a projection GEMM leaves them, [tokens][kv-heads][D] (token
+    stride Hkv*D, head stride D), with per-page source offsets for two sequences of different length stored
+    back to back; records must equal the oracle's on the same tokens."""
+    import torch
+    from paper_2511_18643_amd import kitty
+    w = synth.scaled(synth.WORKLOADS["c2"], batch=2, n_q_heads=8, n_kv_heads=4, context=0)
+    lens = [3 * 128, 5 * 128]
+    hkv = 4
+    k, v = H.gen_sequences(w, lens)                       # [B][Hkv][L][D]
+    flat_k = np.concatenate([k[b, :, :lens[b]].transpose(1, 0, 2) for b in range(2)], axis=0)   # [tokens][Hkv][D]
+    flat_v = np.concatenate([v[b, :, :lens[b]].transpose(1, 0, 2) for b in range(2)], axis=0)
+    kt, vt = H.bf16_tensor(flat_k), H.bf16_tensor(flat_v)
+    layout = kitty.make_layout(8, hkv, w.n_boost, 128, w.rank_metric)
+    n_pages = sum(lens) // 128
+    pool = torch.full((n_pages, hkv, kitty.kitty_page_bytes(layout)), 0xA5, dtype=torch.uint8, device="cuda")
+    tok0 = [0, lens[0]]
+    offs = torch.tensor([(tok0[b] + 128 * i) * hkv * 128 for b in range(2) for i in range(lens[b] // 128)],
+                        dtype=torch.int64, device="cuda")
+    ids = torch.arange(n_pages, dtype=torch.int32, device="cuda")
+    kitty.kitty_quantize_pages(layout, kt, vt, 0, 128, hkv * 128, ids, n_pages, pool, n_pages, src_page_offsets=offs)
+    torch.cuda.synchronize()
+    got = pool.cpu().numpy()
+    pid = 0
+    for b in range(2):
+        for i in range(lens[b] // 128):
+            for h in range(hkv):
+                kp = ko.quantize_k_page(ko.bf16_bits_to_f32(k[b, h, 128 * i:128 * (i + 1)]), w.n_boost, w.rank_metric)
+                vp = ko.quantize_v_page(ko.bf16_bits_to_f32(v[b, h, 128 * i:128 * (i + 1)]))
+                assert np.array_equal(got[pid, h], ko.pack_record(kp, vp)), (b, i, h)
+            pid += 1
