@@ -81,7 +81,8 @@ size_t kitty_page_payload_bytes(const kitty_layout* layout /*host*/);
  * GPU's compute-unit count; otherwise n_splits_req ranges are used.  On return *n_splits is the
  * number of page ranges per (sequence, kv-head) and *min_pages the fewest pages a range covers:
  * a sequence with np pages uses min(n_splits, max(1, np / min_pages)) ranges of near-equal
- * length, and its last range also takes the bf16 window.  Host pointers. */
+ * length, each of which also takes an equal share of the rows held in full precision (Sink, window).
+ * Host pointers. */
 int kitty_decode_plan(const kitty_layout* layout, int32_t batch, int32_t max_pages,
                       int32_t n_splits_req, int32_t* n_splits, int32_t* min_pages);
 

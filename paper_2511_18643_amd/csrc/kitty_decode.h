@@ -892,7 +892,7 @@ __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void
       }
   }
 
-  // ================= merge the eight partials (4 wavefronts x {pages, window}), write the result ===========
+  // ================= merge the 2*NW partials (wavefronts x {pages, full-precision rows}), write the result ====
   float lsum[HPL], zsum[HPL], lwsum[HPL];
 #pragma unroll
   for (int e = 0; e < HPL; ++e) { lsum[e] = row_sum(pw.l_run[e]); zsum[e] = row_sum(pw.z_run[e]); lwsum[e] = row_sum(lw[e]); }
