@@ -504,14 +504,23 @@ def main():
         torch.cuda.synchronize()
     clocks = gpu_clocks(busy)
 
-    # ---- page quantizer on its own (prefill rate), for the record ---------------------------------
-    ev0.record()
-    kitty.kitty_quantize_pages(layout, kt, vt, 128 * 128, L * 128, 128, ids, B * n_pages0, caches[0].pool,
-                               caches[0].n_pool_pages, src_page_offsets=offs)
-    ev1.record()
-    torch.cuda.synchronize()
-    quant_ms = ev0.elapsed_time(ev1)
+    # ---- page quantizer on its own (prefill rate), for the record: every sequence reads its own copy of the
+    # source tokens, so that the input comes from HBM and not from the last-level cache ---------------
+    reps_src = (B + nsrc - 1) // nsrc
+    kt_all, vt_all = kt.repeat(reps_src, 1, 1, 1)[:B].contiguous(), vt.repeat(reps_src, 1, 1, 1)[:B].contiguous()
+    offs_all = torch.tensor([b * hkv * L * 128 + i * 128 * 128 for b in range(B) for i in range(n_pages0)],
+                            dtype=torch.int64, device=dev)
+    quant_ms = []
+    for _ in range(3):
+        ev0.record()
+        kitty.kitty_quantize_pages(layout, kt_all, vt_all, 128 * 128, L * 128, 128, ids, B * n_pages0, caches[0].pool,
+                                   caches[0].n_pool_pages, src_page_offsets=offs_all)
+        ev1.record()
+        torch.cuda.synchronize()
+        quant_ms.append(ev0.elapsed_time(ev1))
+    quant_ms = min(quant_ms)
     quant_pages = B * n_pages0 * hkv
+    del kt_all, vt_all
     # restore: the records just rewritten are identical (same inputs), nothing else to do
 
     if args.calib_copy_mib:
@@ -617,7 +626,9 @@ def main():
         "cpu_baseline": cpu,
         "max_abs_err_vs_oracle_sample": max_err,
         "quantize_pages": {"pages": quant_pages, "ms": round(quant_ms, 4),
-                           "input_gbps": round(quant_pages * 65536 / (quant_ms * 1e-3) / 1e9, 1)},
+                           "input_gbps": round(quant_pages * 65536 / (quant_ms * 1e-3) / 1e9, 1),
+                           "traffic_gbps": round(quant_pages * (65536 + rec_bytes) / (quant_ms * 1e-3) / 1e9, 1),
+                           "frac_of_hbm_peak": round(quant_pages * (65536 + rec_bytes) / (quant_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)},
         "clocks_under_load": clocks,
         "setup_s": {"generate": round(gen_s, 1), "prefill_quantize_all_copies": round(quant_s, 2)},
     }

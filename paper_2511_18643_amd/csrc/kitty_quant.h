@@ -55,21 +55,31 @@ struct Pack16 {
 };
 __device__ __forceinline__ float inv_scale(float s) { return s > 0.0f ? __fdiv_rn(1.0f, s) : 0.0f; }
 
-// src: bf16 rows of 128 channels, row t at src + t*token_stride (elements), 16-byte aligned.
-__device__ __forceinline__ void load_tile(QuantSmem& s, const uint16_t* __restrict__ src, int64_t token_stride, int tid) {
+// src: bf16 rows of 128 channels, row t at src + t*token_stride (elements), 16-byte aligned.  A thread
+// fetches eight 16-byte pieces (fetch_tile) and puts them into the padded LDS tile (store_tile); the two
+// halves are separate so that the Value tile can be on its way while the Key tile is being worked on.
+struct TileRegs { uint4 v[8]; };
+__device__ __forceinline__ void fetch_tile(TileRegs& r, const uint16_t* __restrict__ src, int64_t token_stride, int tid) {
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    int chunk = tid + 256 * i;
-    int t = chunk >> 4, part = chunk & 15;
-    uint4 v = *reinterpret_cast<const uint4*>(src + (int64_t)t * token_stride + part * 8);
+    const int chunk = tid + 256 * i;
+    const int t = chunk >> 4, part = chunk & 15;
+    r.v[i] = *reinterpret_cast<const uint4*>(src + (int64_t)t * token_stride + part * 8);
+  }
+}
+__device__ __forceinline__ void store_tile(QuantSmem& s, const TileRegs& r, int tid) {
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int chunk = tid + 256 * i;
+    const int t = chunk >> 4, part = chunk & 15;
     uint32_t* d = &s.tile[t * 65 + part * 4];
-    d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
+    d[0] = r.v[i].x; d[1] = r.v[i].y; d[2] = r.v[i].z; d[3] = r.v[i].w;
   }
 }
 
 // One block of at least 256 threads; threads 0..255 do the work, every thread takes part in the barriers.
 template <int NB16>
-__device__ void quantize_page(QuantSmem& s, const uint16_t* __restrict__ ksrc, const uint16_t* __restrict__ vsrc,
+__device__ __forceinline__ void quantize_page(QuantSmem& s, const uint16_t* __restrict__ ksrc, const uint16_t* __restrict__ vsrc,
                               int64_t token_stride, uint8_t* __restrict__ rec, int rank_metric) {
   using R = Rec<NB16>;
   const int tid = threadIdx.x;
@@ -77,7 +87,12 @@ __device__ void quantize_page(QuantSmem& s, const uint16_t* __restrict__ ksrc, c
   const int c = tid & 127, half = (tid >> 7) & 1;
 
   // ---------------- Key page ----------------
-  if (act) load_tile(s, ksrc, token_stride, tid);
+  TileRegs tr;
+  if (act) {
+    fetch_tile(tr, ksrc, token_stride, tid);
+    store_tile(s, tr, tid);
+    fetch_tile(tr, vsrc, token_stride, tid);   // used after the Key page is done
+  }
   __syncthreads();
   if (act) {  // per-channel min, max, sum |x| over half of the tokens
     float mn = INFINITY, mx = -INFINITY;
@@ -176,7 +191,7 @@ __device__ void quantize_page(QuantSmem& s, const uint16_t* __restrict__ ksrc, c
   __syncthreads();
 
   // ---------------- Value page ----------------
-  if (act) load_tile(s, vsrc, token_stride, tid);
+  if (act) store_tile(s, tr, tid);
   __syncthreads();
   if (act) {  // per-token min, max over half of the channels
     const int t = c;
@@ -247,7 +262,7 @@ struct QuantPagesParams {
 };
 
 template <int NB16>
-__global__ __launch_bounds__(256) void quantize_pages_kernel(QuantPagesParams p) {
+__global__ __launch_bounds__(256, 4) void quantize_pages_kernel(QuantPagesParams p) {
   __shared__ QuantSmem smem;
   const int i = blockIdx.x, h = blockIdx.y;
   const int32_t pid = p.dst_page_ids[i];
@@ -291,7 +306,7 @@ __device__ __forceinline__ size_t resid_v_offset(int b, int h, int n_kv_heads, i
 constexpr int TICKET_SHIFT = 8;
 
 template <int NB16>
-__global__ __launch_bounds__(256) void append_token_kernel(AppendParams p) {
+__global__ __launch_bounds__(256, 4) void append_token_kernel(AppendParams p) {
   __shared__ QuantSmem smem;
   const int h = blockIdx.x, b = blockIdx.y;
   const int nr = p.n_resid[b] & ((1 << TICKET_SHIFT) - 1);
