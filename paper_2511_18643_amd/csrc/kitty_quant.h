@@ -6,22 +6,38 @@
 
 namespace kitty {
 
+// Work split of the 256 threads: thread (wave, g, part) = (tid >> 6, (tid >> 4) & 3, tid & 15) holds, for both
+// the Key and the Value page, the eight channels 8*part..8*part+7 of the eight tokens 4*wave + g + 16*i (i < 8),
+// in registers, straight from its eight 16-byte loads.  Per-channel statistics are reduced over i in the thread
+// and over the 16 (wave, g) classes through LDS; per-token statistics over the 16 lanes of a row with DPP.  The
+// tokens of a thread are the positions 8*(4*wave + g) + i of the Value plane, i.e. half a packed word per
+// channel, and its channels are half a packed word of the dense Key plane per token: the other half sits in a
+// neighbouring lane (lane ^ 16, lane ^ 1).  Packed words are staged in LDS and stored as one 16-byte piece per
+// thread, which is exactly what a decode lane reads back.
 struct QuantSmem {
-  uint32_t tile[G * 65];   // 128 rows of 128 bf16, row stride 65 dwords (bank-conflict-free rows and columns)
-  double sum[2][D];
+  union {
+    struct {                 // per (wave, g) partial statistics of the Key page
+      float mn[16][D];
+      float mx[16][D];
+      double sum[16][D];
+    } st;
+    struct {
+      uint8_t codes[G][D];   // 4-bit Key codes [token][channel], read back by the boost-plane pass
+      uint32_t kout[1024];   // dense Key plane as it goes to memory
+      uint32_t vout[1024];   // Value plane as it goes to memory
+    } pk;
+  };
   double score[D];
-  float mn[2][D];
-  float mx[2][D];
-  float inv[D];            // 1 / float(fp16 scale) (0 if the scale is 0), per channel (K phase) or per token (V phase)
-  float zr[D];             // float(fp16 zero-point)
-  float qm[D];             // 15 or 3
-  unsigned long long ballot0;
+  float keyf[D];             // score rounded to fp32
+  int32_t rk[2][D];          // partial rank counts
+  float inv[D];              // per channel: 1 / float(fp16 scale) (0 if the scale is 0)
+  float zr[D];               // float(fp16 zero-point)
+  float qm[D];               // 15 or 3
+  float vinv[G];             // per token, index 8*(4*wave + g) + i
+  float vzr[G];
+  unsigned long long ballot0, ballot1;
   uint8_t chl[D];
 };
-
-__device__ __forceinline__ float tile_elem(const QuantSmem& s, int t, int c) {
-  return bf16_to_f32(reinterpret_cast<const uint16_t*>(s.tile)[t * 130 + c]);
-}
 
 // code = clamp(rint((x - zero) * inv), 0, qmax), inv = 1/scale rounded once (IEEE), 0 for a zero scale.
 // fp32 subtract and multiply, ties to even; with inv == 0 every code is 0.
@@ -32,100 +48,134 @@ __device__ __forceinline__ uint32_t qcode_bits(float x, float inv, float z, floa
   const float f = __builtin_amdgcn_fmed3f(__fmul_rn(__fsub_rn(x, z), inv), 0.0f, qmax);
   return __float_as_uint(__fadd_rn(f, 12582912.0f));
 }
-
-// Sixteen codes on their way into one packed word.  Register v collects the low bytes of elements 4v..4v+3
-// (three byte permutes per four codes); the word takes the low two bits of every byte of register v at bit
-// offset 2v (low plane), or bits 2..3 (high plane of 4-bit codes).
-struct Pack16 {
-  uint32_t u[16];
-  __device__ __forceinline__ void put(int a, uint32_t bits) { u[a] = bits; }
-  __device__ __forceinline__ uint32_t bytes(int v) const {
-    const uint32_t lo = __builtin_amdgcn_perm(u[4 * v + 1], u[4 * v], 0x0c0c0400u);
-    const uint32_t hi = __builtin_amdgcn_perm(u[4 * v + 3], u[4 * v + 2], 0x0c0c0400u);
-    return __builtin_amdgcn_perm(hi, lo, 0x05040100u);
-  }
-  __device__ __forceinline__ uint32_t low() const {
-    constexpr uint32_t m = 0x03030303u;
-    return (bytes(0) & m) | ((bytes(1) & m) << 2) | ((bytes(2) & m) << 4) | ((bytes(3) & m) << 6);
-  }
-  __device__ __forceinline__ uint32_t high() const {
-    constexpr uint32_t m = 0x0c0c0c0cu;
-    return ((bytes(0) & m) >> 2) | (bytes(1) & m) | ((bytes(2) & m) << 2) | ((bytes(3) & m) << 4);
-  }
-};
 __device__ __forceinline__ float inv_scale(float s) { return s > 0.0f ? __fdiv_rn(1.0f, s) : 0.0f; }
 
-// src: bf16 rows of 128 channels, row t at src + t*token_stride (elements), 16-byte aligned.  A thread
-// fetches eight 16-byte pieces (fetch_tile) and puts them into the padded LDS tile (store_tile); the two
-// halves are separate so that the Value tile can be on its way while the Key tile is being worked on.
+// low bytes of a, b, c, d -> one word (a in byte 0)
+__device__ __forceinline__ uint32_t low_bytes(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
+  const uint32_t lo = __builtin_amdgcn_perm(b, a, 0x0c0c0400u);
+  const uint32_t hi = __builtin_amdgcn_perm(d, c, 0x0c0c0400u);
+  return __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+}
+
+// Eight bf16 values of a 16-byte piece, widened.
+__device__ __forceinline__ void widen8(const uint4& v, float (&x)[8]) {
+  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    x[2 * k] = __uint_as_float(w[k] << 16);
+    x[2 * k + 1] = __uint_as_float(w[k] & 0xffff0000u);
+  }
+}
+
+// Dword index inside a 4 KB packed plane of the word with row index r (token for Keys, channel for Values) and
+// word index cw (channel block for Keys, position block for Values): byte 1024*(r/32) + 16*((r%16) + 16*(cw%4))
+// + 4*(2*((r/16)%2) + cw/4), divided by four.
+__device__ __forceinline__ int plane_word(int r, int cw) {
+  return 4 * (64 * (r >> 5) + 16 * (cw & 3) + (r & 15)) + 2 * ((r >> 4) & 1) + (cw >> 2);
+}
+
+// src: bf16 rows of 128 channels, row t at src + t*token_stride (elements), 16-byte aligned.
 struct TileRegs { uint4 v[8]; };
 __device__ __forceinline__ void fetch_tile(TileRegs& r, const uint16_t* __restrict__ src, int64_t token_stride, int tid) {
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    const int chunk = tid + 256 * i;
-    const int t = chunk >> 4, part = chunk & 15;
+    const int t = (tid >> 4) + 16 * i, part = tid & 15;
     r.v[i] = *reinterpret_cast<const uint4*>(src + (int64_t)t * token_stride + part * 8);
-  }
-}
-__device__ __forceinline__ void store_tile(QuantSmem& s, const TileRegs& r, int tid) {
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int chunk = tid + 256 * i;
-    const int t = chunk >> 4, part = chunk & 15;
-    uint32_t* d = &s.tile[t * 65 + part * 4];
-    d[0] = r.v[i].x; d[1] = r.v[i].y; d[2] = r.v[i].z; d[3] = r.v[i].w;
   }
 }
 
 // One block of at least 256 threads; threads 0..255 do the work, every thread takes part in the barriers.
+// Both source pages are read into registers before the first barrier and never touched again.
 template <int NB16>
 __device__ __forceinline__ void quantize_page(QuantSmem& s, const uint16_t* __restrict__ ksrc, const uint16_t* __restrict__ vsrc,
-                              int64_t token_stride, uint8_t* __restrict__ rec, int rank_metric) {
+                                              int64_t token_stride, uint8_t* __restrict__ rec, int rank_metric) {
   using R = Rec<NB16>;
   const int tid = threadIdx.x;
   const bool act = tid < 256;
-  const int c = tid & 127, half = (tid >> 7) & 1;
-
-  // ---------------- Key page ----------------
-  TileRegs tr;
+  const int c = tid & 127;
+  const int part = tid & 15, cls = (tid >> 4) & 15;   // cls = 4*wave + g: tokens cls + 16*i, positions 8*cls + i
+  TileRegs kq, vq;
   if (act) {
-    fetch_tile(tr, ksrc, token_stride, tid);
-    store_tile(s, tr, tid);
-    fetch_tile(tr, vsrc, token_stride, tid);   // used after the Key page is done
+    fetch_tile(kq, ksrc, token_stride, tid);
+    fetch_tile(vq, vsrc, token_stride, tid);
   }
-  __syncthreads();
-  if (act) {  // per-channel min, max, sum |x| over half of the tokens
-    float mn = INFINITY, mx = -INFINITY;
-    double sum = 0.0;
-    for (int t = half * 64; t < half * 64 + 64; ++t) {
-      float x = tile_elem(s, t, c);
-      mn = fminf(mn, x);
-      mx = fmaxf(mx, x);
-      sum += (double)fabsf(x);   // exact for bf16 inputs: the order of the additions does not matter
+
+  // ---------------- Key page: per-channel min, max, sum |x| ----------------
+  if (act) {
+    float mn[8], mx[8];
+    double sum[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) { mn[k] = INFINITY; mx[k] = -INFINITY; sum[k] = 0.0; }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      float x[8];
+      widen8(kq.v[i], x);
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        mn[k] = fminf(mn[k], x[k]);
+        mx[k] = fmaxf(mx[k], x[k]);
+        sum[k] += (double)fabsf(x[k]);   // exact for bf16 inputs: the order of the additions does not matter
+      }
     }
-    s.mn[half][c] = mn; s.mx[half][c] = mx; s.sum[half][c] = sum;
+    *reinterpret_cast<float4*>(&s.st.mn[cls][8 * part]) = make_float4(mn[0], mn[1], mn[2], mn[3]);
+    *reinterpret_cast<float4*>(&s.st.mn[cls][8 * part + 4]) = make_float4(mn[4], mn[5], mn[6], mn[7]);
+    *reinterpret_cast<float4*>(&s.st.mx[cls][8 * part]) = make_float4(mx[0], mx[1], mx[2], mx[3]);
+    *reinterpret_cast<float4*>(&s.st.mx[cls][8 * part + 4]) = make_float4(mx[4], mx[5], mx[6], mx[7]);
+#pragma unroll
+    for (int k = 0; k < 8; k += 2) *reinterpret_cast<double2*>(&s.st.sum[cls][8 * part + k]) = make_double2(sum[k], sum[k + 1]);
   }
   __syncthreads();
   float mn = 0.f, mx = 0.f;
   if (tid < 128) {
-    mn = fminf(s.mn[0][c], s.mn[1][c]);
-    mx = fmaxf(s.mx[0][c], s.mx[1][c]);
-    s.score[c] = rank_metric == 0 ? s.sum[0][c] + s.sum[1][c] : (double)__fsub_rn(mx, mn);
+    mn = INFINITY; mx = -INFINITY;
+    double sum = 0.0;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      mn = fminf(mn, s.st.mn[r][c]);
+      mx = fmaxf(mx, s.st.mx[r][c]);
+      sum += s.st.sum[r][c];
+    }
+    const double sc = rank_metric == 0 ? sum : (double)__fsub_rn(mx, mn);
+    s.score[c] = sc;
+    s.keyf[c] = (float)sc;     // round to nearest: monotone
+  }
+  __syncthreads();
+  // Boosted set = the 16*NB16 channels that come first under (score descending, channel ascending).  Fast
+  // path: count, per channel, the channels whose score rounded to fp32 is strictly larger (rounding is
+  // monotone, so a strictly larger fp32 key means a strictly larger score; both halves of the block take 64
+  // candidates each).  Channels with equal fp32 keys get equal counts; membership in the set is still decided
+  // correctly unless such a group straddles the boundary, and then more than 16*NB16 channels pass the test:
+  // in that case only, the exact comparison on the fp64 scores is run.
+  constexpr int KB = 16 * NB16;
+  if (act) {
+    const float my = s.keyf[c];
+    const int o0 = (tid >> 7) * 64;
+    int cnt = 0;
+    for (int o = o0; o < o0 + 64; ++o) cnt += s.keyf[o] > my;
+    s.rk[tid >> 7][c] = cnt;
   }
   __syncthreads();
   bool boosted = false;
-  if (tid < 128) {  // rank under (score descending, channel ascending)
-    const double my = s.score[c];
-    int rank = 0;
-    for (int o = 0; o < 128; ++o) {
-      double so = s.score[o];
-      rank += (so > my) || (so == my && o < c);
-    }
-    boosted = rank < 16 * NB16;
-  }
+  if (tid < 128) boosted = s.rk[0][c] + s.rk[1][c] < KB;
   unsigned long long bal = __ballot(boosted);
   if (tid == 0) s.ballot0 = bal;
+  if (tid == 64) s.ballot1 = bal;
   __syncthreads();
+  if (__popcll(s.ballot0) + __popcll(s.ballot1) != KB) {   // same for every thread of the block
+    __syncthreads();                                       // everybody has read the ballots
+    if (tid < 128) {
+      const double my = s.score[c];
+      int rank = 0;
+      for (int o = 0; o < 128; ++o) {
+        double so = s.score[o];
+        rank += (so > my) || (so == my && o < c);
+      }
+      boosted = rank < KB;
+    }
+    bal = __ballot(boosted);
+    if (tid == 0) s.ballot0 = bal;
+    __syncthreads();
+  }
   if (tid < 128) {
     const int lane = tid & 63;
     int slot = __popcll(bal & ((1ull << lane) - 1ull)) + (tid >= 64 ? __popcll(s.ballot0) : 0);
@@ -140,115 +190,122 @@ __device__ __forceinline__ void quantize_page(QuantSmem& s, const uint16_t* __re
     if (boosted) { s.chl[slot] = (uint8_t)c; rec[R::ch + slot] = (uint8_t)c; }
     if (c >= 16 * NB16) rec[R::ch + c] = 0;   // pad bytes of the channel list
   }
-  __syncthreads();
-  if (act) {  // dense plane: thread (q, lane) builds the 16 bytes that lane reads back in the decode kernel
-    const int q = tid >> 6, lane = tid & 63;
-    uint32_t w[4];
-#pragma unroll
-    for (int csel = 0; csel < 2; ++csel) {
-      const int cb = 4 * csel + (lane >> 4);
-      float inv[16], zr[16], qm[16];
-#pragma unroll
-      for (int a4 = 0; a4 < 4; ++a4) {
-        const float4 i4 = *reinterpret_cast<const float4*>(&s.inv[16 * cb + 4 * a4]);
-        const float4 z4 = *reinterpret_cast<const float4*>(&s.zr[16 * cb + 4 * a4]);
-        const float4 q4 = *reinterpret_cast<const float4*>(&s.qm[16 * cb + 4 * a4]);
-        inv[4 * a4] = i4.x; inv[4 * a4 + 1] = i4.y; inv[4 * a4 + 2] = i4.z; inv[4 * a4 + 3] = i4.w;
-        zr[4 * a4] = z4.x; zr[4 * a4 + 1] = z4.y; zr[4 * a4 + 2] = z4.z; zr[4 * a4 + 3] = z4.w;
-        qm[4 * a4] = q4.x; qm[4 * a4 + 1] = q4.y; qm[4 * a4 + 2] = q4.z; qm[4 * a4 + 3] = q4.w;
-      }
-#pragma unroll
-      for (int tsel = 0; tsel < 2; ++tsel) {
-        const int t = 32 * q + 16 * tsel + (lane & 15);
-        Pack16 pk;
-#pragma unroll
-        for (int a2 = 0; a2 < 8; ++a2) {
-          const uint32_t two = s.tile[t * 65 + 8 * cb + a2];
-          const float x0 = __uint_as_float(two << 16), x1 = __uint_as_float(two & 0xffff0000u);
-          pk.put(2 * a2, qcode_bits(x0, inv[2 * a2], zr[2 * a2], qm[2 * a2]));
-          pk.put(2 * a2 + 1, qcode_bits(x1, inv[2 * a2 + 1], zr[2 * a2 + 1], qm[2 * a2 + 1]));
-        }
-        w[2 * tsel + csel] = pk.low();
-      }
+  __syncthreads();   // (also: everybody is done with the partial statistics, whose memory the codes reuse)
+
+  // ---------------- Key codes: half a dense word per token and thread ----------------
+  if (act) {
+    float inv[8], zr[8], qm[8];
+    {
+      const float4 i0 = *reinterpret_cast<const float4*>(&s.inv[8 * part]), i1 = *reinterpret_cast<const float4*>(&s.inv[8 * part + 4]);
+      const float4 z0 = *reinterpret_cast<const float4*>(&s.zr[8 * part]), z1 = *reinterpret_cast<const float4*>(&s.zr[8 * part + 4]);
+      const float4 q0 = *reinterpret_cast<const float4*>(&s.qm[8 * part]), q1 = *reinterpret_cast<const float4*>(&s.qm[8 * part + 4]);
+      inv[0] = i0.x; inv[1] = i0.y; inv[2] = i0.z; inv[3] = i0.w; inv[4] = i1.x; inv[5] = i1.y; inv[6] = i1.z; inv[7] = i1.w;
+      zr[0] = z0.x; zr[1] = z0.y; zr[2] = z0.z; zr[3] = z0.w; zr[4] = z1.x; zr[5] = z1.y; zr[6] = z1.z; zr[7] = z1.w;
+      qm[0] = q0.x; qm[1] = q0.y; qm[2] = q0.z; qm[3] = q0.w; qm[4] = q1.x; qm[5] = q1.y; qm[6] = q1.z; qm[7] = q1.w;
     }
-    reinterpret_cast<uint4*>(rec + R::kd)[64 * q + lane] = make_uint4(w[0], w[1], w[2], w[3]);
+    const uint32_t sh0 = 4u * (uint32_t)(part & 1);   // elements 8*(part&1)..+7 of the word: bit offsets 2*(a/4)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int t = cls + 16 * i;
+      float x[8];
+      widen8(kq.v[i], x);
+      uint32_t u[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) u[k] = qcode_bits(x[k], inv[k], zr[k], qm[k]);
+      const uint32_t r0 = low_bytes(u[0], u[1], u[2], u[3]), r1 = low_bytes(u[4], u[5], u[6], u[7]);
+      if constexpr (NB16 > 0) *reinterpret_cast<uint2*>(&s.pk.codes[t][8 * part]) = make_uint2(r0, r1);
+      const uint32_t half = ((r0 & 0x03030303u) | ((r1 & 0x03030303u) << 2)) << sh0;
+      const uint32_t other = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)half, 0xB1, 0xf, 0xf, true);   // lane ^ 1
+      if ((part & 1) == 0) s.pk.kout[plane_word(t, part >> 1)] = half | other;
+    }
   }
-  if constexpr (NB16 > 0) {  // boost plane: high two bits of the boosted channels, slot order
-    if (act) {
+
+  // ---------------- Value page: per-token min, max over the 16 lanes of a row ----------------
+  if (act) {
+    float tmn[8], tmx[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      float x[8];
+      widen8(vq.v[i], x);
+      float a = fminf(fminf(fminf(x[0], x[1]), fminf(x[2], x[3])), fminf(fminf(x[4], x[5]), fminf(x[6], x[7])));
+      float b = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+      a = fminf(a, row_ror<8>(a)); a = fminf(a, row_ror<4>(a)); a = fminf(a, row_ror<2>(a)); a = fminf(a, row_ror<1>(a));
+      b = fmaxf(b, row_ror<8>(b)); b = fmaxf(b, row_ror<4>(b)); b = fmaxf(b, row_ror<2>(b)); b = fmaxf(b, row_ror<1>(b));
+      tmn[i] = a; tmx[i] = b;
+    }
+    // lane `part` < 8 of a row finishes token i = part: fp16 scale and zero-point, reciprocal
+    float mnv = tmn[0], mxv = tmx[0];
+#pragma unroll
+    for (int i = 1; i < 8; ++i) { mnv = part == i ? tmn[i] : mnv; mxv = part == i ? tmx[i] : mxv; }
+    if (part < 8) {
+      const uint16_t sh = f32_to_f16_bits(__fdiv_rn(__fsub_rn(mxv, mnv), 3.0f));
+      const uint16_t zh = f32_to_f16_bits(mnv);
+      const int p = 8 * cls + part;        // position of token cls + 16*part
+      s.vinv[p] = inv_scale(f16_bits_to_f32(sh));
+      s.vzr[p] = f16_bits_to_f32(zh);
+      reinterpret_cast<uint16_t*>(rec + R::vs)[p] = sh;
+      reinterpret_cast<uint16_t*>(rec + R::vz)[p] = zh;
+    }
+  }
+  __syncthreads();   // Key words and codes staged, per-token metadata in place
+  if (act) {
+    *reinterpret_cast<uint4*>(rec + R::kd + 16 * tid) = *reinterpret_cast<const uint4*>(&s.pk.kout[4 * tid]);
+    if constexpr (NB16 > 0) {   // boost plane: high two bits of the boosted channels, slot order
       for (int idx = tid; idx < 128 * NB16; idx += 256) {
         const int sblk = idx >> 7, u = (idx >> 6) & 1, lane = idx & 63;
         const int t = 16 * (4 * u + (lane >> 4)) + (lane & 15);
-        Pack16 pk;
+        uint32_t word = 0;
 #pragma unroll
         for (int a = 0; a < 16; ++a) {
-          const int ch = s.chl[16 * sblk + a];
-          pk.put(a, qcode_bits(tile_elem(s, t, ch), s.inv[ch], s.zr[ch], 15.0f));
+          const uint32_t code = s.pk.codes[t][s.chl[16 * sblk + a]];
+          word |= (code >> 2) << (8 * (a & 3) + 2 * (a >> 2));
         }
-        *reinterpret_cast<uint32_t*>(rec + R::kb + 512 * sblk + 8 * lane + 4 * u) = pk.high();
+        *reinterpret_cast<uint32_t*>(rec + R::kb + 512 * sblk + 8 * lane + 4 * u) = word;
       }
+    }
+    // ---------------- Value codes: half a word per channel and thread ----------------
+    float inv[8], zr[8];
+    {
+      const float4 i0 = *reinterpret_cast<const float4*>(&s.vinv[8 * cls]), i1 = *reinterpret_cast<const float4*>(&s.vinv[8 * cls + 4]);
+      const float4 z0 = *reinterpret_cast<const float4*>(&s.vzr[8 * cls]), z1 = *reinterpret_cast<const float4*>(&s.vzr[8 * cls + 4]);
+      inv[0] = i0.x; inv[1] = i0.y; inv[2] = i0.z; inv[3] = i0.w; inv[4] = i1.x; inv[5] = i1.y; inv[6] = i1.z; inv[7] = i1.w;
+      zr[0] = z0.x; zr[1] = z0.y; zr[2] = z0.z; zr[3] = z0.w; zr[4] = z1.x; zr[5] = z1.y; zr[6] = z1.z; zr[7] = z1.w;
+    }
+    uint32_t r0[8], r1[8];   // per channel k: code bytes of tokens i = 0..3 and 4..7
+    {
+      uint32_t u[4][8];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        float x[8];
+        widen8(vq.v[i], x);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) u[i][k] = qcode_bits(x[k], inv[i], zr[i], 3.0f);
+      }
+#pragma unroll
+      for (int k = 0; k < 8; ++k) r0[k] = low_bytes(u[0][k], u[1][k], u[2][k], u[3][k]);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        float x[8];
+        widen8(vq.v[4 + i], x);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) u[i][k] = qcode_bits(x[k], inv[4 + i], zr[4 + i], 3.0f);
+      }
+#pragma unroll
+      for (int k = 0; k < 8; ++k) r1[k] = low_bytes(u[0][k], u[1][k], u[2][k], u[3][k]);
+    }
+    // positions 8*cls + i are elements 8*(cls&1) + i of word cls/2 of the channel; the other half is in lane ^ 16
+    const uint32_t sh0 = 4u * (uint32_t)(cls & 1);
+    const int wv = cls >> 1;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const uint32_t half = ((r0[k] & 0x03030303u) | ((r1[k] & 0x03030303u) << 2)) << sh0;
+      const uint32_t other = (uint32_t)__shfl_xor((int)half, 16);
+      if (((cls & 1) == 0) == (k < 4)) s.pk.vout[plane_word(8 * part + k, wv)] = half | other;   // each lane of the pair stores four
     }
   }
   __syncthreads();
-
-  // ---------------- Value page ----------------
-  if (act) store_tile(s, tr, tid);
-  __syncthreads();
-  if (act) {  // per-token min, max over half of the channels
-    const int t = c;
-    float mn2 = INFINITY, mx2 = -INFINITY;
-    for (int k = 0; k < 32; ++k) {
-      uint32_t two = s.tile[t * 65 + half * 32 + k];
-      float a = __uint_as_float(two << 16), b = __uint_as_float(two & 0xffff0000u);
-      mn2 = fminf(mn2, fminf(a, b));
-      mx2 = fmaxf(mx2, fmaxf(a, b));
-    }
-    s.mn[half][t] = mn2; s.mx[half][t] = mx2;
-  }
-  __syncthreads();
-  if (tid < 128) {
-    const int t = c;
-    const float mnv = fminf(s.mn[0][t], s.mn[1][t]);
-    const float mxv = fmaxf(s.mx[0][t], s.mx[1][t]);
-    const uint16_t sh = f32_to_f16_bits(__fdiv_rn(__fsub_rn(mxv, mnv), 3.0f));
-    const uint16_t zh = f32_to_f16_bits(mnv);
-    // kept in position order: position p holds token 16*(p%8) + p/8
-    const int p = 8 * (t & 15) + (t >> 4);
-    s.inv[p] = inv_scale(f16_bits_to_f32(sh));
-    s.zr[p] = f16_bits_to_f32(zh);
-    reinterpret_cast<uint16_t*>(rec + R::vs)[p] = sh;
-    reinterpret_cast<uint16_t*>(rec + R::vz)[p] = zh;
-  }
-  __syncthreads();
-  if (act) {
-    const int q = tid >> 6, lane = tid & 63;
-    uint32_t w[4];
-#pragma unroll
-    for (int vsel = 0; vsel < 2; ++vsel) {
-      const int wv = 4 * vsel + (lane >> 4);
-      float inv[16], zr[16];
-#pragma unroll
-      for (int a4 = 0; a4 < 4; ++a4) {
-        const float4 i4 = *reinterpret_cast<const float4*>(&s.inv[16 * wv + 4 * a4]);
-        const float4 z4 = *reinterpret_cast<const float4*>(&s.zr[16 * wv + 4 * a4]);
-        inv[4 * a4] = i4.x; inv[4 * a4 + 1] = i4.y; inv[4 * a4 + 2] = i4.z; inv[4 * a4 + 3] = i4.w;
-        zr[4 * a4] = z4.x; zr[4 * a4 + 1] = z4.y; zr[4 * a4 + 2] = z4.z; zr[4 * a4 + 3] = z4.w;
-      }
-#pragma unroll
-      for (int dsel = 0; dsel < 2; ++dsel) {
-        const int d = 32 * q + 16 * dsel + (lane & 15);
-        Pack16 pk;
-#pragma unroll
-        for (int a = 0; a < 16; ++a) {
-          const int p = 16 * wv + a;
-          const int t = 16 * (p & 7) + (p >> 3);
-          pk.put(a, qcode_bits(tile_elem(s, t, d), inv[a], zr[a], 3.0f));
-        }
-        w[2 * dsel + vsel] = pk.low();
-      }
-    }
-    reinterpret_cast<uint4*>(rec + R::vd)[64 * q + lane] = make_uint4(w[0], w[1], w[2], w[3]);
-  }
-  __syncthreads();   // the tile and the window rows may be overwritten by the caller after this
+  if (act) *reinterpret_cast<uint4*>(rec + R::vd + 16 * tid) = *reinterpret_cast<const uint4*>(&s.pk.vout[4 * tid]);
+  __syncthreads();   // the shared memory may be reused by the caller after this
 }
 
 struct QuantPagesParams {

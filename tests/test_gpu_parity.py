@@ -107,6 +107,9 @@ def test_adversarial_pages_bit_exact():
     pages.append(x * 3000.0)                                            # large
     t = np.tile(np.arange(128, dtype=np.float32)[:, None], (1, 128)); pages.append(t)   # identical channels
     pages.append(np.where(r.random((128, 128)) < 0.5, -1.0, 1.0).astype(np.float32))    # two-level
+    # scores that agree when rounded to fp32 and differ in fp64: 127 + k * 2^-30 with k a permutation of 1..128
+    near = np.ones((128, 128), np.float32); near[127, :] = (r.permutation(128) + 1).astype(np.float32) * 2.0 ** -30
+    pages.append(near)
     kbits = np.stack([synth.to_bf16_bits(p) for p in pages])[:, None]   # [n][1][128][128]
     vbits = kbits[::-1].copy()
     n = len(pages)
