@@ -92,9 +92,10 @@ class KPage:
 
 @dataclass
 class VPage:
-    codes: np.ndarray      # uint8 [G][D], 0..3
+    codes: np.ndarray      # uint8 [G][D], 0..3 (0..15 for the 4-bit Value variant)
     scale: np.ndarray      # float16 [G]
     zero: np.ndarray       # float16 [G]
+    bits: int = 2          # 2 (the method) or 4 (the K2V4 point of the design-space study, Table 2)
 
 
 def _asym_quant(x: np.ndarray, mn: np.ndarray, mx: np.ndarray, qmax: np.ndarray):
@@ -154,14 +155,15 @@ def quantize_k_page(x: np.ndarray, n_boost: int, rank_metric: int = 0) -> KPage:
     return KPage(codes=codes, scale=scale_h[0], zero=zero_h[0], ch=ch, score=score)
 
 
-def quantize_v_page(x: np.ndarray) -> VPage:
-    """Quantize one Value page x[G][D]: per token, 2-bit, group = the whole head (Sec. 2.1)."""
+def quantize_v_page(x: np.ndarray, bits: int = 2) -> VPage:
+    """Quantize one Value page x[G][D]: per token, `bits`-bit, group = the whole head (Sec. 2.1)."""
+    assert bits in (2, 4)
     x = np.asarray(x, dtype=np.float32)
     mn = x.min(axis=1)
     mx = x.max(axis=1)
-    qmax = np.full((x.shape[0], 1), 3.0, dtype=np.float32)
+    qmax = np.full((x.shape[0], 1), float(2 ** bits - 1), dtype=np.float32)
     codes, scale_h, zero_h = _asym_quant(x, mn[:, None], mx[:, None], qmax)
-    return VPage(codes=codes, scale=scale_h[:, 0], zero=zero_h[:, 0])
+    return VPage(codes=codes, scale=scale_h[:, 0], zero=zero_h[:, 0], bits=bits)
 
 
 def dequant_k(kp: KPage) -> np.ndarray:
@@ -195,13 +197,17 @@ class RecordLayout:
       V codes, word (d, wv) = positions 16wv..16wv+15 of channel d, where the token at
                position p is 16*(p%8) + p//8
                at  vd_off + 1024*(d//32) + 16*((d%16) + 16*(wv%4)) + 4*(2*((d//16)%2) + wv//4)
+      V high   (4-bit Value variant only) the high 2 bits, same word placement, 4096 bytes further
       v_scale, v_zero   fp16[128], position order (entry p belongs to token 16*(p%8) + p//8)
     """
 
-    def __init__(self, n_boost: int):
+    def __init__(self, n_boost: int, v_bits: int = 2):
         if n_boost % 16 or not (0 <= n_boost <= HEAD_DIM):
             raise ValueError("n_boost must be a multiple of 16 in [0, 128]")
+        if v_bits not in (2, 4):
+            raise ValueError("v_bits must be 2 or 4")
         self.n_boost = n_boost
+        self.v_bits = v_bits
         nb16 = n_boost // 16
         self.kd_off = 0
         self.kb_off = 4096
@@ -209,7 +215,8 @@ class RecordLayout:
         self.kz_off = self.ks_off + 256
         self.ch_off = self.kz_off + 256
         self.vd_off = self.ch_off + 128
-        self.vs_off = self.vd_off + 4096
+        self.vh_off = self.vd_off + 4096                      # only present with 4-bit Values
+        self.vs_off = self.vh_off + (4096 if v_bits == 4 else 0)
         self.vz_off = self.vs_off + 256
         self.record_bytes = self.vz_off + 256
         # bytes the method has to move per page (padding of the channel list excluded)
@@ -255,7 +262,7 @@ def _get_words(buf32: np.ndarray, byte_off: np.ndarray) -> np.ndarray:
 
 def pack_record(kp: KPage, vp: VPage) -> np.ndarray:
     """Byte image (uint8[record_bytes]) of one page of one kv-head."""
-    lay = RecordLayout(len(kp.ch))
+    lay = RecordLayout(len(kp.ch), vp.bits)
     g, d = kp.codes.shape
     assert g == PAGE_SIZE and d == HEAD_DIM
     rec = np.zeros(lay.record_bytes, dtype=np.uint8)
@@ -282,15 +289,17 @@ def pack_record(kp: KPage, vp: VPage) -> np.ndarray:
     dd = np.arange(d)
     wv = np.arange(g // 16)
     off = lay.vd_word_off(dd[:, None], wv[None, :])
-    _put_words(r32, off, vt.reshape(d, g // 16, 16))
+    _put_words(r32, off, (vt & np.uint8(3)).reshape(d, g // 16, 16))
+    if vp.bits == 4:
+        _put_words(r32, off + (lay.vh_off - lay.vd_off), (vt >> np.uint8(2)).reshape(d, g // 16, 16))
     rec[lay.vs_off:lay.vs_off + 256] = vp.scale[tok_at].astype(np.float16).view(np.uint8)
     rec[lay.vz_off:lay.vz_off + 256] = vp.zero[tok_at].astype(np.float16).view(np.uint8)
     return rec
 
 
-def unpack_record(rec: np.ndarray, n_boost: int):
+def unpack_record(rec: np.ndarray, n_boost: int, v_bits: int = 2):
     """Inverse of pack_record: (KPage, VPage) with score left empty."""
-    lay = RecordLayout(n_boost)
+    lay = RecordLayout(n_boost, v_bits)
     rec = np.ascontiguousarray(np.asarray(rec, dtype=np.uint8))
     assert rec.shape[0] == lay.record_bytes
     r32 = rec.view(np.uint32)
@@ -311,11 +320,13 @@ def unpack_record(rec: np.ndarray, n_boost: int):
     dd = np.arange(d)
     wv = np.arange(g // 16)
     vt = _get_words(r32, lay.vd_word_off(dd[:, None], wv[None, :])).reshape(d, g)   # [D][position]
+    if v_bits == 4:
+        vt = vt | (_get_words(r32, lay.vd_word_off(dd[:, None], wv[None, :]) + (lay.vh_off - lay.vd_off)).reshape(d, g) << np.uint8(2))
     pos_of = lay.v_pos_of(t)
     v_codes = vt[:, pos_of].T
     vs = rec[lay.vs_off:lay.vs_off + 256].view(np.float16)[pos_of].copy()
     vz = rec[lay.vz_off:lay.vz_off + 256].view(np.float16)[pos_of].copy()
-    return kp, VPage(codes=v_codes, scale=vs, zero=vz)
+    return kp, VPage(codes=v_codes, scale=vs, zero=vz, bits=v_bits)
 
 
 def to_paper_tensors(rec: np.ndarray, n_boost: int):
@@ -380,12 +391,12 @@ class KittyCacheOracle:
     """
 
     def __init__(self, batch, n_kv_heads, n_q_heads, n_boost, residual_window, max_pages,
-                 n_pool_pages, rank_metric=0):
+                 n_pool_pages, rank_metric=0, v_bits=2):
         assert n_q_heads % n_kv_heads == 0
         assert residual_window in (0, PAGE_SIZE)
         self.b, self.hkv, self.hq = batch, n_kv_heads, n_q_heads
-        self.n_boost, self.r, self.metric = n_boost, residual_window, rank_metric
-        self.lay = RecordLayout(n_boost)
+        self.n_boost, self.r, self.metric, self.v_bits = n_boost, residual_window, rank_metric, v_bits
+        self.lay = RecordLayout(n_boost, v_bits)
         self.pool = np.zeros((n_pool_pages, n_kv_heads, self.lay.record_bytes), dtype=np.uint8)
         self.page_table = np.zeros((batch, max_pages), dtype=np.int32)
         self.n_pages = np.zeros(batch, dtype=np.int32)
@@ -399,7 +410,7 @@ class KittyCacheOracle:
         for i, pid in enumerate(page_ids):
             for h in range(self.hkv):
                 kp = quantize_k_page(bf16_bits_to_f32(k_bits[i, h]), self.n_boost, self.metric)
-                vp = quantize_v_page(bf16_bits_to_f32(v_bits[i, h]))
+                vp = quantize_v_page(bf16_bits_to_f32(v_bits[i, h]), self.v_bits)
                 self.pool[pid, h] = pack_record(kp, vp)
 
     # -- one decode-step insert (Sec. 4.3 steps 1 and 3) ------------------------------
@@ -412,7 +423,7 @@ class KittyCacheOracle:
                 pid = int(fresh_page_ids[b])
                 for h in range(self.hkv):
                     kp = quantize_k_page(bf16_bits_to_f32(self.resid_k[b, h]), self.n_boost, self.metric)
-                    vp = quantize_v_page(bf16_bits_to_f32(self.resid_v[b, h]))
+                    vp = quantize_v_page(bf16_bits_to_f32(self.resid_v[b, h]), self.v_bits)
                     self.pool[pid, h] = pack_record(kp, vp)
                 self.page_table[b, self.n_pages[b]] = pid
                 self.n_pages[b] += 1
@@ -427,7 +438,7 @@ class KittyCacheOracle:
     def dequantized(self, b, h):
         ks, vs = [], []
         for i in range(int(self.n_pages[b])):
-            kp, vp = unpack_record(self.pool[self.page_table[b, i], h], self.n_boost)
+            kp, vp = unpack_record(self.pool[self.page_table[b, i], h], self.n_boost, self.v_bits)
             ks.append(dequant_k(kp))
             vs.append(dequant_v(vp))
         r = int(self.n_resid[b])
@@ -474,8 +485,9 @@ class KittyUnitOracle:
     Pages are kept as KPage / VPage objects: nothing here depends on the byte layout of a record.
     """
 
-    def __init__(self, n_boost, sink=32, local=PAGE_SIZE, rank_metric=0, group=PAGE_SIZE):
+    def __init__(self, n_boost, sink=32, local=PAGE_SIZE, rank_metric=0, group=PAGE_SIZE, v_bits=2):
         self.n_boost, self.S, self.R, self.G, self.metric = n_boost, sink, local, group, rank_metric
+        self.v_bits = v_bits
         self.sink_k, self.sink_v = [], []          # rows of bf16 bit patterns
         self.k_pages, self.k_qbuf = [], []
         self.v_pages, self.v_qbuf, self.v_local = [], [], []
@@ -501,7 +513,7 @@ class KittyUnitOracle:
             self.k_qbuf = []
             self.k_flushes += 1
         if len(self.v_qbuf) == self.G:
-            self.v_pages.append(quantize_v_page(bf16_bits_to_f32(np.stack(self.v_qbuf))))
+            self.v_pages.append(quantize_v_page(bf16_bits_to_f32(np.stack(self.v_qbuf)), self.v_bits))
             self.v_qbuf = []
             self.v_flushes += 1
 

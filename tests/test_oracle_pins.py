@@ -558,3 +558,60 @@ def test_unit_sink_recovers_accuracy_on_sink_heavy_attention():
         u.prefill(kb, vb)
         errs[S] = np.abs(u.attention(q, 0.0884)[0] - exact).max()
     assert errs[32] < 0.5 * errs[0]
+
+
+# ------------------------------------------------------------------ 4-bit Value variant (the K2V4 point of Table 2)
+def test_v4_is_plain_4bit_per_token_and_error_bound():
+    x = page(31, outliers=(), gain=1.0)
+    vp = ko.quantize_v_page(x, 4)
+    assert vp.bits == 4 and vp.codes.max() <= 15 and vp.codes.min() == 0
+    # independent per-token 4-bit asymmetric quantizer, one token at a time
+    for t in (0, 17, 127):
+        row = x[t]
+        mn, mx = np.float32(row.min()), np.float32(row.max())
+        sh = np.float16(np.float32(mx - mn) / np.float32(15.0))
+        zh = np.float16(mn)
+        inv = np.float32(1.0) / np.float32(sh)
+        code = np.clip(np.rint((row - np.float32(zh)) * inv), 0, 15).astype(np.uint8)
+        assert np.array_equal(code, vp.codes[t]) and sh == vp.scale[t] and zh == vp.zero[t]
+    deq = ko.dequant_v(vp)
+    s = vp.scale.astype(np.float32)[:, None]
+    assert np.all(np.abs(deq - x) <= s / 2 * (1 + 2.0 ** -10) + 4e-7 * np.abs(x).max())
+    # sixteen levels are about five times finer than four
+    e2 = np.abs(ko.dequant_v(ko.quantize_v_page(x, 2)) - x).max()
+    assert np.abs(deq - x).max() < e2 / 4
+
+
+def test_v4_record_layout_and_round_trip():
+    x, y = page(32), page(33, outliers=())
+    kp = ko.quantize_k_page(x, 16, 0)
+    v4 = ko.quantize_v_page(y, 4)
+    rec = ko.pack_record(kp, v4)
+    lay4, lay2 = ko.RecordLayout(16, 4), ko.RecordLayout(16, 2)
+    assert rec.shape[0] == lay4.record_bytes == lay2.record_bytes + 4096 == 9856 + 4096
+    assert lay4.payload_bytes == lay2.payload_bytes + 4096
+    # the two Value planes are the packed low and high bits, each laid out like the 2-bit plane
+    lo = ko.pack_record(kp, ko.VPage(v4.codes & 3, v4.scale, v4.zero, 2))
+    hi = ko.pack_record(kp, ko.VPage(v4.codes >> 2, v4.scale, v4.zero, 2))
+    assert np.array_equal(rec[lay4.vd_off:lay4.vd_off + 4096], lo[lay2.vd_off:lay2.vd_off + 4096])
+    assert np.array_equal(rec[lay4.vh_off:lay4.vh_off + 4096], hi[lay2.vd_off:lay2.vd_off + 4096])
+    assert np.array_equal(rec[:lay4.vd_off], lo[:lay2.vd_off])                       # Key part untouched
+    assert np.array_equal(rec[lay4.vs_off:], lo[lay2.vs_off:])                       # per-token metadata
+    kp2, vp2 = ko.unpack_record(rec, 16, 4)
+    assert np.array_equal(vp2.codes, v4.codes) and np.array_equal(kp2.codes, kp.codes)
+    assert np.array_equal(vp2.scale, v4.scale) and np.array_equal(vp2.zero, v4.zero)
+
+
+def test_v4_attention_closer_to_exact_than_v2():
+    r = np.random.default_rng(41)
+    n = 4 * 128
+    k = ko.f32_to_bf16_bits(r.standard_normal((n, 128)).astype(np.float32))
+    v = ko.f32_to_bf16_bits(r.standard_normal((n, 128)).astype(np.float32))
+    q = ko.f32_to_bf16_bits(r.standard_normal((1, 128)).astype(np.float32))
+    exact = ko.softmax_attention(ko.bf16_bits_to_f32(q[0]), ko.bf16_bits_to_f32(k), ko.bf16_bits_to_f32(v), 0.0884)
+    err = {}
+    for bits in (2, 4):
+        u = ko.KittyUnitOracle(16, sink=0, local=0, v_bits=bits)
+        u.prefill(k, v)
+        err[bits] = np.abs(u.attention(q, 0.0884)[0] - exact).max()
+    assert err[4] < err[2]
