@@ -49,6 +49,8 @@ def parse():
                     help="step = kitty_append_token + kitty_decode_attention instead of the single kitty_decode_step call")
     ap.add_argument("--n-boost", type=int, default=-1,
                     help="override the workload's boosted-channel count (0, 16, 32, 64 or 128): the variant sweep")
+    ap.add_argument("--v-bits", type=int, default=2, choices=[2, 4],
+                    help="4: Values quantized to 4 bits (the K2V4-like variants; n_boost 0 or 16)")
     ap.add_argument("--sink-tokens", type=int, default=0,
                     help="keep this many initial tokens in full precision (the paper's Sink; parity covered by the tests, "
                          "the CPU baseline leg is skipped)")
@@ -336,7 +338,9 @@ def main():
     if full_scheme:
         args.no_cpu_baseline = True
     layout = kitty.make_layout(w.n_q_heads, w.n_kv_heads, w.n_boost, w.residual_window, w.rank_metric,
-                               sink_tokens=S, v_local=VL)
+                               sink_tokens=S, v_local=VL, v_bits=args.v_bits)
+    if args.v_bits != 2:
+        args.no_cpu_baseline = True      # the live oracle replay below is written for the default record
     payload = kitty.kitty_page_payload_bytes(layout)
     rec_bytes = kitty.kitty_page_bytes(layout)
     n_pages0, r0 = w.pages_and_resid()                      # c3: 255 pages + 128 window rows
@@ -611,6 +615,7 @@ def main():
             "workload": f"{w.name}: batch {B}, {w.n_q_heads}q/{hkv}kv heads, head_dim 128, context {w.context} "
                         f"({n_pages0} pages + 128-token bf16 window at the first timed step"
                         f"{f' + {S}-token Sink' if S else ''}{', Values of the newest page in the bf16 Local window' if VL else ''}), n_boost {w.n_boost}, "
+                        f"{args.v_bits}-bit Values, "
                         f"step = append_token + decode_attention ({'two calls' if args.two_calls else 'kitty_decode_step'}, {args.launch} launch)",
             "n_splits": ns, "min_pages_per_split": pps, "cache_copies": n_copies, "record_bytes": rec_bytes,
             "payload_bytes_per_page": payload, "distinct_source_sequences": nsrc,
@@ -619,7 +624,7 @@ def main():
         "decode_tokens_per_s": round(tokens_per_s, 1),
         "roofline": {
             "bound": "hbm", "kernel": "decode_split_kernel", "achieved": round(kern_gbps, 1), "peak": HBM_PEAK_GBPS,
-            "unit": "GB/s", "frac": round(kern_gbps / HBM_PEAK_GBPS, 4), "traffic": recorded_traffic(w.name) if args.n_boost < 0 and not full_scheme else None,
+            "unit": "GB/s", "frac": round(kern_gbps / HBM_PEAK_GBPS, 4), "traffic": recorded_traffic(w.name) if args.n_boost < 0 and not full_scheme and args.v_bits == 2 else None,
             "avg_launch_ms": round(kern_ms, 5), "algorithmic_bytes_per_launch": int(kbytes / n_kern),
             "single_launch": spread,
         },

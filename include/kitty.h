@@ -44,6 +44,9 @@ typedef struct kitty_layout {
   int32_t sink_tokens;     /* S: initial tokens kept in full precision for K and V (Fig. 1, Sec. 3.1): 0..128 */
   int32_t v_local;         /* Value Local window (Fig. 1, Sec. 4.3 step 1): 0 = off, 128 = the Values of the newest
                               page are read in full precision until the next page forms; needs R = 128       */
+  int32_t v_bits;          /* bits per Value code: 2 (the method; 0 means 2) or 4 (the K2V4 / K4V4-like points of the
+                              design-space study, Table 2: a second Value plane holds the high bits); 4 needs
+                              n_boost 0 or 16                                                                  */
 } kitty_layout;
 
 /* One batch's cache.  All pointers are device pointers.
@@ -71,7 +74,8 @@ typedef struct kitty_cache {
 /* Size in bytes of one (page, kv-head) record: a multiple of 128.  0 if the layout is unsupported.
  * Record contents (Sec. 4.1): dense 2-bit plane with the low bits of every Key channel, compact
  * 2-bit plane with the high bits of the boosted channels, fp16 scale and zero-point per channel,
- * ascending list of boosted channels, 2-bit Value plane, fp16 scale and zero-point per token. */
+ * ascending list of boosted channels, 2-bit Value plane (and the plane of the high bits with 4-bit Values),
+ * fp16 scale and zero-point per token. */
 size_t kitty_page_bytes(const kitty_layout* layout /*host*/);
 
 /* Bytes of a record the method has to move (record minus alignment padding).  0 if unsupported. */

@@ -23,6 +23,8 @@ int check_layout(const kitty_layout* L) {
   if (L->sink_tokens < 0 || L->v_local < 0) return KITTY_ERR_INVALID_ARG;
   if (L->sink_tokens > G) return KITTY_ERR_UNSUPPORTED;
   if (L->v_local != 0 && (L->v_local != G || L->residual_window != G)) return KITTY_ERR_UNSUPPORTED;
+  if (L->v_bits != 0 && L->v_bits != 2 && L->v_bits != 4) return KITTY_ERR_INVALID_ARG;
+  if (L->v_bits == 4 && nb16 > 1) return KITTY_ERR_UNSUPPORTED;   // 4-bit Values: with n_boost 0 or 16 only
   return KITTY_OK;
 }
 
@@ -84,14 +86,25 @@ void plan_splits(const kitty_layout* L, int32_t batch, int32_t max_pages, int32_
   *min_pages = mp;
 }
 
+bool v4_of(const kitty_layout* L) { return L->v_bits == 4; }
+
+// f(number of 16-channel boost blocks, 4-bit Values?) with both as compile-time constants
 template <typename F>
-int dispatch_nb16(int nb16, F&& f) {
+int dispatch_variant(const kitty_layout* L, F&& f) {
+  const int nb16 = L->n_boost / 16;
+  if (v4_of(L)) {
+    switch (nb16) {
+      case 0: return f(std::integral_constant<int, 0>{}, std::true_type{});
+      case 1: return f(std::integral_constant<int, 1>{}, std::true_type{});
+    }
+    return KITTY_ERR_UNSUPPORTED;
+  }
   switch (nb16) {
-    case 0: return f(std::integral_constant<int, 0>{});
-    case 1: return f(std::integral_constant<int, 1>{});
-    case 2: return f(std::integral_constant<int, 2>{});
-    case 4: return f(std::integral_constant<int, 4>{});
-    case 8: return f(std::integral_constant<int, 8>{});
+    case 0: return f(std::integral_constant<int, 0>{}, std::false_type{});
+    case 1: return f(std::integral_constant<int, 1>{}, std::false_type{});
+    case 2: return f(std::integral_constant<int, 2>{}, std::false_type{});
+    case 4: return f(std::integral_constant<int, 4>{}, std::false_type{});
+    case 8: return f(std::integral_constant<int, 8>{}, std::false_type{});
   }
   return KITTY_ERR_UNSUPPORTED;
 }
@@ -156,12 +169,12 @@ extern "C" {
 
 size_t kitty_page_bytes(const kitty_layout* L) {
   if (check_layout(L) != KITTY_OK) return 0;
-  return (size_t)record_bytes(L->n_boost / 16);
+  return (size_t)record_bytes(L->n_boost / 16, v4_of(L));
 }
 
 size_t kitty_page_payload_bytes(const kitty_layout* L) {
   if (check_layout(L) != KITTY_OK) return 0;
-  return (size_t)record_bytes(L->n_boost / 16) - (size_t)(128 - L->n_boost);
+  return (size_t)record_bytes(L->n_boost / 16, v4_of(L)) - (size_t)(128 - L->n_boost);
 }
 
 int kitty_decode_plan(const kitty_layout* L, int32_t batch, int32_t max_pages, int32_t n_splits_req,
@@ -208,9 +221,10 @@ int kitty_quantize_pages(const kitty_layout* L, const void* k_src, const void* v
   P.n_pool_pages = n_pool_pages;
   P.rank_metric = L->rank_metric;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  return dispatch_nb16(L->n_boost / 16, [&](auto nb) {
+  return dispatch_variant(L, [&](auto nb, auto v4) {
     constexpr int NB = decltype(nb)::value;
-    hipLaunchKernelGGL(quantize_pages_kernel<NB>, dim3(n_pages, L->n_kv_heads), dim3(256), 0, st, P);
+    constexpr bool V4 = decltype(v4)::value;
+    hipLaunchKernelGGL((quantize_pages_kernel<NB, V4>), dim3(n_pages, L->n_kv_heads), dim3(256), 0, st, P);
     return launch_status();
   });
 }
@@ -246,9 +260,10 @@ int kitty_append_token(const kitty_layout* L, const kitty_cache* C, const void* 
   P.n_kv_heads = L->n_kv_heads;
   P.rank_metric = L->rank_metric;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  return dispatch_nb16(L->n_boost / 16, [&](auto nb) {
+  return dispatch_variant(L, [&](auto nb, auto v4) {
     constexpr int NB = decltype(nb)::value;
-    hipLaunchKernelGGL(append_token_kernel<NB>, dim3(L->n_kv_heads, C->batch), dim3(256), 0, st, P);
+    constexpr bool V4 = decltype(v4)::value;
+    hipLaunchKernelGGL((append_token_kernel<NB, V4>), dim3(L->n_kv_heads, C->batch), dim3(256), 0, st, P);
     return launch_status();
   });
 }
@@ -296,12 +311,13 @@ int launch_split(const kitty_layout* L, const kitty_cache* C, const void* q, flo
   const bool wide = P.gqa == 8;
   const bool big = waves_per_block(C->max_pages, P.n_splits) == 8;
   const bool fused = step != nullptr;
-  return dispatch_nb16(L->n_boost / 16, [&](auto nb) {
+  return dispatch_variant(L, [&](auto nb, auto v4) {
     constexpr int NB = decltype(nb)::value;
+    constexpr bool V4 = decltype(v4)::value;
     auto go = [&](auto hpl, auto nw, auto fu) {
       constexpr int HPL = decltype(hpl)::value, NW = decltype(nw)::value;
       constexpr bool FU = decltype(fu)::value;
-      hipLaunchKernelGGL((decode_split_kernel<NB, HPL, NW, FU>), grid, dim3(64 * NW), 0, st, P);
+      hipLaunchKernelGGL((decode_split_kernel<NB, HPL, NW, FU, V4>), grid, dim3(64 * NW), 0, st, P);
     };
     using I1 = std::integral_constant<int, 1>; using I2 = std::integral_constant<int, 2>;
     using I4 = std::integral_constant<int, 4>; using I8 = std::integral_constant<int, 8>;
@@ -372,7 +388,7 @@ const char* kitty_strerror(int code) {
   switch (code) {
     case KITTY_OK: return "ok";
     case KITTY_ERR_INVALID_ARG: return "invalid argument (null pointer, bad alignment or inconsistent sizes)";
-    case KITTY_ERR_UNSUPPORTED: return "unsupported size (head_dim, page_size, residual window, Sink, Local window, boost count or GQA group)";
+    case KITTY_ERR_UNSUPPORTED: return "unsupported size (head_dim, page_size, residual window, Sink, Local window, boost count, Value bits or GQA group)";
     case KITTY_ERR_WORKSPACE: return "workspace too small";
     case KITTY_ERR_HIP: return "HIP launch failed";
   }

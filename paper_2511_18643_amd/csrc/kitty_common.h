@@ -15,10 +15,11 @@ constexpr int G = 128;   // page_size
 //   ch              uint8[n_boost] ascending, zero-padded to 128 B
 //   V plane         4096 B   word (d, wv) at 1024*(d/32) + 16*((d%16) + 16*(wv%4)) + 4*(2*((d/16)%2) + wv/4)
 //                   position p of a channel row holds token 16*(p%8) + p/8
+//   V high plane    4096 B   only with 4-bit Values (V4): the high two bits, placed like the V plane
 //   v_scale, v_zero fp16[128] each, position order
 // Every word holds sixteen 2-bit elements, element a at bit 8*(a%4) + 2*(a/4), so that
 // (w >> 2v) & 0x03030303 yields elements 4v..4v+3 as four bytes: an int8 matrix-core operand.
-template <int NB16>
+template <int NB16, bool V4 = false>
 struct Rec {
   static constexpr int kd = 0;
   static constexpr int kb = 4096;
@@ -26,12 +27,13 @@ struct Rec {
   static constexpr int kz = ks + 256;
   static constexpr int ch = kz + 256;
   static constexpr int vd = ch + 128;
-  static constexpr int vs = vd + 4096;
+  static constexpr int vh = vd + 4096;
+  static constexpr int vs = vh + (V4 ? 4096 : 0);
   static constexpr int vz = vs + 256;
   static constexpr int bytes = vz + 256;
 };
 
-__host__ __device__ constexpr int record_bytes(int nb16) { return 9344 + 512 * nb16; }
+__host__ __device__ constexpr int record_bytes(int nb16, bool v4 = false) { return 9344 + 512 * nb16 + (v4 ? 4096 : 0); }
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 

@@ -72,21 +72,22 @@ __device__ __forceinline__ int active_splits(int np, int r, int n_splits, int mi
 // One page's code planes as they sit in a lane's registers.  The four fp16 arrays travel separately: lane
 // group 0 fetches k_scale, 1 k_zero, 2 v_scale, 3 v_zero (entries 8j..8j+7 each) and the groups exchange
 // them through LDS.
-template <int NB16>
+template <int NB16, bool V4 = false>
 struct PageRegs {
   uint4 kd[4];
   uint2 kb[NB16 ? NB16 : 1];
   uint32_t chv[NB16 ? NB16 : 1];
   uint4 vd[4];
+  uint4 vh[V4 ? 4 : 1];   // high Value plane (4-bit Values)
 };
 
 // Byte offsets of a lane into a record (32-bit, so loads take the scalar record base + one VGPR offset).
 struct LaneOffsets {
   uint32_t o16, o8, j, meta;
 };
-template <int NB16>
+template <int NB16, bool V4>
 __device__ __forceinline__ LaneOffsets lane_offsets(int l) {
-  using R = Rec<NB16>;
+  using R = Rec<NB16, V4>;
   const uint32_t j = l & 15, gi = l >> 4;
   const uint32_t base = gi == 0 ? R::ks : (gi == 1 ? R::kz : (gi == 2 ? R::vs : R::vz));
   return LaneOffsets{(uint32_t)l * 16u, (uint32_t)l * 8u, j, base + 16u * j};
@@ -95,15 +96,15 @@ __device__ __forceinline__ LaneOffsets lane_offsets(int l) {
 // A page is fetched in three pieces: the lane's 16 bytes of fp16 arrays, the Key planes (+ channel list), the
 // Value plane.  Each piece of the next page is requested as soon as the registers of the current one are dead.
 // Records are addressed through a buffer resource (base = the record, size = its bytes): the loads take the
-// scalar descriptor, one 32-bit lane offset and a constant, so no vector address arithmetic is needed, and a
-// descriptor of size 0 ("no next page") makes every load return zeros without touching memory.
+// scalar descriptor, one 32-bit lane offset and a constant, so no vector address arithmetic is needed (and an
+// offset beyond the record would read zeros instead of foreign memory).
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 typedef unsigned int v2u __attribute__((ext_vector_type(2)));
 using RecRef = __amdgpu_buffer_rsrc_t;
-template <int NB16>
-__device__ __forceinline__ RecRef rec_ref(const uint8_t* rec, bool present) {
+template <int NB16, bool V4>
+__device__ __forceinline__ RecRef rec_ref(const uint8_t* rec) {
   // word 3 of a gfx9-family raw buffer descriptor: 32-bit data format, no swizzle, range-checked by byte offset
-  return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(rec), 0, present ? Rec<NB16>::bytes : 0, 0x00020000);
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(rec), 0, Rec<NB16, V4>::bytes, 0x00020000);
 }
 __device__ __forceinline__ uint4 buf_load16(RecRef r, uint32_t voff, int soff) {
   const v4u v = __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0);
@@ -113,9 +114,9 @@ template <int NB16>
 __device__ __forceinline__ uint4 load_meta(RecRef rec, const LaneOffsets& o) {
   return buf_load16(rec, o.meta, 0);
 }
-template <int NB16>
-__device__ __forceinline__ void load_k(PageRegs<NB16>& r, RecRef rec, const LaneOffsets& o) {
-  using R = Rec<NB16>;
+template <int NB16, bool V4>
+__device__ __forceinline__ void load_k(PageRegs<NB16, V4>& r, RecRef rec, const LaneOffsets& o) {
+  using R = Rec<NB16, V4>;
 #pragma unroll
   for (int i = 0; i < 4; ++i) r.kd[i] = buf_load16(rec, o.o16, R::kd + 1024 * i);
 #pragma unroll
@@ -125,11 +126,15 @@ __device__ __forceinline__ void load_k(PageRegs<NB16>& r, RecRef rec, const Lane
     r.chv[s] = __builtin_amdgcn_raw_buffer_load_b8(rec, o.j, R::ch + 16 * s, 0);
   }
 }
-template <int NB16>
-__device__ __forceinline__ void load_v(PageRegs<NB16>& r, RecRef rec, const LaneOffsets& o) {
-  using R = Rec<NB16>;
+template <int NB16, bool V4>
+__device__ __forceinline__ void load_v(PageRegs<NB16, V4>& r, RecRef rec, const LaneOffsets& o) {
+  using R = Rec<NB16, V4>;
 #pragma unroll
   for (int i = 0; i < 4; ++i) r.vd[i] = buf_load16(rec, o.o16, R::vd + 1024 * i);
+  if constexpr (V4) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r.vh[i] = buf_load16(rec, o.o16, R::vh + 1024 * i);
+  }
 }
 
 // sixteen 2-bit elements -> four registers of four int8 each (elements 4v..4v+3 in register v)
@@ -268,7 +273,7 @@ union __attribute__((aligned(16))) DecodeSmem {
 // (wA, wB) = (1, 4) for even j and (16, 1) for odd j; it divides its values by that weight before
 // taking the integer image, and keeps sums and maxima of unweighted values by recombining two halves.
 // Groups of eight query heads (HPL == 2) carry two terms (16-bit images, plain unpack); see THIRD_PASS.
-template <int NB16, int HPL>
+template <int NB16, int HPL, bool V4 = false>
 struct PageWorker {
   // Eight-head groups: a third byte term needs 24 matrix rows, i.e. a second MFMA pass over the same code
   // operand.  Measured on the 128k-context workload it costs 20 % of the kernel's throughput (the matrix
@@ -278,6 +283,7 @@ struct PageWorker {
   static constexpr int TR = (HPL == 1 || THIRD_PASS) ? 3 : 2;     // byte terms per value
   static constexpr bool WEIGHTED = TR == 3;       // mask-only unpack (relies on the precision of three terms)
   static constexpr bool TWO_PASS = HPL == 2 && THIRD_PASS;
+  static_assert(!(V4 && TWO_PASS), "the high Value plane has no second-pass accumulator");
   static constexpr float NLIM = TR == 3 ? 1048000.0f : 32000.0f;   // bound of the integer images
 
   // Matrix row of term t of head hd.  Four heads: rows 4hd + t of one matrix.  Eight heads: terms 0, 1 in
@@ -305,7 +311,7 @@ struct PageWorker {
   static constexpr int B_PASS = 16 * (16 * (NB16 ? NB16 : 1) + 16);
 
   __device__ __forceinline__ PageWorker(WaveScratch<NB16, HPL>& ws_, int l)
-      : ws(ws_), j(l & 15), gi(l >> 4), lo(lane_offsets<NB16>(l)) {
+      : ws(ws_), j(l & 15), gi(l >> 4), lo(lane_offsets<NB16, V4>(l)) {
     a_ptr = &ws.abuf[j][16 * gi];
     p_ptr = &ws.pbuf[j][16 * gi];
 #pragma unroll
@@ -343,7 +349,7 @@ struct PageWorker {
 
   // Phases A-C: integer logits of the 128 tokens of the page in `pg` (k_scale, k_zero staged in LDS).
   // The logit of head gi*HPL + e and token 16T + j is inv_alpha[e] * join(dq[T]...) + bias[e] (log2 domain).
-  __device__ __forceinline__ void logits(const PageRegs<NB16>& pg, v4i (&dq)[8], v4i (&dqx)[TWO_PASS ? 8 : 1],
+  __device__ __forceinline__ void logits(const PageRegs<NB16, V4>& pg, v4i (&dq)[8], v4i (&dqx)[TWO_PASS ? 8 : 1],
                                          float (&inv_alpha)[HPL], float (&bias)[HPL]) {
     // ================= A: integer image of q*s, bias q.z =================
     float ks[8], kz[8];
@@ -456,7 +462,7 @@ struct PageWorker {
 
   // Logits only (log2 domain, float) of the page in `pg`, stored as x[token][head]: used for the newest page
   // when its Values are still read in full precision (they are then handled with the other bf16 rows).
-  __device__ __forceinline__ void logits_to(const PageRegs<NB16>& pg, float (*x)[4 * HPL]) {
+  __device__ __forceinline__ void logits_to(const PageRegs<NB16, V4>& pg, float (*x)[4 * HPL]) {
     v4i dq[8], dqx[TWO_PASS ? 8 : 1];
     float inv_alpha[HPL], bias[HPL];
     logits(pg, dq, dqx, inv_alpha, bias);
@@ -470,13 +476,13 @@ struct PageWorker {
   // Processes the page held in `pg` (its fp16 arrays already staged in LDS).  The pieces of the wavefront's
   // next page (record `rec_nx`; an empty reference if there is none) are requested into the same registers as
   // soon as they are dead.
-  __device__ __forceinline__ void process(PageRegs<NB16>& pg, RecRef rec_nx, bool has_nx) {
+  __device__ __forceinline__ void process(PageRegs<NB16, V4>& pg, RecRef rec_nx, bool has_nx) {
     uint4 meta_nx = make_uint4(0, 0, 0, 0);
     if (has_nx) meta_nx = load_meta<NB16>(rec_nx, lo);
     v4i dq[8], dqx[TWO_PASS ? 8 : 1];
     float inv_alpha[HPL], bias[HPL];
     logits(pg, dq, dqx, inv_alpha, bias);
-    if (has_nx) load_k<NB16>(pg, rec_nx, lo);   // the Key planes of this page are in the matrix pipeline now
+    if (has_nx) load_k<NB16, V4>(pg, rec_nx, lo);   // the Key planes of this page are in the matrix pipeline now
     // ================= D: online softmax; lane (j, gi) owns token 16T + j of heads gi*HPL + e ==========
     float vs[8], vz[8];
     f16x8_to_f32(*reinterpret_cast<const uint4*>(&ws.meta[2][16 * j]), vs);
@@ -541,24 +547,28 @@ struct PageWorker {
       const uint4 ld = pg.vd[Td >> 1];
       const uint32_t w0 = (Td & 1) ? ld.z : ld.x, w1 = (Td & 1) ? ld.w : ld.y;
       const v4i b0 = unpack(w0), b1 = unpack(w1);
-      v4i c = {0, 0, 0, 0}, cx = {0, 0, 0, 0};
+      v4i c = {0, 0, 0, 0}, cx = {0, 0, 0, 0}, chi = {0, 0, 0, 0};
       c = __builtin_amdgcn_mfma_i32_16x16x64_i8(pa0, b0, c, 0, 0, 0);
       c = __builtin_amdgcn_mfma_i32_16x16x64_i8(pa1, b1, c, 0, 0, 0);
+      if constexpr (V4) {   // the high two bits of 4-bit Values: same contraction, weight 4
+        const uint4 lh = pg.vh[Td >> 1];
+        const v4i h0 = unpack((Td & 1) ? lh.z : lh.x), h1 = unpack((Td & 1) ? lh.w : lh.y);
+        chi = __builtin_amdgcn_mfma_i32_16x16x64_i8(pa0, h0, chi, 0, 0, 0);
+        chi = __builtin_amdgcn_mfma_i32_16x16x64_i8(pa1, h1, chi, 0, 0, 0);
+      }
       if constexpr (TWO_PASS) {
         cx = __builtin_amdgcn_mfma_i32_16x16x64_i8(pa0x, b0, cx, 0, 0, 0);
         cx = __builtin_amdgcn_mfma_i32_16x16x64_i8(pa1x, b1, cx, 0, 0, 0);
       }
 #pragma unroll
       for (int e = 0; e < HPL; ++e) {
-        int ne;
-        if constexpr (HPL == 1) ne = join_terms(c[0], c[1], c[2]);
-        else if constexpr (TWO_PASS) ne = join_terms(c[2 * e], c[2 * e + 1], cx[e]);
-        else ne = join_terms(c[2 * e], c[2 * e + 1]);
+        int ne = joined(c, cx, e);
+        if constexpr (V4) ne += 4 * joined(chi, cx, e);
         fma_in_place(acc[e][Td], rescale[e], (float)ne);
       }
     }
     if (has_nx) {
-      load_v<NB16>(pg, rec_nx, lo);
+      load_v<NB16, V4>(pg, rec_nx, lo);
       stage_meta(meta_nx);   // requested at the top of this page
     }
     wave_lds_fence();   // the next page overwrites abuf/pbuf and reads the staged arrays
@@ -580,9 +590,9 @@ constexpr int decode_waves_per_simd() { return 2; }
 // freshly written record is fenced before it is read back, and the sequence state is advanced by the block of
 // the sequence that is last to have read the old state (ticket in bits 8.. of n_resid, as in append_token_kernel;
 // the ticket is taken right after the state has been read and looked at only at the end).
-template <int NB16, int HPL, int NW, bool FUSED>
+template <int NB16, int HPL, int NW, bool FUSED, bool V4>
 __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void decode_split_kernel(DecodeParams p) {
-  using R = Rec<NB16>;
+  using R = Rec<NB16, V4>;
   constexpr int RPH = 4 / HPL;
   constexpr int NH = 4 * HPL;              // heads handled by the block
 
@@ -632,7 +642,7 @@ __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void
         if (flush) {
           uint8_t* rec = p.pool_w + ((size_t)pid * p.n_kv_heads + h) * (size_t)R::bytes;
           const uint16_t* wv_old = p.resid_v_w + resid_v_offset(b, h, p.n_kv_heads, p.v_local, np_old);
-          quantize_page<NB16>(smem.quant, wkw, wv_old, D, rec, p.rank_metric);
+          quantize_page<NB16, V4>(smem.quant, wkw, wv_old, D, rec, p.rank_metric);
           __threadfence();          // the record is read back by this block's wavefronts
           __syncthreads();
           fresh_pid = pid;
@@ -684,7 +694,7 @@ __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void
   float (*lagx)[NH] = reinterpret_cast<float (*)[NH]>(&smem.w[lag_here ? (p1q - p0) % NW : 0].nbuf[0][0]);
   static_assert(sizeof(ws.nbuf) == sizeof(float) * G * NH, "lagx aliases nbuf");
   const size_t qrow = ((size_t)b * p.n_q_heads + (size_t)h * g);
-  PageWorker<NB16, HPL> pw(ws, l);
+  PageWorker<NB16, HPL, V4> pw(ws, l);
 
   if (p0 < p1) {
     const int32_t* pt = p.page_table + (size_t)b * p.max_pages;
@@ -703,7 +713,7 @@ __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void
       return pool_h + (size_t)id * rec_stride;
     };
     // one register buffer: each piece of the next page is requested when the current page no longer needs it.
-    PageRegs<NB16> pg{};
+    PageRegs<NB16, V4> pg{};
     int idx = p0 + w;
     uint4 m0 = make_uint4(0, 0, 0, 0);
     // ---- zero the operand matrices once (rows of absent heads and the unused term row stay zero)
@@ -722,10 +732,10 @@ __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void
       pw.set_q(e, raw, p.qk_scale_log2, live);
     }
     if (idx < p1) {
-      const RecRef rec = rec_ref<NB16>(rec_at(0, idx), true);
+      const RecRef rec = rec_ref<NB16, V4>(rec_at(0, idx));
       m0 = load_meta<NB16>(rec, pw.lo);
-      load_k<NB16>(pg, rec, pw.lo);
-      load_v<NB16>(pg, rec, pw.lo);
+      load_k<NB16, V4>(pg, rec, pw.lo);
+      load_v<NB16, V4>(pg, rec, pw.lo);
       pw.stage_meta(m0);
       wave_lds_fence();
       // The two wavefronts that share a SIMD take the higher issue priority in turn, page by page: with equal
@@ -739,7 +749,7 @@ __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void
         ++turn;
         ++k;
         if ((k & 63) == 0) ids = load_ids(k);
-        pw.process(pg, rec_ref<NB16>(has_nx ? rec_at(k, idx + NW) : pool_h, true), has_nx);
+        pw.process(pg, rec_ref<NB16, V4>(has_nx ? rec_at(k, idx + NW) : pool_h), has_nx);
       }
       __builtin_amdgcn_s_setprio(0);
       if (lag_here && idx == p1q) pw.logits_to(pg, lagx);   // this wavefront holds the newest page

@@ -25,6 +25,7 @@ struct QuantSmem {
       uint8_t codes[G][D];   // 4-bit Key codes [token][channel], read back by the boost-plane pass
       uint32_t kout[1024];   // dense Key plane as it goes to memory
       uint32_t vout[1024];   // Value plane as it goes to memory
+      uint32_t vout_hi[1024];  // high Value plane (4-bit Values only)
     } pk;
   };
   double score[D];
@@ -86,10 +87,11 @@ __device__ __forceinline__ void fetch_tile(TileRegs& r, const uint16_t* __restri
 
 // One block of at least 256 threads; threads 0..255 do the work, every thread takes part in the barriers.
 // Both source pages are read into registers before the first barrier and never touched again.
-template <int NB16>
+template <int NB16, bool V4 = false>
 __device__ __forceinline__ void quantize_page(QuantSmem& s, const uint16_t* __restrict__ ksrc, const uint16_t* __restrict__ vsrc,
                                               int64_t token_stride, uint8_t* __restrict__ rec, int rank_metric) {
-  using R = Rec<NB16>;
+  using R = Rec<NB16, V4>;
+  constexpr float VQMAX = V4 ? 15.0f : 3.0f;
   const int tid = threadIdx.x;
   const bool act = tid < 256;
   const int c = tid & 127;
@@ -238,7 +240,7 @@ __device__ __forceinline__ void quantize_page(QuantSmem& s, const uint16_t* __re
 #pragma unroll
     for (int i = 1; i < 8; ++i) { mnv = part == i ? tmn[i] : mnv; mxv = part == i ? tmx[i] : mxv; }
     if (part < 8) {
-      const uint16_t sh = f32_to_f16_bits(__fdiv_rn(__fsub_rn(mxv, mnv), 3.0f));
+      const uint16_t sh = f32_to_f16_bits(__fdiv_rn(__fsub_rn(mxv, mnv), VQMAX));
       const uint16_t zh = f32_to_f16_bits(mnv);
       const int p = 8 * cls + part;        // position of token cls + 16*part
       s.vinv[p] = inv_scale(f16_bits_to_f32(sh));
@@ -279,7 +281,7 @@ __device__ __forceinline__ void quantize_page(QuantSmem& s, const uint16_t* __re
         float x[8];
         widen8(vq.v[i], x);
 #pragma unroll
-        for (int k = 0; k < 8; ++k) u[i][k] = qcode_bits(x[k], inv[i], zr[i], 3.0f);
+        for (int k = 0; k < 8; ++k) u[i][k] = qcode_bits(x[k], inv[i], zr[i], VQMAX);
       }
 #pragma unroll
       for (int k = 0; k < 8; ++k) r0[k] = low_bytes(u[0][k], u[1][k], u[2][k], u[3][k]);
@@ -288,7 +290,7 @@ __device__ __forceinline__ void quantize_page(QuantSmem& s, const uint16_t* __re
         float x[8];
         widen8(vq.v[4 + i], x);
 #pragma unroll
-        for (int k = 0; k < 8; ++k) u[i][k] = qcode_bits(x[k], inv[4 + i], zr[4 + i], 3.0f);
+        for (int k = 0; k < 8; ++k) u[i][k] = qcode_bits(x[k], inv[4 + i], zr[4 + i], VQMAX);
       }
 #pragma unroll
       for (int k = 0; k < 8; ++k) r1[k] = low_bytes(u[0][k], u[1][k], u[2][k], u[3][k]);
@@ -301,10 +303,18 @@ __device__ __forceinline__ void quantize_page(QuantSmem& s, const uint16_t* __re
       const uint32_t half = ((r0[k] & 0x03030303u) | ((r1[k] & 0x03030303u) << 2)) << sh0;
       const uint32_t other = (uint32_t)__shfl_xor((int)half, 16);
       if (((cls & 1) == 0) == (k < 4)) s.pk.vout[plane_word(8 * part + k, wv)] = half | other;   // each lane of the pair stores four
+      if constexpr (V4) {
+        const uint32_t hh = (((r0[k] & 0x0c0c0c0cu) >> 2) | (r1[k] & 0x0c0c0c0cu)) << sh0;
+        const uint32_t ho = (uint32_t)__shfl_xor((int)hh, 16);
+        if (((cls & 1) == 0) == (k < 4)) s.pk.vout_hi[plane_word(8 * part + k, wv)] = hh | ho;
+      }
     }
   }
   __syncthreads();
-  if (act) *reinterpret_cast<uint4*>(rec + R::vd + 16 * tid) = *reinterpret_cast<const uint4*>(&s.pk.vout[4 * tid]);
+  if (act) {
+    *reinterpret_cast<uint4*>(rec + R::vd + 16 * tid) = *reinterpret_cast<const uint4*>(&s.pk.vout[4 * tid]);
+    if constexpr (V4) *reinterpret_cast<uint4*>(rec + R::vh + 16 * tid) = *reinterpret_cast<const uint4*>(&s.pk.vout_hi[4 * tid]);
+  }
   __syncthreads();   // the shared memory may be reused by the caller after this
 }
 
@@ -318,15 +328,15 @@ struct QuantPagesParams {
   int32_t n_kv_heads, n_pool_pages, rank_metric;
 };
 
-template <int NB16>
+template <int NB16, bool V4>
 __global__ __launch_bounds__(256, 4) void quantize_pages_kernel(QuantPagesParams p) {
   __shared__ QuantSmem smem;
   const int i = blockIdx.x, h = blockIdx.y;
   const int32_t pid = p.dst_page_ids[i];
   if (pid < 0 || pid >= p.n_pool_pages) return;
   const int64_t off = (p.src_page_offsets ? p.src_page_offsets[i] : (int64_t)i * p.page_stride) + (int64_t)h * p.head_stride;
-  uint8_t* rec = p.pool + ((size_t)pid * p.n_kv_heads + h) * (size_t)Rec<NB16>::bytes;
-  quantize_page<NB16>(smem, p.k_src + off, p.v_src + off, p.token_stride, rec, p.rank_metric);
+  uint8_t* rec = p.pool + ((size_t)pid * p.n_kv_heads + h) * (size_t)Rec<NB16, V4>::bytes;
+  quantize_page<NB16, V4>(smem, p.k_src + off, p.v_src + off, p.token_stride, rec, p.rank_metric);
 }
 
 struct AppendParams {
@@ -362,7 +372,7 @@ __device__ __forceinline__ size_t resid_v_offset(int b, int h, int n_kv_heads, i
 // of the last ticket writes the new state, which also clears the tickets.
 constexpr int TICKET_SHIFT = 8;
 
-template <int NB16>
+template <int NB16, bool V4>
 __global__ __launch_bounds__(256, 4) void append_token_kernel(AppendParams p) {
   __shared__ QuantSmem smem;
   const int h = blockIdx.x, b = blockIdx.y;
@@ -388,8 +398,8 @@ __global__ __launch_bounds__(256, 4) void append_token_kernel(AppendParams p) {
     int slot = nr;
     uint16_t* wv = p.resid_v + resid_v_offset(b, h, p.n_kv_heads, p.v_local, np);
     if (flush) {
-      uint8_t* rec = p.pool + ((size_t)pid * p.n_kv_heads + h) * (size_t)Rec<NB16>::bytes;
-      quantize_page<NB16>(smem, wk, wv, D, rec, p.rank_metric);
+      uint8_t* rec = p.pool + ((size_t)pid * p.n_kv_heads + h) * (size_t)Rec<NB16, V4>::bytes;
+      quantize_page<NB16, V4>(smem, wk, wv, D, rec, p.rank_metric);
       slot = 0;
       wv = p.resid_v + resid_v_offset(b, h, p.n_kv_heads, p.v_local, np + 1);
     }

@@ -27,7 +27,7 @@ EXPORTS = (
 
 class KittyLayout(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("head_dim", "page_size", "v_group", "n_boost", "residual_window",
-                                         "n_q_heads", "n_kv_heads", "rank_metric", "sink_tokens", "v_local")]
+                                         "n_q_heads", "n_kv_heads", "rank_metric", "sink_tokens", "v_local", "v_bits")]
 
 
 class KittyCache(C.Structure):
@@ -83,9 +83,9 @@ def lib() -> C.CDLL:
 
 def make_layout(n_q_heads: int, n_kv_heads: int, n_boost: int = 16, residual_window: int = 128,
                 rank_metric: int = 0, head_dim: int = 128, page_size: int = 128, v_group: int = 128,
-                sink_tokens: int = 0, v_local: int = 0) -> KittyLayout:
+                sink_tokens: int = 0, v_local: int = 0, v_bits: int = 2) -> KittyLayout:
     return KittyLayout(head_dim, page_size, v_group, n_boost, residual_window, n_q_heads, n_kv_heads, rank_metric,
-                       sink_tokens, v_local)
+                       sink_tokens, v_local, v_bits)
 
 
 def _ptr(t) -> int | None:

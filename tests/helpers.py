@@ -22,9 +22,9 @@ def gen_sequences(w, lengths):
     return k, v
 
 
-def oracle_cache(w, lengths, k, v, max_pages):
+def oracle_cache(w, lengths, k, v, max_pages, v_bits=2):
     c = ko.KittyCacheOracle(w.batch, w.n_kv_heads, w.n_q_heads, w.n_boost, w.residual_window,
-                            max_pages, w.batch * max_pages, w.rank_metric)
+                            max_pages, w.batch * max_pages, w.rank_metric, v_bits)
     for b in range(w.batch):
         n_pages, r = w.pages_and_resid(lengths[b]) if lengths[b] else (0, 0)
         ids = np.arange(n_pages) + b * max_pages
@@ -46,11 +46,11 @@ def bf16_tensor(bits, device="cuda"):
     return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(device).view(torch.bfloat16)
 
 
-def gpu_cache(w, lengths, k, v, max_pages, poison=True):
+def gpu_cache(w, lengths, k, v, max_pages, poison=True, v_bits=2):
     """Cache filled by kitty_quantize_pages + window copies.  Returns (layout, Cache)."""
     import torch
     from paper_2511_18643_amd import kitty
-    layout = kitty.make_layout(w.n_q_heads, w.n_kv_heads, w.n_boost, w.residual_window, w.rank_metric)
+    layout = kitty.make_layout(w.n_q_heads, w.n_kv_heads, w.n_boost, w.residual_window, w.rank_metric, v_bits=v_bits)
     c = kitty.Cache(layout, w.batch, max_pages, w.batch * max_pages)
     if poison:
         c.pool.fill_(0xA5)      # every byte of a written record must be overwritten

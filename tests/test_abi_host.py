@@ -45,6 +45,12 @@ def test_unsupported_layouts_are_rejected():
     assert kitty.kitty_page_bytes(kitty.make_layout(30, 8, 16)) == 0           # heads do not divide
     assert kitty.kitty_page_bytes(kitty.make_layout(48, 8, 16)) == 0           # GQA group of 6
     assert kitty.kitty_page_bytes(kitty.make_layout(32, 8, 16, rank_metric=2)) == 0
+    # 4-bit Values: one more 4 KB plane; only with 0 or 16 boosted channels
+    assert kitty.kitty_page_bytes(kitty.make_layout(32, 8, 16, v_bits=4)) == 9856 + 4096
+    assert kitty.kitty_page_payload_bytes(kitty.make_layout(32, 8, 0, v_bits=4)) == 9216 + 4096
+    assert kitty.kitty_page_bytes(kitty.make_layout(32, 8, 16, v_bits=0)) == 9856
+    assert kitty.kitty_page_bytes(kitty.make_layout(32, 8, 32, v_bits=4)) == 0
+    assert kitty.kitty_page_bytes(kitty.make_layout(32, 8, 16, v_bits=3)) == 0
     # Sink up to one page; the Value Local window is one page long and needs the residual window
     assert kitty.kitty_page_bytes(kitty.make_layout(32, 8, 16, sink_tokens=32, v_local=128)) == 9856
     assert kitty.kitty_page_bytes(kitty.make_layout(32, 8, 16, sink_tokens=129)) == 0

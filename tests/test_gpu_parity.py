@@ -28,13 +28,13 @@ def check_pool(w, lengths, oc, gc):
                     raise AssertionError(f"record b={b} page={i} head={h}: {len(bad)} bytes differ, first at {bad[:8]}")
 
 
-def run_case(w, lengths, n_splits_list=(0,), max_pages=None):
+def run_case(w, lengths, n_splits_list=(0,), max_pages=None, v_bits=2):
     # groups of 8 query heads carry two byte terms per value instead of three (coarser fixed point)
     tol32 = TOL_FP32 if w.gqa <= 4 else 1e-3
     k, v = H.gen_sequences(w, lengths)
     mp = max_pages or max(max((w.pages_and_resid(n)[0] if n else 0) for n in lengths), 1)
-    oc = H.oracle_cache(w, lengths, k, v, mp)
-    layout, gc = H.gpu_cache(w, lengths, k, v, mp)
+    oc = H.oracle_cache(w, lengths, k, v, mp, v_bits)
+    layout, gc = H.gpu_cache(w, lengths, k, v, mp, v_bits=v_bits)
     check_pool(w, lengths, oc, gc)
     q = synth.query(w)
     want = oc.decode_attention(q, w.sm_scale)
@@ -407,3 +407,44 @@ def test_quantize_pages_reads_projection_layout_in_place():
                 vp = ko.quantize_v_page(ko.bf16_bits_to_f32(v[b, h, 128 * i:128 * (i + 1)]))
                 assert np.array_equal(got[pid, h], ko.pack_record(kp, vp)), (b, i, h)
             pid += 1
+
+
+# ------------------------------------------------------------------ 4-bit Values (the K2V4 point of Table 2)
+@pytest.mark.parametrize("nb,hq", [(0, 8), (16, 8), (16, 16), (0, 2)])
+def test_v4_values(nb, hq):
+    """Second Value plane with the high bits: records bit-exact, attention within the same bounds; ragged
+    lengths, several split plans."""
+    w = synth.scaled(synth.WORKLOADS["c2"], batch=4, n_q_heads=hq, n_kv_heads=2, n_boost=nb, context=0)
+    run_case(w, [128 + 1, 5 * 128 + 77, 0, 40 * 128 + 128], n_splits_list=(0, 1, 3), max_pages=48, v_bits=4)
+
+
+def test_v4_decode_steps_across_a_flush():
+    """kitty_decode_step and kitty_append_token with 4-bit Values: state, flushed records and outputs."""
+    import torch
+    from paper_2511_18643_amd import kitty
+    w = synth.scaled(synth.WORKLOADS["c2"], batch=3, n_q_heads=8, n_kv_heads=2, context=0)
+    start = [120, 128 + 127, 3 * 128 + 5]
+    k0, v0 = H.gen_sequences(w, start)
+    for fused in (True, False):
+        oc = H.oracle_cache(w, start, k0, v0, 6, 4)
+        layout, gc = H.gpu_cache(w, start, k0, v0, 6, v_bits=4)
+        assert kitty.kitty_page_bytes(layout) == 9856 + 4096
+        ws = kitty.new_workspace(layout, 3, 6)
+        out = torch.empty((3, 8, 128), dtype=torch.float32, device="cuda")
+        for step in range(1, 12):
+            kn, vn = synth.new_token(w, step)
+            q = synth.query(w, step)
+            fresh = np.array([b * 6 + int(oc.n_pages[b]) for b in range(3)], np.int32)
+            oc.append_token(kn, vn, fresh)
+            args = (H.bf16_tensor(kn), H.bf16_tensor(vn), torch.from_numpy(fresh).cuda())
+            if fused:
+                kitty.kitty_decode_step(layout, gc, *args, H.bf16_tensor(q), out, w.sm_scale, ws)
+            else:
+                kitty.kitty_append_token(layout, gc, *args)
+                kitty.kitty_decode_attention(layout, gc, H.bf16_tensor(q), out, w.sm_scale, ws)
+            torch.cuda.synchronize()
+            assert np.array_equal(gc.n_pages.cpu().numpy(), oc.n_pages) and np.array_equal(gc.n_resid.cpu().numpy(), oc.n_resid)
+            err = float(np.abs(out.cpu().numpy() - oc.decode_attention(q, w.sm_scale)).max())
+            assert err <= TOL_FP32, (fused, step, err)
+        check_pool(w, None, oc, gc)
+        assert list(oc.n_pages) == [1, 2, 3]
