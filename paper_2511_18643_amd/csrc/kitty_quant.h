@@ -22,7 +22,8 @@ struct QuantSmem {
       double sum[16][D];
     } st;
     struct {
-      uint8_t codes[G][D];   // 4-bit Key codes [token][channel], read back by the boost-plane pass
+      uint8_t codes[G][D + 4];   // 4-bit Key codes [token][channel] for the boost-plane pass (rows 33 dwords apart:
+                                 // the pass reads one channel of 64 tokens at a time)
       uint32_t kout[1024];   // dense Key plane as it goes to memory
       uint32_t vout[1024];   // Value plane as it goes to memory
       uint32_t vout_hi[1024];  // high Value plane (4-bit Values only)
@@ -215,7 +216,10 @@ __device__ __forceinline__ void quantize_page(QuantSmem& s, const uint16_t* __re
 #pragma unroll
       for (int k = 0; k < 8; ++k) u[k] = qcode_bits(x[k], inv[k], zr[k], qm[k]);
       const uint32_t r0 = low_bytes(u[0], u[1], u[2], u[3]), r1 = low_bytes(u[4], u[5], u[6], u[7]);
-      if constexpr (NB16 > 0) *reinterpret_cast<uint2*>(&s.pk.codes[t][8 * part]) = make_uint2(r0, r1);
+      if constexpr (NB16 > 0) {
+        *reinterpret_cast<uint32_t*>(&s.pk.codes[t][8 * part]) = r0;
+        *reinterpret_cast<uint32_t*>(&s.pk.codes[t][8 * part + 4]) = r1;
+      }
       const uint32_t half = ((r0 & 0x03030303u) | ((r1 & 0x03030303u) << 2)) << sh0;
       const uint32_t other = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)half, 0xB1, 0xf, 0xf, true);   // lane ^ 1
       if ((part & 1) == 0) s.pk.kout[plane_word(t, part >> 1)] = half | other;
