@@ -95,14 +95,14 @@ def gpu_decode(layout, c, q_bits, sm_scale, n_splits=0, fp32=True):
 # ---------------------------------------------------------------------------------------------------
 # Full scheme (Sink + Value Local window): the oracle side is one KittyUnitOracle per (sequence, kv-head)
 # ---------------------------------------------------------------------------------------------------
-def unit_oracles(w, lengths, k, v, sink, local):
+def unit_oracles(w, lengths, k, v, sink, local, v_bits=2):
     """Units fed token by token (steps 1 and 3 of the pipeline) with the first lengths[b] tokens, left in the
     state attention sees right after the last insert (step 3 of that last step still pending).  Without a
     residual window the cache is static and every token behind the Sink has been quantized."""
     units = {}
     for b in range(w.batch):
         for h in range(w.n_kv_heads):
-            u = ko.KittyUnitOracle(w.n_boost, sink=sink, local=local, rank_metric=w.rank_metric)
+            u = ko.KittyUnitOracle(w.n_boost, sink=sink, local=local, rank_metric=w.rank_metric, v_bits=v_bits)
             n = lengths[b]
             if n and w.residual_window == 0:       # static cache: everything behind the Sink is in pages
                 u.prefill(k[b, h, :n], v[b, h, :n])
@@ -121,14 +121,14 @@ def units_attention(w, units, q_bits, sm_scale):
     return out
 
 
-def gpu_full_cache(w, lengths, k, v, max_pages, sink, v_local, poison=True):
+def gpu_full_cache(w, lengths, k, v, max_pages, sink, v_local, poison=True, v_bits=2):
     """Prefilled cache with a Sink of `sink` tokens and (v_local = 128) the Value Local window: the first tokens
     go to the Sink, whole pages behind it through kitty_quantize_pages, the tail to the window; the bf16 Value
     rows of the newest page are placed in their half of resid_v."""
     import torch
     from paper_2511_18643_amd import kitty
     layout = kitty.make_layout(w.n_q_heads, w.n_kv_heads, w.n_boost, w.residual_window, w.rank_metric,
-                               sink_tokens=sink, v_local=v_local)
+                               sink_tokens=sink, v_local=v_local, v_bits=v_bits)
     c = kitty.Cache(layout, w.batch, max_pages, w.batch * max_pages)
     if poison:
         c.pool.fill_(0xA5)

@@ -172,3 +172,68 @@ def test_c3_shape_full_scheme_sampled():
         want = u.attention(q[b, h * g:(h + 1) * g], w.sm_scale)
         worst = max(worst, float(np.abs(got[b, h * g:(h + 1) * g] - want).max()))
     assert worst <= TOL_FP32, worst
+
+
+def test_randomized_configurations():
+    """Seeded random draws over the layout knobs (heads, GQA group, boost count, Value bits, Sink size, Local
+    window, ranking metric), batch shapes (ragged lengths incl. empty), split plans and dispatch orders; each
+    cache is prefilled, then advanced by three decode steps (alternating the one-call and two-call paths), and
+    every output is compared with the unit oracles."""
+    import torch
+    from paper_2511_18643_amd import kitty
+    rng = np.random.default_rng(20251127)
+    for trial in range(14):
+        hkv = int(rng.choice([1, 2, 4]))
+        g = int(rng.choice([1, 2, 4, 8]))
+        v_bits = int(rng.choice([2, 2, 4]))
+        nb = int(rng.choice([0, 16] if v_bits == 4 else [0, 16, 32, 64, 128]))
+        sink = int(rng.choice([0, 0, 7, 32, 128]))
+        v_local = int(rng.choice([0, 128]))
+        metric = int(rng.choice([0, 1]))
+        B = int(rng.integers(1, 5))
+        n_splits = int(rng.choice([0, 0, 1, 2, 5]))
+        max_pages = int(rng.choice([6, 40]))
+        w = synth.scaled(synth.WORKLOADS["c2"], batch=B, n_q_heads=hkv * g, n_kv_heads=hkv, n_boost=nb, context=0,
+                         rank_metric=metric, seed=9000 + trial)
+        top = (max_pages - 1) * 128
+        lengths = [int(x) for x in rng.integers(0, min(top, 20 * 128) + sink, size=B)]
+        if trial % 3 == 0:
+            lengths[0] = 0
+        k, v = H.gen_sequences(w, lengths)
+        units = H.unit_oracles(w, lengths, k, v, sink, v_local, v_bits)
+        layout, gc = H.gpu_full_cache(w, lengths, k, v, max_pages, sink, v_local, v_bits=v_bits)
+        if trial % 2:
+            gc.seq_order = torch.from_numpy(rng.permutation(B).astype(np.int32)).cuda()
+        # short, peaky sequences are the worst case of the fixed-point images: up to 3.5e-4 with 20-bit images
+        # (groups of up to four query heads) and up to 1.4e-3 with the 16-bit images of eight-head groups when
+        # the outlier channels are not boosted (measured over all variants); the stated bar is 2e-3
+        tol = 5e-4 if g <= 4 else 1.6e-3
+        tag = dict(trial=trial, hkv=hkv, g=g, v_bits=v_bits, nb=nb, sink=sink, v_local=v_local, metric=metric, B=B,
+                   n_splits=n_splits, max_pages=max_pages, lengths=lengths)
+        q = synth.query(w)
+        got = H.gpu_decode(layout, gc, q, w.sm_scale, n_splits, fp32=True)
+        err = float(np.abs(got - H.units_attention(w, units, q, w.sm_scale)).max())
+        assert np.isfinite(got).all(), tag
+        assert err <= tol, (err, str(tag))
+        ws = kitty.new_workspace(layout, B, max_pages, n_splits)
+        out = torch.empty((B, hkv * g, 128), dtype=torch.float32, device="cuda")
+        for step in range(1, 4):
+            kn, vn = synth.new_token(w, step)
+            q = synth.query(w, step)
+            # both sides turn a full window into a page at the start of the next step, so the page about to be
+            # written is the one after those the unit holds now
+            fresh = np.array([b * max_pages + len(units[(b, 0)].k_pages) for b in range(B)], np.int32)
+            for (b, h), u in units.items():
+                u.quantize_if_full()
+                u.insert(kn[b, h], vn[b, h])
+            args = (H.bf16_tensor(kn), H.bf16_tensor(vn), torch.from_numpy(fresh).cuda())
+            if (trial + step) % 2:
+                kitty.kitty_decode_step(layout, gc, *args, H.bf16_tensor(q), out, w.sm_scale, ws, n_splits)
+            else:
+                kitty.kitty_append_token(layout, gc, *args)
+                kitty.kitty_decode_attention(layout, gc, H.bf16_tensor(q), out, w.sm_scale, ws, n_splits)
+            torch.cuda.synchronize()
+            got = out.cpu().numpy()
+            err = float(np.abs(got - H.units_attention(w, units, q, w.sm_scale)).max())
+            assert np.isfinite(got).all(), (step, tag)
+            assert err <= tol, (err, step, str(tag))
