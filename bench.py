@@ -114,13 +114,17 @@ def run_c5(args):
     layers = args.layers or synth.C5_LAYERS
     steps = args.steps or synth.C5_STEPS
     B, hkv, hq = w.batch, w.n_kv_heads, w.n_q_heads
-    layout = kitty.make_layout(hq, hkv, w.n_boost, w.residual_window, w.rank_metric)
+    S, VL = args.sink_tokens, args.v_local        # the paper's full cache organisation (Fig. 1) if given
+    if S or VL or args.v_bits != 2:
+        args.no_cpu_baseline = True               # the live oracle replay below is written for the default layout
+    layout = kitty.make_layout(hq, hkv, w.n_boost, w.residual_window, w.rank_metric, sink_tokens=S, v_local=VL,
+                               v_bits=args.v_bits)
     payload, rec_bytes = kitty.kitty_page_payload_bytes(layout), kitty.kitty_page_bytes(layout)
     lengths = synth.sequence_lengths(w)
     total = args.warmup + steps
-    np0 = [(n + 127) // 128 - 1 for n in lengths]
-    r0 = [n - 128 * p for n, p in zip(lengths, np0)]
-    np_end = [(n + total + 127) // 128 - 1 for n in lengths]
+    np0 = [(n - S + 127) // 128 - 1 for n in lengths]            # the first S tokens sit in the Sink
+    r0 = [n - S - 128 * p for n, p in zip(lengths, np0)]
+    np_end = [(n - S + total + 127) // 128 - 1 for n in lengths]
     max_pages = max(np_end) + 1
     base = np.concatenate([[0], np.cumsum([p + 1 for p in np_end])]).astype(np.int64)   # one spare page per run
     n_pool = int(base[-1])
@@ -144,7 +148,7 @@ def run_c5(args):
     caches = []
     for layer in range(layers):
         c = kitty.Cache(layout, B, max_pages, n_pool, device=dev)
-        offs = torch.tensor([(b % nsrc) * hkv * Ls * 128 + (layer + i) * 128 * 128 for b in range(B) for i in range(np0[b])],
+        offs = torch.tensor([(b % nsrc) * hkv * Ls * 128 + (S + (layer + i) * 128) * 128 for b in range(B) for i in range(np0[b])],
                             dtype=torch.int64, device=dev)
         kitty.kitty_quantize_pages(layout, kt, vt, 128 * 128, Ls * 128, 128, ids, ids.numel(), c.pool, n_pool,
                                    src_page_offsets=offs)
@@ -152,9 +156,18 @@ def run_c5(args):
         c.n_pages.copy_(torch.tensor(np0, dtype=torch.int32))
         c.n_resid.copy_(torch.tensor(r0, dtype=torch.int32))
         for b in range(B):
-            a = (layer + np0[b]) * 128
+            a = S + (layer + np0[b]) * 128
             c.resid_k[b, :, :r0[b]] = kt[b % nsrc, :, a:a + r0[b]]
-            c.resid_v[b, :, :r0[b]] = vt[b % nsrc, :, a:a + r0[b]]
+            if VL:      # the window's half, and the bf16 Value rows of the newest page in the other half
+                c.resid_v[b, :, np0[b] & 1, :r0[b]] = vt[b % nsrc, :, a:a + r0[b]]
+                c.resid_v[b, :, (np0[b] - 1) & 1] = vt[b % nsrc, :, a - 128:a]
+            else:
+                c.resid_v[b, :, :r0[b]] = vt[b % nsrc, :, a:a + r0[b]]
+            if S:
+                c.sink_k[b] = kt[b % nsrc, :, :S]
+                c.sink_v[b] = vt[b % nsrc, :, :S]
+        if S:
+            c.n_sink.fill_(S)
         caches.append(c)
     # dispatch order: longest sequences first (every sequence grows by one token per step, so the order holds)
     if not args.no_seq_order:
@@ -213,7 +226,7 @@ def run_c5(args):
                 st_np[b] += 1
                 st_r[b] = 0
             st_r[b] += 1
-            nbytes += st_np[b] * payload + st_r[b] * 512
+            nbytes += st_np[b] * payload + (st_r[b] + S) * 512 + (128 * 128 * 2 - (4096 + 512) if VL else 0)
         if graphs is not None:
             graphs[i % n_rot].replay()
         else:
@@ -237,7 +250,8 @@ def run_c5(args):
 
     # ---- the streaming kernel alone on the final state, HIP events on the launch stream ------------
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    kbytes = hkv * sum(p * payload + r * 512 for p, r in zip(st_np, st_r)) + 2 * B * hq * 256
+    kbytes = hkv * sum(p * payload + (r + S) * 512 + (128 * 128 * 2 - (4096 + 512) if VL else 0) for p, r in zip(st_np, st_r)) \
+        + 2 * B * hq * 256
     for c in caches[:2]:
         kitty.kitty_decode_split(layout, c, qs[0], w.sm_scale, ws, args.n_splits)
     torch.cuda.synchronize()
@@ -296,7 +310,8 @@ def run_c5(args):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
         "config": {
             "workload": f"c5: {layers} layers, batch {B}, {hq}q/{hkv}kv heads, head_dim 128, lengths uniform in [1024, 32768] "
-                        f"(seeded; mean {np.mean(lengths):.0f}), n_boost {w.n_boost}, step = one token per sequence through "
+                        f"(seeded; mean {np.mean(lengths):.0f}), n_boost {w.n_boost}, {args.v_bits}-bit Values"
+                        f"{f', {S}-token Sink' if S else ''}{', Value Local window' if VL else ''}, step = one token per sequence through "
                         f"all layers ({'append_token + decode_attention' if args.two_calls else 'kitty_decode_step'} per layer, "
                         f"{args.launch} launch)",
             "n_splits": ns, "min_pages_per_split": pps, "record_bytes": rec_bytes, "payload_bytes_per_page": payload,
