@@ -448,3 +448,21 @@ def test_v4_decode_steps_across_a_flush():
             assert err <= TOL_FP32, (fused, step, err)
         check_pool(w, None, oc, gc)
         assert list(oc.n_pages) == [1, 2, 3]
+
+
+def test_long_single_sequence_many_pages_per_wavefront():
+    """One sequence of 2048 pages + 37 window rows (262 181 tokens), one kv-head: with one range every
+    wavefront walks 256 pages (its page-id register is refilled every 64); with the automatic plan the sequence
+    is cut into many ranges and merged."""
+    w = synth.scaled(synth.WORKLOADS["c2"], batch=1, n_q_heads=2, n_kv_heads=1, context=0, seed=4242)
+    n = 2048 * 128 + 37
+    k, v = H.gen_sequences(w, [n])
+    oc = H.oracle_cache(w, [n], k, v, 2048)
+    layout, gc = H.gpu_cache(w, [n], k, v, 2048)
+    check_pool(w, [n], oc, gc)
+    q = synth.query(w)
+    want = oc.decode_attention(q, w.sm_scale)
+    for ns in (1, 0, 7):
+        got = H.gpu_decode(layout, gc, q, w.sm_scale, ns, fp32=True)
+        err = float(np.abs(got - want).max())
+        assert err <= TOL_FP32, (ns, err)
