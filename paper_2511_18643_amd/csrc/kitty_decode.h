@@ -61,6 +61,12 @@ struct DecodeParams {
   int32_t n_pool_pages, rank_metric;
 };
 
+// Packed pages of sequence b as the kernels use it (a count outside [0, max_pages], or pages without a pool,
+// can only come from a corrupted state and is folded into the valid range).
+__device__ __forceinline__ int page_count(const DecodeParams& p, int b) {
+  return p.n_pool_pages > 0 ? max(min(p.n_pages[b], p.max_pages), 0) : 0;
+}
+
 // Page ranges of one sequence: with np pages and r full-precision rows (Sink + window), the sequence uses
 // Sb = min(n_splits, max(1, np / min_pages)) ranges (one if it only has such rows, none if it is empty);
 // range s covers pages [s*np/Sb, (s+1)*np/Sb) and full-precision rows [s*r/Sb, (s+1)*r/Sb).
@@ -607,7 +613,7 @@ __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void
   const int g = p.gqa;
   const size_t pair = (size_t)b * p.n_kv_heads + h;
 
-  int np = min(p.n_pages[b], p.max_pages);
+  int np = page_count(p, b);
   int r = p.has_window ? min(p.n_resid[b] & ((1 << TICKET_SHIFT) - 1), G) : 0;
   int ns = p.sink_cap ? min(p.n_sink[b], p.sink_cap) : 0;
   // fused append: state before the step, what the step does to it
@@ -706,9 +712,12 @@ __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void
       const int i = p0 + w + NW * (first + l);
       return i < p1 ? pt[i] : 0;
     };
+    // (an id outside the pool, which only a corrupted table can hold, is folded onto the pool's last page
+    // rather than followed out of bounds: one scalar instruction per page)
+    const uint32_t last_page = (uint32_t)(p.n_pool_pages - 1);
     int32_t ids = load_ids(0);
     auto rec_at = [&](int k, int idx) {     // record of the wavefront's k-th page, which is page idx of the sequence
-      const int32_t got = __builtin_amdgcn_readlane(ids, k & 63);
+      const int32_t got = (int32_t)min((uint32_t)__builtin_amdgcn_readlane(ids, k & 63), last_page);
       const int32_t id = (FUSED && idx == np_old && fresh_pid >= 0) ? fresh_pid : got;
       return pool_h + (size_t)id * rec_stride;
     };
@@ -990,7 +999,7 @@ __global__ __launch_bounds__(128) void decode_merge_kernel(DecodeParams p) {
       lv[s] = in ? base[s * slot_stride + D + 1] : 0.f;
       av[s] = in ? base[s * slot_stride + d] : 0.f;
     }
-    const int np = min(p.n_pages[b], p.max_pages);
+    const int np = page_count(p, b);
     const int r = (p.has_window ? min(p.n_resid[b], G) : 0) + (p.sink_cap ? min(p.n_sink[b], p.sink_cap) : 0);
     const int sb = active_splits(np, r, p.n_splits, p.min_pages);
     float M = -INFINITY;
@@ -1005,7 +1014,7 @@ __global__ __launch_bounds__(128) void decode_merge_kernel(DecodeParams p) {
       }
     }
   } else {
-    const int np = min(p.n_pages[b], p.max_pages);
+    const int np = page_count(p, b);
     const int r = (p.has_window ? min(p.n_resid[b], G) : 0) + (p.sink_cap ? min(p.n_sink[b], p.sink_cap) : 0);
     const int sb = active_splits(np, r, p.n_splits, p.min_pages);
     float M = -INFINITY;
