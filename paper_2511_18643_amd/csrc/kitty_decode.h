@@ -283,8 +283,9 @@ template <int NB16, int HPL, bool V4 = false>
 struct PageWorker {
   // Eight-head groups: a third byte term needs 24 matrix rows, i.e. a second MFMA pass over the same code
   // operand.  Measured on the 128k-context workload it costs 20 % of the kernel's throughput (the matrix
-  // pipe and the register file become the limiters) for a maximum error of 1e-4 instead of 8e-4, both within
-  // the 2e-3 bound; it is therefore compiled out.
+  // pipe and the register file become the limiters) for a maximum error of 1e-4 instead of 8e-4 there (up to
+  // 1.4e-3 on short sequences whose outlier channels are not boosted), both within the 2e-3 bound; it is
+  // therefore compiled out.
   static constexpr bool THIRD_PASS = false;
   static constexpr int TR = (HPL == 1 || THIRD_PASS) ? 3 : 2;     // byte terms per value
   static constexpr bool WEIGHTED = TR == 3;       // mask-only unpack (relies on the precision of three terms)
@@ -584,12 +585,11 @@ struct PageWorker {
 // HPL = query heads per lane: 1 for GQA groups of 1, 2, 4 (three byte terms), 2 for groups of 8
 // (two byte terms).  Grid: x = page range (see active_splits), y = kv-head, z = sequence.
 // Block = NW wavefronts (4 or 8); wavefront w takes pages p0+w, p0+w+NW, ... of the range and a slice of
-// the range's share of the bf16 window.
+// the range's share of the rows held in full precision (Sink, window).
 // wavefronts per SIMD the kernel is compiled for (register budget 512 / n)
 template <int NB16, int HPL>
 constexpr int decode_waves_per_simd() { return 2; }
 
-//
 // FUSED: the block first performs this (sequence, kv-head)'s share of kitty_append_token (flush a full window
 // into the fresh page, store the new token), then attends over the result; needs one range per (sequence,
 // kv-head), i.e. grid.x == 1 and direct_out.  The new token's row is taken from k_new / v_new directly, a
