@@ -152,14 +152,15 @@ __device__ __forceinline__ v4i unpack16(uint32_t w) {
   r.w = (int)((w >> 6) & 0x03030303u);
   return r;
 }
-// cheaper variant: elements 4..7 come out multiplied by 4 and elements 8..11 by 16 (mask only, no
-// shift); the other operand carries the inverse weights
+// cheaper variant (one shift, four masks): elements 4..7 and 12..15 come out multiplied by 4; the other
+// operand carries the inverse weights
 __device__ __forceinline__ v4i unpack16_w(uint32_t w) {
   v4i r;
+  const uint32_t t = w >> 4;
   r.x = (int)(w & 0x03030303u);
   r.y = (int)(w & 0x0c0c0c0cu);
-  r.z = (int)(w & 0x30303030u);
-  r.w = (int)((w >> 6) & 0x03030303u);
+  r.z = (int)(t & 0x03030303u);
+  r.w = (int)(t & 0x0c0c0c0cu);
   return r;
 }
 // same, each element multiplied by 4 (the weight of the high bits of a 4-bit code)
@@ -226,8 +227,9 @@ __device__ __forceinline__ void f16x8_to_f32(const uint4& v, float (&f)[8]) {
 
 // x = x * a + b written over x.  The compiler otherwise accumulates into the register of b (the two-operand
 // form) and copies the result back for the next loop iteration, one move per running sum and page.  The operands
-// are results of ordinary vector instructions (never of a matrix instruction, whose hazards the assembler does
-// not track through inline code).
+// must be results of ordinary vector instructions: never of a matrix instruction, of a transcendental one
+// (v_exp, v_rcp: a dependent instruction needs a wait state after them) or of a load, because the compiler does
+// not track those hazards and waits through inline code.
 __device__ __forceinline__ void fma_in_place(float& x, float a, float b) {
   asm("v_fma_f32 %0, %0, %1, %2" : "+v"(x) : "v"(a), "v"(b));
 }
@@ -273,11 +275,11 @@ union __attribute__((aligned(16))) DecodeSmem {
 // or positions 8j..8j+7 (V side) of heads gi*HPL + e; in the matrix role it is row/column j of
 // k-block gi.  Both roles put head gi*HPL + e in lane group gi, so no cross-group traffic is needed.
 //
-// With three byte terms the code planes are unpacked with masks only (unpack16_w), which
-// leaves elements 4..7 of a word multiplied by 4 and elements 8..11 by 16.  The compact lane owns
-// elements 8*(j&1)..8*(j&1)+7, i.e. its first four values have weight wA and its last four wB with
-// (wA, wB) = (1, 4) for even j and (16, 1) for odd j; it divides its values by that weight before
-// taking the integer image, and keeps sums and maxima of unweighted values by recombining two halves.
+// With three byte terms the code planes are unpacked with one shift and four masks (unpack16_w), which
+// leaves elements 4..7 and 12..15 of a word multiplied by 4.  The compact lane owns elements
+// 8*(j&1)..8*(j&1)+7, i.e. its first four values have weight 1 and its last four weight 4; it divides its
+// values by that weight before taking the integer image (two bits of the image's precision), and keeps sums
+// and maxima of unweighted values by recombining the two halves.
 // Groups of eight query heads (HPL == 2) carry two terms (16-bit images, plain unpack); see THIRD_PASS.
 template <int NB16, int HPL, bool V4 = false>
 struct PageWorker {
@@ -288,7 +290,11 @@ struct PageWorker {
   // therefore compiled out.
   static constexpr bool THIRD_PASS = false;
   static constexpr int TR = (HPL == 1 || THIRD_PASS) ? 3 : 2;     // byte terms per value
-  static constexpr bool WEIGHTED = TR == 3;       // mask-only unpack (relies on the precision of three terms)
+  // cheap unpack; relies on the precision of three terms (with two-term images it was measured on the Value
+  // side alone: 2.5e-3 instead of 9e-4 maximum error for eight-head groups, and no faster)
+  static constexpr bool WEIGHTED = TR == 3;
+  // weights of the lane's first and last four values (Key side: channels; Value side: tokens) and their log2
+  static constexpr float wA = 1.f, wB = WEIGHTED ? 4.f : 1.f, oA = 0.f, oB = WEIGHTED ? 2.f : 0.f;
   static constexpr bool TWO_PASS = HPL == 2 && THIRD_PASS;
   static_assert(!(V4 && TWO_PASS), "the high Value plane has no second-pass accumulator");
   static constexpr float NLIM = TR == 3 ? 1048000.0f : 32000.0f;   // bound of the integer images
@@ -308,7 +314,6 @@ struct PageWorker {
   const uint8_t* p_ptr;      // A operand of the Value sum
   const uint8_t* b_ptr[4];   // boost rows for tile kb (zeros unless gi == kb)
   LaneOffsets lo;            // byte offsets of the lane into a record
-  float wA, wB, oA, oB;      // weights of the lane's two halves and their log2
   float qv[HPL][8];          // q * sm_scale * log2(e) divided by the weight, compact layout
   float m_run[HPL], l_run[HPL], z_run[HPL];
   float acc[HPL][8];         // channel 16*Td + j, in units of acc_unit (the fixed-point step of the last page's p*s)
@@ -323,11 +328,6 @@ struct PageWorker {
     p_ptr = &ws.pbuf[j][16 * gi];
 #pragma unroll
     for (int kb = 0; kb < 4; ++kb) b_ptr[kb] = (gi == kb) ? &ws.bbuf[j][0] : ws.zero;
-    const bool odd = j & 1;
-    wA = WEIGHTED ? (odd ? 16.f : 1.f) : 1.f;
-    wB = WEIGHTED ? (odd ? 1.f : 4.f) : 1.f;
-    oA = WEIGHTED ? (odd ? 4.f : 0.f) : 0.f;
-    oB = WEIGHTED ? (odd ? 0.f : 2.f) : 0.f;
 #pragma unroll
     for (int e = 0; e < HPL; ++e) {
       m_run[e] = -INFINITY; l_run[e] = 0.f; z_run[e] = 0.f; acc_unit[e] = 1.f;
@@ -398,9 +398,8 @@ struct PageWorker {
 #pragma unroll
       for (int s = 0; s < NB16; ++s) {
         const uint32_t ch = pg.chv[s];
-        // weight the dense plane applies to this channel: 1, 4, 16, 1 for elements 0-3, 4-7, 8-11, 12-15
-        const uint32_t grp = (ch >> 2) & 3u;
-        const uint32_t sh = WEIGHTED ? (grp == 1u ? 2u : (grp == 2u ? 4u : 0u)) : 0u;
+        // weight the dense plane applies to this channel: 1, 4, 1, 4 for elements 0-3, 4-7, 8-11, 12-15
+        const uint32_t sh = WEIGHTED ? ((ch >> 1) & 2u) : 0u;
 #pragma unroll
         for (int e = 0; e < HPL; ++e) {
           const int hd = gi * HPL + e;
@@ -523,8 +522,8 @@ struct PageWorker {
         pmA = fmaxf(pmA, ps[T]); pmB = fmaxf(pmB, ps[T + 4]);
       }
       float psum = fmaf(psA, wA, psB * wB), zsum = fmaf(zsA, wA, zsB * wB), pmax = fmaxf(pmA * wA, pmB * wB);
-      fma_in_place(l_run[e], corr[e], psum);
-      fma_in_place(z_run[e], corr[e], zsum);
+      l_run[e] = fmaf(l_run[e], corr[e], psum);     // (corr comes out of v_exp: not for fma_in_place)
+      z_run[e] = fmaf(z_run[e], corr[e], zsum);
       // (the floor keeps the running sums, which are held in units of pmax / NLIM, far from overflow; a page
       // whose weights are all below it contributes less than 1e-12 of the total)
       pmax = fmaxf(row_max_nonneg(pmax), 1e-12f);

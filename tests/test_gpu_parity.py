@@ -254,10 +254,11 @@ def test_c4_full_size_sampled():
 
 
 # ------------------------------------------------------------------ fused step (append + attention in one call)
-@pytest.mark.parametrize("max_pages,n_splits", [(4, 0), (40, 1), (4, 2)])
+@pytest.mark.parametrize("max_pages,n_splits", [(4, 0), (40, 1), (4, 2), (132, 4)])
 def test_decode_step_matches_append_then_attention(max_pages, n_splits):
     """kitty_decode_step against the oracle's append followed by its attention, across flush boundaries.
-    (4, 0): one launch, 4-wavefront blocks; (40, 1): one launch, 8-wavefront blocks; (4, 2): two-call path."""
+    (4, 0): one launch, 4-wavefront blocks; (40, 1): one launch, 8-wavefront blocks; (4, 2) and (132, 4): several
+    ranges per (sequence, kv-head), i.e. the two-call path, with 4- and 8-wavefront blocks."""
     import torch
     from paper_2511_18643_amd import kitty
     w = synth.scaled(synth.WORKLOADS["c2"], batch=4, n_q_heads=8, n_kv_heads=2, context=0)
@@ -266,7 +267,7 @@ def test_decode_step_matches_append_then_attention(max_pages, n_splits):
     oc = H.oracle_cache(w, start, k0, v0, max_pages)
     layout, gc = H.gpu_cache(w, start, k0, v0, max_pages)
     ns, _ = kitty.kitty_decode_plan(layout, 4, max_pages, n_splits)
-    assert ns == (2 if n_splits == 2 else 1)
+    assert ns == (n_splits if n_splits > 1 else 1)
     ws = kitty.new_workspace(layout, 4, max_pages, n_splits)
     out = torch.empty((4, 8, 128), dtype=torch.float32, device="cuda")
     for step in range(1, 140):
