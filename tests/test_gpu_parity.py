@@ -292,6 +292,54 @@ def test_decode_step_matches_append_then_attention(max_pages, n_splits):
             assert np.abs(got - want).max() <= TOL_FP32, step
 
 
+@pytest.mark.parametrize("max_pages,n_splits", [(4, 0), (4, 2)])
+def test_decode_step_replayed_from_a_graph_matches_eager(max_pages, n_splits):
+    """kitty_decode_step captured once into a HIP graph and replayed step after step (the sequence state lives on
+    the device, so one graph serves every step, flushes included), with eager copies and an eager twin of the
+    same step between the replays: every replay is compared with the eager result (bit-equal: same kernels, same
+    summation order), with the state of the eager cache, and with the oracle.  The library only launches kernels
+    on the given stream (no memsets, allocations or synchronisation), which is what makes it capturable."""
+    import torch
+    from paper_2511_18643_amd import kitty
+    w = synth.scaled(synth.WORKLOADS["c2"], batch=3, n_q_heads=8, n_kv_heads=2, context=0)
+    start = [100, 125, 128 + 126]      # the three sequences flush at different replays
+    k0, v0 = H.gen_sequences(w, start)
+    oc = H.oracle_cache(w, start, k0, v0, max_pages)
+    layout, gc_e = H.gpu_cache(w, start, k0, v0, max_pages)
+    _, gc_g = H.gpu_cache(w, start, k0, v0, max_pages)
+    ws_e, ws_g = kitty.new_workspace(layout, 3, max_pages, n_splits), kitty.new_workspace(layout, 3, max_pages, n_splits)
+    kn_t = torch.zeros((3, 2, 128), dtype=torch.bfloat16, device="cuda")
+    vn_t, q_t = torch.zeros_like(kn_t), torch.zeros((3, 8, 128), dtype=torch.bfloat16, device="cuda")
+    fresh_t = torch.zeros(3, dtype=torch.int32, device="cuda")
+    out_g = torch.zeros((3, 8, 128), dtype=torch.float32, device="cuda")
+    out_e = torch.zeros_like(out_g)
+    # the kernels are loaded by an eager call on a throw-away cache before the capture
+    _, gc_w = H.gpu_cache(w, start, k0, v0, max_pages)
+    kitty.kitty_decode_step(layout, gc_w, kn_t, vn_t, fresh_t, q_t, out_e, w.sm_scale, kitty.new_workspace(layout, 3, max_pages, n_splits), n_splits)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        kitty.kitty_decode_step(layout, gc_g, kn_t, vn_t, fresh_t, q_t, out_g, w.sm_scale, ws_g, n_splits)
+    torch.cuda.synchronize()
+    for step in range(1, 34):
+        kn, vn = synth.new_token(w, step)
+        q = synth.query(w, step)
+        fresh = np.array([b * max_pages + int(oc.n_pages[b]) for b in range(3)], np.int32)
+        oc.append_token(kn, vn, fresh)
+        kn_t.copy_(H.bf16_tensor(kn)); vn_t.copy_(H.bf16_tensor(vn)); q_t.copy_(H.bf16_tensor(q))
+        fresh_t.copy_(torch.from_numpy(fresh).cuda())
+        graph.replay()
+        kitty.kitty_decode_step(layout, gc_e, kn_t, vn_t, fresh_t, q_t, out_e, w.sm_scale, ws_e, n_splits)
+        torch.cuda.synchronize()
+        assert torch.equal(out_g, out_e), step
+        for name in ("n_pages", "n_resid", "page_table"):
+            assert torch.equal(getattr(gc_g, name), getattr(gc_e, name)), (step, name)
+        assert np.array_equal(gc_g.n_pages.cpu().numpy(), oc.n_pages) and np.array_equal(gc_g.n_resid.cpu().numpy(), oc.n_resid), step
+        assert np.abs(out_g.cpu().numpy() - oc.decode_attention(q, w.sm_scale)).max() <= TOL_FP32, step
+    assert torch.equal(gc_g.pool, gc_e.pool)
+    assert list(oc.n_pages) == [1, 1, 2]
+
+
 def test_variable_length_decode_loop_c5_shape():
     """Config-5-shaped loop at reduced scale: variable-length batch (seeded uniform lengths), prefill through
     kitty_quantize_pages, then decode steps (append with flushes at different steps per sequence + attention),
