@@ -191,17 +191,32 @@ constexpr uint32_t T2_ADD = 0x8080u - 0x400000u;  // byte 2 of (bits + 0x8080 - 
 
 template <int TR>
 __device__ __forceinline__ void split_terms(const uint32_t (&u)[8], uint2 (&w)[TR]) {
-  uint32_t t1[8], t2[8];
+  if constexpr (TR == 2) {
+    // 16-bit images: the low halves of two values share a register, the carry into the high byte is one packed
+    // 16-bit add for both, and each term word is gathered from two such registers
+    typedef unsigned short us2 __attribute__((ext_vector_type(2)));
+    uint32_t lo[4], up[4];
 #pragma unroll
-  for (int k = 0; k < 8; ++k) {
-    t1[k] = u[k] + T1_ADD;
-    t2[k] = u[k] + T2_ADD;
-  }
-  w[0].x = gather_byte<0>(u[0], u[1], u[2], u[3]);
-  w[0].y = gather_byte<0>(u[4], u[5], u[6], u[7]);
-  w[1].x = gather_byte<1>(t1[0], t1[1], t1[2], t1[3]);
-  w[1].y = gather_byte<1>(t1[4], t1[5], t1[6], t1[7]);
-  if constexpr (TR == 3) {
+    for (int i = 0; i < 4; ++i) {
+      lo[i] = __builtin_amdgcn_perm(u[2 * i + 1], u[2 * i], 0x05040100u);
+      const us2 c = __builtin_bit_cast(us2, lo[i]) + (us2){0x80, 0x80};
+      up[i] = __builtin_bit_cast(uint32_t, c);
+    }
+    w[0].x = __builtin_amdgcn_perm(lo[1], lo[0], 0x06040200u);
+    w[0].y = __builtin_amdgcn_perm(lo[3], lo[2], 0x06040200u);
+    w[1].x = __builtin_amdgcn_perm(up[1], up[0], 0x07050301u);
+    w[1].y = __builtin_amdgcn_perm(up[3], up[2], 0x07050301u);
+  } else {
+    uint32_t t1[8], t2[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      t1[k] = u[k] + T1_ADD;
+      t2[k] = u[k] + T2_ADD;
+    }
+    w[0].x = gather_byte<0>(u[0], u[1], u[2], u[3]);
+    w[0].y = gather_byte<0>(u[4], u[5], u[6], u[7]);
+    w[1].x = gather_byte<1>(t1[0], t1[1], t1[2], t1[3]);
+    w[1].y = gather_byte<1>(t1[4], t1[5], t1[6], t1[7]);
     w[2].x = gather_byte<2>(t2[0], t2[1], t2[2], t2[3]);
     w[2].y = gather_byte<2>(t2[4], t2[5], t2[6], t2[7]);
   }
