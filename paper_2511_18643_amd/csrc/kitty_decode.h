@@ -638,7 +638,7 @@ __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void
   bool ok = true, flush = false;
   const uint16_t* knew_h = nullptr;
   const uint16_t* vnew_h = nullptr;
-  // the new token's copy into the cache (threads 0..31 hold 16 bytes each): fetched here, stored at the end of
+  // the new token's copy into the cache (threads 0..31 hold 16 bytes each): fetched early, stored at the end of
   // the kernel, so that nobody waits for the round trip; attention reads the token from k_new / v_new itself
   uint4 keep_val = make_uint4(0, 0, 0, 0);
   uint16_t* keep_dst = nullptr;
@@ -649,7 +649,6 @@ __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void
     if (ns_old < p.sink_cap) {    // the Sink is not full: the token goes there and nothing else changes
       if (tid < 32) {
         const int part = tid & 15;
-        keep_val = *reinterpret_cast<const uint4*>((tid < 16 ? knew_h : vnew_h) + part * 8);
         keep_dst = (tid < 16 ? p.sink_k_w : p.sink_v_w) + (pair * p.sink_cap + ns_old) * D + part * 8;
       }
       newsink = ns_old;
@@ -676,7 +675,6 @@ __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void
         if (tid < 32) {             // keep the token for the following steps
           const int part = tid & 15;
           uint16_t* wvw = p.resid_v_w + resid_v_offset(b, h, p.n_kv_heads, p.v_local, np);
-          keep_val = *reinterpret_cast<const uint4*>((tid < 16 ? knew_h : vnew_h) + part * 8);
           keep_dst = (tid < 16 ? wkw : wvw) + (size_t)newrow * D + part * 8;
         }
       }
@@ -689,6 +687,8 @@ __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void
   if constexpr (FUSED) {
     __syncthreads();            // all wavefronts of this block have read the state (they branched on it above)
     if (tid == 0) ticket = atomicAdd(&p.n_resid_w[b], 1 << TICKET_SHIFT);
+    // (fetched behind the barrier, which waits for every outstanding load of the wavefront)
+    if (keep_dst) keep_val = *reinterpret_cast<const uint4*>((tid < 16 ? knew_h : vnew_h) + (tid & 15) * 8);
   }
   const int nfp = ns + r;       // rows read in full precision for both Keys and Values: Sink, then window
   const int sb = active_splits(np, nfp, p.n_splits, p.min_pages);
