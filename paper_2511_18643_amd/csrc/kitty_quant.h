@@ -86,9 +86,28 @@ __device__ __forceinline__ void fetch_tile(TileRegs& r, const uint16_t* __restri
   }
 }
 
+// Stores of the code planes.  STREAM marks them non-temporal: a prefill-sized batch of records is not read again
+// soon, and written that way the same traffic is served ~5 % faster (measured on the bare load/store pattern and
+// on the kernel); a flush inside a decode step reads its record back at once and keeps ordinary stores.
+template <bool STREAM>
+__device__ __forceinline__ void plane_store16(uint8_t* dst, const uint4& v) {
+  if constexpr (STREAM) {
+    typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+    const v4u x = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(x, reinterpret_cast<v4u*>(dst));
+  } else {
+    *reinterpret_cast<uint4*>(dst) = v;
+  }
+}
+template <bool STREAM>
+__device__ __forceinline__ void plane_store4(uint8_t* dst, uint32_t v) {
+  if constexpr (STREAM) __builtin_nontemporal_store(v, reinterpret_cast<uint32_t*>(dst));
+  else *reinterpret_cast<uint32_t*>(dst) = v;
+}
+
 // One block of at least 256 threads; threads 0..255 do the work, every thread takes part in the barriers.
 // Both source pages are read into registers before the first barrier and never touched again.
-template <int NB16, bool V4 = false>
+template <int NB16, bool V4 = false, bool STREAM = false>
 __device__ __forceinline__ void quantize_page(QuantSmem& s, const uint16_t* __restrict__ ksrc, const uint16_t* __restrict__ vsrc,
                                               int64_t token_stride, uint8_t* __restrict__ rec, int rank_metric) {
   using R = Rec<NB16, V4>;
@@ -255,7 +274,7 @@ __device__ __forceinline__ void quantize_page(QuantSmem& s, const uint16_t* __re
   }
   __syncthreads();   // Key words and codes staged, per-token metadata in place
   if (act) {
-    *reinterpret_cast<uint4*>(rec + R::kd + 16 * tid) = *reinterpret_cast<const uint4*>(&s.pk.kout[4 * tid]);
+    plane_store16<STREAM>(rec + R::kd + 16 * tid, *reinterpret_cast<const uint4*>(&s.pk.kout[4 * tid]));
     if constexpr (NB16 > 0) {   // boost plane: high two bits of the boosted channels, slot order
       for (int idx = tid; idx < 128 * NB16; idx += 256) {
         const int sblk = idx >> 7, u = (idx >> 6) & 1, lane = idx & 63;
@@ -266,7 +285,7 @@ __device__ __forceinline__ void quantize_page(QuantSmem& s, const uint16_t* __re
           const uint32_t code = s.pk.codes[t][s.chl[16 * sblk + a]];
           word |= (code >> 2) << (8 * (a & 3) + 2 * (a >> 2));
         }
-        *reinterpret_cast<uint32_t*>(rec + R::kb + 512 * sblk + 8 * lane + 4 * u) = word;
+        plane_store4<STREAM>(rec + R::kb + 512 * sblk + 8 * lane + 4 * u, word);
       }
     }
     // ---------------- Value codes: half a word per channel and thread ----------------
@@ -316,8 +335,8 @@ __device__ __forceinline__ void quantize_page(QuantSmem& s, const uint16_t* __re
   }
   __syncthreads();
   if (act) {
-    *reinterpret_cast<uint4*>(rec + R::vd + 16 * tid) = *reinterpret_cast<const uint4*>(&s.pk.vout[4 * tid]);
-    if constexpr (V4) *reinterpret_cast<uint4*>(rec + R::vh + 16 * tid) = *reinterpret_cast<const uint4*>(&s.pk.vout_hi[4 * tid]);
+    plane_store16<STREAM>(rec + R::vd + 16 * tid, *reinterpret_cast<const uint4*>(&s.pk.vout[4 * tid]));
+    if constexpr (V4) plane_store16<STREAM>(rec + R::vh + 16 * tid, *reinterpret_cast<const uint4*>(&s.pk.vout_hi[4 * tid]));
   }
   __syncthreads();   // the shared memory may be reused by the caller after this
 }
@@ -340,7 +359,7 @@ __global__ __launch_bounds__(256, 4) void quantize_pages_kernel(QuantPagesParams
   if (pid < 0 || pid >= p.n_pool_pages) return;
   const int64_t off = (p.src_page_offsets ? p.src_page_offsets[i] : (int64_t)i * p.page_stride) + (int64_t)h * p.head_stride;
   uint8_t* rec = p.pool + ((size_t)pid * p.n_kv_heads + h) * (size_t)Rec<NB16, V4>::bytes;
-  quantize_page<NB16, V4>(smem, p.k_src + off, p.v_src + off, p.token_stride, rec, p.rank_metric);
+  quantize_page<NB16, V4, true>(smem, p.k_src + off, p.v_src + off, p.token_stride, rec, p.rank_metric);
 }
 
 struct AppendParams {
