@@ -778,14 +778,10 @@ __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void
         ++turn;
         ++k;
         // Where the reloaded ids are first used decides where the compiler waits for them.  Used in this rare
-        // branch (eight-head groups), the wait sits here; otherwise the loop head has to assume the load may be
-        // pending and drains the whole load queue, the current page's Value plane included, before every page.
-        // Measured: the drain costs the instruction-bound eight-head kernel 2 % and gains the bandwidth-bound
-        // four-head kernel 1 % (it paces the requests).
-        if ((k & 63) == 0) {
-          ids = load_ids(k);
-          if constexpr (HPL == 2) ids = max(ids, 0);
-        }
+        // branch, the wait sits here; otherwise the loop head has to assume the load may be pending and drains
+        // the whole load queue, the current page's Value plane included, before every page (+5 % on the 32k
+        // workload).
+        if ((k & 63) == 0) ids = max(load_ids(k), 0);
         pw.process(pg, rec_ref<NB16, V4>(has_nx ? rec_at(k, idx + NW) : pool_h), has_nx);
       }
       __builtin_amdgcn_s_setprio(0);
