@@ -77,12 +77,21 @@ __device__ __forceinline__ int plane_word(int r, int cw) {
 }
 
 // src: bf16 rows of 128 channels, row t at src + t*token_stride (elements), 16-byte aligned.
+// STREAM: the source is read once (batch quantization): non-temporal loads.
 struct TileRegs { uint4 v[8]; };
+template <bool STREAM>
 __device__ __forceinline__ void fetch_tile(TileRegs& r, const uint16_t* __restrict__ src, int64_t token_stride, int tid) {
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const int t = (tid >> 4) + 16 * i, part = tid & 15;
-    r.v[i] = *reinterpret_cast<const uint4*>(src + (int64_t)t * token_stride + part * 8);
+    const uint16_t* at = src + (int64_t)t * token_stride + part * 8;
+    if constexpr (STREAM) {
+      typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+      const v4u x = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(at));
+      r.v[i] = make_uint4(x.x, x.y, x.z, x.w);
+    } else {
+      r.v[i] = *reinterpret_cast<const uint4*>(at);
+    }
   }
 }
 
@@ -118,8 +127,8 @@ __device__ __forceinline__ void quantize_page(QuantSmem& s, const uint16_t* __re
   const int part = tid & 15, cls = (tid >> 4) & 15;   // cls = 4*wave + g: tokens cls + 16*i, positions 8*cls + i
   TileRegs kq, vq;
   if (act) {
-    fetch_tile(kq, ksrc, token_stride, tid);
-    fetch_tile(vq, vsrc, token_stride, tid);
+    fetch_tile<STREAM>(kq, ksrc, token_stride, tid);
+    fetch_tile<STREAM>(vq, vsrc, token_stride, tid);
   }
 
   // ---------------- Key page: per-channel min, max, sum |x| ----------------
