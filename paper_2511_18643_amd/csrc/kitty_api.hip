@@ -60,8 +60,13 @@ int num_compute_units() {
   return cus;
 }
 
-// Blocks of 8 wavefronts when a range can feed them (>= 4 pages per wavefront), else 4.
-int waves_per_block(int32_t max_pages, int32_t n_splits) { return max_pages / (n_splits > 0 ? n_splits : 1) >= 32 ? 8 : 4; }
+// Blocks of 8 wavefronts when a range can feed them (>= 4 pages per wavefront), else 4.  A grid with several
+// times more blocks than compute units (a large or variable-length batch) also takes 4: two such blocks share a
+// compute unit, so one block's start-up and tail run under the other's streaming (+2 % on the 36-layer loop).
+int waves_per_block(int32_t max_pages, int32_t n_splits, int64_t blocks) {
+  if (blocks >= 4 * (int64_t)num_compute_units()) return 4;
+  return max_pages / (n_splits > 0 ? n_splits : 1) >= 32 ? 8 : 4;
+}
 
 // n_splits page ranges per (sequence, kv-head); a range never covers fewer than min_pages pages
 // unless the sequence has fewer (see active_splits in the kernels).
@@ -309,7 +314,7 @@ int launch_split(const kitty_layout* L, const kitty_cache* C, const void* q, flo
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   const dim3 grid(P.n_splits, L->n_kv_heads, C->batch);
   const bool wide = P.gqa == 8;
-  const bool big = waves_per_block(C->max_pages, P.n_splits) == 8;
+  const bool big = waves_per_block(C->max_pages, P.n_splits, (int64_t)P.n_splits * L->n_kv_heads * C->batch) == 8;
   const bool fused = step != nullptr;
   return dispatch_variant(L, [&](auto nb, auto v4) {
     constexpr int NB = decltype(nb)::value;

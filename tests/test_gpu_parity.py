@@ -189,7 +189,8 @@ def _full_size_case(name, n_src_seqs, sample_pairs, tol32):
     against the oracle, which rebuilds the sampled sequences from the inputs."""
     import torch
     from paper_2511_18643_amd import kitty
-    w = synth.WORKLOADS[name]
+    w = synth.WORKLOADS[name] if isinstance(name, str) else name
+    name = w.name
     B, hkv, g = w.batch, w.n_kv_heads, w.gqa
     n_pages, r = w.pages_and_resid()
     L = n_pages * 128 + r
@@ -251,6 +252,14 @@ def test_c3_full_size_sampled():
 
 def test_c4_full_size_sampled():
     _full_size_case("c4", 1, [(0, 0), (7, 5)], 1e-3)
+
+
+def test_wide_batch_long_ranges_in_four_wavefront_blocks_sampled():
+    """A batch with four times more (sequence, kv-head) pairs than the GPU has compute units: the plan then takes
+    4-wavefront blocks for long ranges too (as in the variable-length 36-layer loop), here with 300 pages per
+    sequence, i.e. 75 per wavefront, so that the page ids are reloaded inside the loop."""
+    w = synth.scaled(synth.WORKLOADS["c3"], batch=128, context=300 * 128 + 77)
+    _full_size_case(w, 2, [(0, 0), (77, 3), (127, 7)], TOL_FP32)
 
 
 # ------------------------------------------------------------------ fused step (append + attention in one call)
