@@ -255,8 +255,8 @@ def test_c4_full_size_sampled():
 
 
 def test_wide_batch_long_ranges_in_four_wavefront_blocks_sampled():
-    """A batch with four times more (sequence, kv-head) pairs than the GPU has compute units: the plan then takes
-    4-wavefront blocks for long ranges too (as in the variable-length 36-layer loop), here with 300 pages per
+    """A batch with more (sequence, kv-head) pairs than the GPU has compute units (four times here): the plan then
+    takes 4-wavefront blocks for long ranges too (as in the variable-length 36-layer loop), here with 300 pages per
     sequence, i.e. 75 per wavefront, so that the page ids are reloaded inside the loop."""
     w = synth.scaled(synth.WORKLOADS["c3"], batch=128, context=300 * 128 + 77)
     _full_size_case(w, 2, [(0, 0), (77, 3), (127, 7)], TOL_FP32)
