@@ -722,125 +722,93 @@ __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void
   const size_t qrow = ((size_t)b * p.n_q_heads + (size_t)h * g);
   PageWorker<NB16, HPL, V4> pw(ws, l);
 
-  if (p0 < p1) {
-    const int32_t* pt = p.page_table + (size_t)b * p.max_pages;
-    const size_t rec_stride = (size_t)p.n_kv_heads * R::bytes;
-    const uint8_t* pool_h = p.pool + (size_t)h * R::bytes;
-    // Page ids of this wavefront's pages: lane k of `ids` holds the id of its k-th page (64 at a time), so the
-    // loop takes them from a register with v_readlane instead of waiting for a scalar load per page.
-    auto load_ids = [&](int first) {
-      const int i = p0 + w + NW * (first + l);
-      return i < p1 ? pt[i] : 0;
-    };
-    // (an id outside the pool, which only a corrupted table can hold, is folded onto the pool's last page
-    // rather than followed out of bounds: one scalar instruction per page)
-    const uint32_t last_page = (uint32_t)(p.n_pool_pages - 1);
-    int32_t ids = load_ids(0);
-    auto rec_at = [&](int k, int idx) {     // record of the wavefront's k-th page, which is page idx of the sequence
-      const int32_t got = (int32_t)min((uint32_t)__builtin_amdgcn_readlane(ids, k & 63), last_page);
-      const int32_t id = (FUSED && idx == np_old && fresh_pid >= 0) ? fresh_pid : got;
-      return pool_h + (size_t)id * rec_stride;
-    };
-    // one register buffer: each piece of the next page is requested when the current page no longer needs it.
-    PageRegs<NB16, V4> pg{};
-    int idx = p0 + w;
-    uint4 m0 = make_uint4(0, 0, 0, 0);
-    // ---- zero the operand matrices once (rows of absent heads and the unused term row stay zero)
-    {
-      uint32_t* z32 = reinterpret_cast<uint32_t*>(&ws.abuf[0][0]);
-      using WSc = WaveScratch<NB16, HPL>;
-      constexpr int nwords = (int)(offsetof(WSc, pw) - offsetof(WSc, abuf)) / 4;   // abuf, bbuf, pbuf are contiguous
-      for (int i = l; i < nwords; i += 64) z32[i] = 0u;
-      if (l < 4) reinterpret_cast<uint32_t*>(ws.zero)[l] = 0u;
-    }
-#pragma unroll
-    for (int e = 0; e < HPL; ++e) {
-      const int hd = gi * HPL + e;
-      const bool live = hd < g;
-      const uint4 raw = live ? *reinterpret_cast<const uint4*>(p.q + (qrow + hd) * D + 8 * j) : make_uint4(0, 0, 0, 0);
-      pw.set_q(e, raw, p.qk_scale_log2, live);
-    }
-    if (idx < p1) {
-      const RecRef rec = rec_ref<NB16, V4>(rec_at(0, idx));
-      m0 = load_meta<NB16>(rec, pw.lo);
-      load_k<NB16, V4>(pg, rec, pw.lo);
-      load_v<NB16, V4>(pg, rec, pw.lo);
-      pw.stage_meta(m0);
-      wave_lds_fence();
-      // The two wavefronts that share a SIMD take the higher issue priority in turn, page by page: with equal
-      // priorities the older one wins every conflict and ends its (equal) share of the pages ~6 % earlier,
-      // leaving the block to wait for the younger one.
-      int turn = w / 4;
-      int k = 0;
-      for (; idx < p1q; idx += NW) {
-        const bool has_nx = idx + NW < p1;
-        if (turn & 1) __builtin_amdgcn_s_setprio(1); else __builtin_amdgcn_s_setprio(0);
-        ++turn;
-        ++k;
-        // Where the reloaded ids are first used decides where the compiler waits for them.  Used in this rare
-        // branch, the wait sits here; otherwise the loop head has to assume the load may be pending and drains
-        // the whole load queue, the current page's Value plane included, before every page (+5 % on the 32k
-        // workload).
-        if ((k & 63) == 0) ids = max(load_ids(k), 0);
-        pw.process(pg, rec_ref<NB16, V4>(has_nx ? rec_at(k, idx + NW) : pool_h), has_nx);
-      }
-      __builtin_amdgcn_s_setprio(0);
-      if (lag_here && idx == p1q) pw.logits_to(pg, lagx);   // this wavefront holds the newest page
-    }
-  }
-  if (lag_here) __syncthreads();   // lagx is complete (the condition is the same for the whole block)
-
   // ================= rows read in full precision, spread over the ranges and wavefronts =================
   // Range `slot` of `sb` takes rows [slot*nfp/sb, (slot+1)*nfp/sb) of the list (Sink rows, then window rows); the
   // last range also takes the G Value rows of the newest page when the Local window is on (their logits are in
   // lagx).  The block's list is cut into NW near-equal runs, one per wavefront, walked in chunks of 32 rows
-  // with an online softmax.
-  float accw[NH][8];        // channels 8j..8j+7 of every head (after the cross-group sum)
+  // with an online softmax.  In 4-wavefront blocks (short ranges, or grids with several blocks per compute unit)
+  // a wavefront that has pages does its Sink and window rows while its first page is on its way and carries the
+  // sums of its own heads through the page loop (+3 % on the variable-length 36-layer loop; in 8-wavefront blocks
+  // the same costs 2.5 % on the 32k workload); the newest page's rows always follow the pages.
+  float accw[NH][8];        // channels 8j..8j+7 of every head (summed over the lane groups by fp_reduce_own)
   float mw[HPL], lw[HPL];
+  auto fp_reset = [&]() {
 #pragma unroll
-  for (int hh = 0; hh < NH; ++hh)
+    for (int hh = 0; hh < NH; ++hh)
 #pragma unroll
-    for (int k = 0; k < 8; ++k) accw[hh][k] = 0.f;
+      for (int k = 0; k < 8; ++k) accw[hh][k] = 0.f;
 #pragma unroll
-  for (int e = 0; e < HPL; ++e) { mw[e] = -INFINITY; lw[e] = 0.f; }
+    for (int e = 0; e < HPL; ++e) { mw[e] = -INFINITY; lw[e] = 0.f; }
+  };
+  // sum over the four lane groups (rows 4i + gi: two butterfly steps); every group then holds the full sums and
+  // keeps those of its own heads
+  auto fp_reduce_own = [&](float (&dst)[HPL][8]) {
+#pragma unroll
+    for (int hh = 0; hh < NH; ++hh)
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        float v = accw[hh][k];
+        v += __shfl_xor(v, 16);
+        v += __shfl_xor(v, 32);
+        accw[hh][k] = v;
+      }
+#pragma unroll
+    for (int e = 0; e < HPL; ++e) {
+      const int hd = gi * HPL + e;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        float v = 0.f;
+#pragma unroll
+        for (int hh = 0; hh < NH; ++hh) v = (hh == hd) ? accw[hh][k] : v;
+        dst[e][k] = v;
+      }
+    }
+  };
+  constexpr bool FP_FIRST = NW == 4 && !(HPL == 2 && NB16 >= 4);   // (not where the registers are all taken)
   const int wr0 = (int)((long long)slot * nfp / sb), wr1 = (int)((long long)(slot + 1) * nfp / sb);
   const int nkv = wr1 - wr0;                       // rows of this block with bf16 Keys and Values
-  const int nrows = nkv + (lag_here ? G : 0);
-  const int per = (nrows + NW - 1) / NW;
-  const int t0 = w * per, t1 = min(t0 + per, nrows);
-  if (t0 < t1) {
-    const uint16_t* wk = p.resid_k + pair * (size_t)(G * D);
-    const uint16_t* wv = p.resid_v + resid_v_offset(b, h, p.n_kv_heads, p.v_local, np);
-    const uint16_t* lagv = p.resid_v + resid_v_offset(b, h, p.n_kv_heads, p.v_local, np - 1);
-    const uint16_t* sk = p.sink_k + pair * (size_t)p.sink_cap * D;
-    const uint16_t* sv = p.sink_v + pair * (size_t)p.sink_cap * D;
-    const uint16_t* qdummy = p.q + qrow * D;       // any readable row: Key operand of rows whose logits come from lagx
-    // row i of the block's list -> its Key row, Value row, and index into lagx (or -1)
-    auto row_ptrs = [&](int i, const uint16_t*& kp, const uint16_t*& vp, int& li) {
-      if (i < nkv) {
-        const int f = wr0 + i;
-        li = -1;
-        if (f < ns) {
-          const bool fresh = FUSED && f == newsink;
-          kp = fresh ? knew_h : sk + (size_t)f * D;
-          vp = fresh ? vnew_h : sv + (size_t)f * D;
-        } else {
-          const int t = f - ns;
-          const bool fresh = FUSED && t == newrow;
-          kp = fresh ? knew_h : wk + (size_t)t * D;
-          vp = fresh ? vnew_h : wv + (size_t)t * D;
-        }
+  const int nlag = lag_here ? G : 0;               // rows of the newest page (list indices nkv ..)
+  // runs of this wavefront: of the whole list, or (rows first) of its two parts
+  const int per = (nkv + nlag + NW - 1) / NW;
+  const int t0 = w * per, t1 = min(t0 + per, nkv + nlag);
+  const int perk = (nkv + NW - 1) / NW, perl = (nlag + NW - 1) / NW;
+  const int kv0 = w * perk, kv1 = min(kv0 + perk, nkv);
+  const int lg0 = nkv + min(w * perl, nlag), lg1 = nkv + min((w + 1) * perl, nlag);
+  float kvacc[HPL][8], kvm[HPL], kvl[HPL];         // rows first: what is carried through the page loop
+  bool kv_done = false;
+  const uint16_t* wk = p.resid_k + pair * (size_t)(G * D);
+  const uint16_t* wv = p.resid_v + resid_v_offset(b, h, p.n_kv_heads, p.v_local, np);
+  const uint16_t* lagv = p.resid_v + resid_v_offset(b, h, p.n_kv_heads, p.v_local, np - 1);
+  const uint16_t* sk = p.sink_k + pair * (size_t)p.sink_cap * D;
+  const uint16_t* sv = p.sink_v + pair * (size_t)p.sink_cap * D;
+  const uint16_t* qdummy = p.q + qrow * D;       // any readable row: Key operand of rows whose logits come from lagx
+  // row i of the block's list -> its Key row, Value row, and index into lagx (or -1)
+  auto row_ptrs = [&](int i, const uint16_t*& kp, const uint16_t*& vp, int& li) {
+    if (i < nkv) {
+      const int f = wr0 + i;
+      li = -1;
+      if (f < ns) {
+        const bool fresh = FUSED && f == newsink;
+        kp = fresh ? knew_h : sk + (size_t)f * D;
+        vp = fresh ? vnew_h : sv + (size_t)f * D;
       } else {
-        li = i - nkv;
-        kp = qdummy;
-        vp = lagv + (size_t)li * D;
+        const int t = f - ns;
+        const bool fresh = FUSED && t == newrow;
+        kp = fresh ? knew_h : wk + (size_t)t * D;
+        vp = fresh ? vnew_h : wv + (size_t)t * D;
       }
-    };
+    } else {
+      li = i - nkv;
+      kp = qdummy;
+      vp = lagv + (size_t)li * D;
+    }
+  };
+  auto fp_rows = [&](int t0, int t1) {
     // A operand: query rows; row hd*RPH carries head hd, the other rows are zero
     const int arow_head = j / RPH;
     const bool arow_live = (j % RPH) == 0 && arow_head < g;
     v8bf aq[4];
-#pragma unroll
+  #pragma unroll
     for (int mm = 0; mm < 4; ++mm) {
       uint4 raw = make_uint4(0, 0, 0, 0);
       if (arow_live) raw = *reinterpret_cast<const uint4*>(p.q + (qrow + arow_head) * D + 32 * mm + 8 * gi);
@@ -923,16 +891,108 @@ __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void
       }
       wave_lds_fence();   // the next chunk overwrites pw
     }
-    // sum over the four lane groups (rows 4i + gi): two butterfly steps across groups
+  };
+
+  if (p0 < p1) {
+    const int32_t* pt = p.page_table + (size_t)b * p.max_pages;
+    const size_t rec_stride = (size_t)p.n_kv_heads * R::bytes;
+    const uint8_t* pool_h = p.pool + (size_t)h * R::bytes;
+    // Page ids of this wavefront's pages: lane k of `ids` holds the id of its k-th page (64 at a time), so the
+    // loop takes them from a register with v_readlane instead of waiting for a scalar load per page.
+    auto load_ids = [&](int first) {
+      const int i = p0 + w + NW * (first + l);
+      return i < p1 ? pt[i] : 0;
+    };
+    // (an id outside the pool, which only a corrupted table can hold, is folded onto the pool's last page
+    // rather than followed out of bounds: one scalar instruction per page)
+    const uint32_t last_page = (uint32_t)(p.n_pool_pages - 1);
+    int32_t ids = load_ids(0);
+    auto rec_at = [&](int k, int idx) {     // record of the wavefront's k-th page, which is page idx of the sequence
+      const int32_t got = (int32_t)min((uint32_t)__builtin_amdgcn_readlane(ids, k & 63), last_page);
+      const int32_t id = (FUSED && idx == np_old && fresh_pid >= 0) ? fresh_pid : got;
+      return pool_h + (size_t)id * rec_stride;
+    };
+    // one register buffer: each piece of the next page is requested when the current page no longer needs it.
+    PageRegs<NB16, V4> pg{};
+    int idx = p0 + w;
+    uint4 m0 = make_uint4(0, 0, 0, 0);
+    // ---- zero the operand matrices once (rows of absent heads and the unused term row stay zero)
+    {
+      uint32_t* z32 = reinterpret_cast<uint32_t*>(&ws.abuf[0][0]);
+      using WSc = WaveScratch<NB16, HPL>;
+      constexpr int nwords = (int)(offsetof(WSc, pw) - offsetof(WSc, abuf)) / 4;   // abuf, bbuf, pbuf are contiguous
+      for (int i = l; i < nwords; i += 64) z32[i] = 0u;
+      if (l < 4) reinterpret_cast<uint32_t*>(ws.zero)[l] = 0u;
+    }
 #pragma unroll
-    for (int hh = 0; hh < NH; ++hh)
+    for (int e = 0; e < HPL; ++e) {
+      const int hd = gi * HPL + e;
+      const bool live = hd < g;
+      const uint4 raw = live ? *reinterpret_cast<const uint4*>(p.q + (qrow + hd) * D + 8 * j) : make_uint4(0, 0, 0, 0);
+      pw.set_q(e, raw, p.qk_scale_log2, live);
+    }
+    if (idx < p1) {
+      const RecRef rec = rec_ref<NB16, V4>(rec_at(0, idx));
+      m0 = load_meta<NB16>(rec, pw.lo);
+      load_k<NB16, V4>(pg, rec, pw.lo);
+      load_v<NB16, V4>(pg, rec, pw.lo);
+      if constexpr (FP_FIRST) {
+        if (kv0 < kv1) {
+          fp_reset();
+          fp_rows(kv0, kv1);
+          fp_reduce_own(kvacc);
 #pragma unroll
-      for (int k = 0; k < 8; ++k) {
-        float v = accw[hh][k];
-        v += __shfl_xor(v, 16);
-        v += __shfl_xor(v, 32);
-        accw[hh][k] = v;
+          for (int e = 0; e < HPL; ++e) { kvm[e] = mw[e]; kvl[e] = lw[e]; }
+          kv_done = true;
+        }
       }
+      pw.stage_meta(m0);
+      wave_lds_fence();
+      // The two wavefronts that share a SIMD take the higher issue priority in turn, page by page: with equal
+      // priorities the older one wins every conflict and ends its (equal) share of the pages ~6 % earlier,
+      // leaving the block to wait for the younger one.
+      int turn = w / 4;
+      int k = 0;
+      for (; idx < p1q; idx += NW) {
+        const bool has_nx = idx + NW < p1;
+        if (turn & 1) __builtin_amdgcn_s_setprio(1); else __builtin_amdgcn_s_setprio(0);
+        ++turn;
+        ++k;
+        // Where the reloaded ids are first used decides where the compiler waits for them.  Used in this rare
+        // branch, the wait sits here; otherwise the loop head has to assume the load may be pending and drains
+        // the whole load queue, the current page's Value plane included, before every page (+5 % on the 32k
+        // workload).
+        if ((k & 63) == 0) ids = max(load_ids(k), 0);
+        pw.process(pg, rec_ref<NB16, V4>(has_nx ? rec_at(k, idx + NW) : pool_h), has_nx);
+      }
+      __builtin_amdgcn_s_setprio(0);
+      if (lag_here && idx == p1q) pw.logits_to(pg, lagx);   // this wavefront holds the newest page
+    }
+  }
+  if (lag_here) __syncthreads();   // lagx is complete (the condition is the same for the whole block)
+
+  // ---- the full-precision rows that are still to do, then what was saved is folded in
+  float own[HPL][8];        // their sums for this lane group's heads, channels 8j..8j+7
+  fp_reset();
+  if constexpr (FP_FIRST) {
+    if (!kv_done && kv0 < kv1) fp_rows(kv0, kv1);
+    if (lg0 < lg1) fp_rows(lg0, lg1);
+  } else {
+    if (t0 < t1) fp_rows(t0, t1);
+  }
+  fp_reduce_own(own);
+  if constexpr (FP_FIRST) {
+    if (kv_done) {
+#pragma unroll
+      for (int e = 0; e < HPL; ++e) {
+        const float M = fmaxf(mw[e], kvm[e]);                       // kvm is finite: the saved part had rows
+        const float fa = __builtin_amdgcn_exp2f(mw[e] - M), fb = __builtin_amdgcn_exp2f(kvm[e] - M);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) own[e][k] = fmaf(own[e][k], fa, kvacc[e][k] * fb);
+        lw[e] = fmaf(lw[e], fa, kvl[e] * fb);
+        mw[e] = M;
+      }
+    }
   }
 
   // ================= merge the 2*NW partials (wavefronts x {pages, full-precision rows}), write the result ====
@@ -953,11 +1013,7 @@ __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void
     const int hd = gi * HPL + e;
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
-      // every lane group holds the full sums; group gi stores its own heads
-      float v = 0.f;
-#pragma unroll
-      for (int hh = 0; hh < NH; ++hh) v = (hh == hd) ? accw[hh][k] : v;
-      mg.acc[NW + w][hd][8 * j + k] = v;
+      mg.acc[NW + w][hd][8 * j + k] = own[e][k];
     }
   }
   __syncthreads();
