@@ -102,3 +102,23 @@ def test_invalid_arguments_return_codes_without_touching_a_gpu():
     assert lib.kitty_decode_split(C.byref(lay_s), C.byref(cache), 0x70000, 1.0, 0, 0x80000, 1 << 30, None) == kitty.ERR_INVALID_ARG
     assert b"workspace" in lib.kitty_strerror(kitty.ERR_WORKSPACE)
     assert lib.kitty_strerror(12345) == b"unknown error"
+
+
+def test_build_report_parser_finds_scratch_use():
+    """The build refuses kernels that spill to scratch memory; this checks the parser of hipcc's
+    kernel-resource-usage remarks that the check relies on."""
+    from paper_2511_18643_amd import build
+    text = "\n".join([
+        "x.h:1:1: remark: Function Name: _ZN5kitty1aEv [-Rpass-analysis=kernel-resource-usage]",
+        "x.h:1:1: remark:     VGPRs: 152 [-Rpass-analysis=kernel-resource-usage]",
+        "x.h:1:1: remark:     ScratchSize [bytes/lane]: 0 [-Rpass-analysis=kernel-resource-usage]",
+        "x.h:1:1: remark:     LDS Size [bytes/block]: 74112 [-Rpass-analysis=kernel-resource-usage]",
+        "x.h:9:1: remark: Function Name: _ZN5kitty1bEv [-Rpass-analysis=kernel-resource-usage]",
+        "x.h:9:1: remark:     VGPRs: 256 [-Rpass-analysis=kernel-resource-usage]",
+        "x.h:9:1: remark:     ScratchSize [bytes/lane]: 24 [-Rpass-analysis=kernel-resource-usage]",
+    ])
+    u = build.kernel_resource_usage(text)
+    assert set(u) == {"_ZN5kitty1aEv", "_ZN5kitty1bEv"}
+    assert u["_ZN5kitty1aEv"]["VGPRs"] == 152 and u["_ZN5kitty1aEv"]["ScratchSize [bytes/lane]"] == 0
+    assert u["_ZN5kitty1aEv"]["LDS Size [bytes/block]"] == 74112
+    assert u["_ZN5kitty1bEv"]["ScratchSize [bytes/lane]"] == 24
