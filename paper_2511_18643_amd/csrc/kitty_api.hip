@@ -328,12 +328,19 @@ int launch_split(const kitty_layout* L, const kitty_cache* C, const void* q, flo
     };
     using I1 = std::integral_constant<int, 1>; using I2 = std::integral_constant<int, 2>;
     using I4 = std::integral_constant<int, 4>; using I8 = std::integral_constant<int, 8>;
+    // 8-wavefront blocks of the variants that fit 168 registers get a ninth wavefront for the full-precision rows
+    constexpr bool ROWW_OK = NB <= 2 && !V4;
+    auto go_rows = [&](auto fu) {
+      constexpr bool FU = decltype(fu)::value;
+      if constexpr (ROWW_OK) hipLaunchKernelGGL((decode_split_kernel<NB, 1, 8, FU, V4, true>), grid, dim3(64 * 9), 0, st, P);
+      else go(I1{}, I8{}, fu);
+    };
     if (fused) {
       if (wide) { if (big) go(I2{}, I8{}, std::true_type{}); else go(I2{}, I4{}, std::true_type{}); }
-      else      { if (big) go(I1{}, I8{}, std::true_type{}); else go(I1{}, I4{}, std::true_type{}); }
+      else      { if (big) go_rows(std::true_type{}); else go(I1{}, I4{}, std::true_type{}); }
     } else {
       if (wide) { if (big) go(I2{}, I8{}, std::false_type{}); else go(I2{}, I4{}, std::false_type{}); }
-      else      { if (big) go(I1{}, I8{}, std::false_type{}); else go(I1{}, I4{}, std::false_type{}); }
+      else      { if (big) go_rows(std::false_type{}); else go(I1{}, I4{}, std::false_type{}); }
     }
     return launch_status();
   });

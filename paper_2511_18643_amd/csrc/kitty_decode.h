@@ -616,13 +616,17 @@ constexpr int decode_waves_per_simd() { return 2; }
 // freshly written record is fenced before it is read back, and the sequence state is advanced by the block of
 // the sequence that is last to have read the old state (ticket in bits 8.. of n_resid, as in append_token_kernel;
 // the ticket is taken right after the state has been read and looked at only at the end).
-template <int NB16, int HPL, int NW, bool FUSED, bool V4>
-__global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void decode_split_kernel(DecodeParams p) {
+// ROWW: one more wavefront (index NW) that only does the block's full-precision rows, concurrently with the page
+// loop of the others, instead of every wavefront doing a share of them after its pages.  A ninth wavefront puts
+// three on one SIMD, so the variant exists where the kernel fits 168 registers.
+template <int NB16, int HPL, int NW, bool FUSED, bool V4, bool ROWW = false>
+__global__ __launch_bounds__(64 * (NW + (ROWW ? 1 : 0)), (ROWW ? 3 : decode_waves_per_simd<NB16, HPL>())) void decode_split_kernel(DecodeParams p) {
   using R = Rec<NB16, V4>;
   constexpr int RPH = 4 / HPL;
   constexpr int NH = 4 * HPL;              // heads handled by the block
+  constexpr int NT = NW + (ROWW ? 1 : 0);  // wavefronts of the block
 
-  __shared__ DecodeSmem<NB16, HPL, NW, FUSED> smem;
+  __shared__ DecodeSmem<NB16, HPL, NT, FUSED> smem;
 
   const int slot = blockIdx.x, h = blockIdx.y;
   const int b = p.seq_order ? p.seq_order[blockIdx.z] : (int)blockIdx.z;
@@ -630,6 +634,7 @@ __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void
   const int tid = threadIdx.x;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: page ids stay in scalar registers
   const int l = tid & 63, j = l & 15, gi = l >> 4;
+  const bool roww = ROWW && w == NW;       // this wavefront does rows, not pages
   const int g = p.gqa;
   const size_t pair = (size_t)b * p.n_kv_heads + h;
 
@@ -700,7 +705,7 @@ __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void
   const int sb = active_splits(np, nfp, p.n_splits, p.min_pages);
   if (slot >= sb) {   // nothing to attend over (never the case in a fused step that appended a token)
     if (p.direct_out && slot == 0) {   // empty sequence: the result is defined as zeros
-      for (int o = tid; o < g * D; o += 64 * NW) {
+      for (int o = tid; o < g * D; o += 64 * NT) {
         const size_t oi = ((size_t)b * p.n_q_heads + (size_t)h * g) * D + o;
         if (p.out_dtype == 0) reinterpret_cast<uint16_t*>(p.out)[oi] = 0;
         else reinterpret_cast<float*>(p.out)[oi] = 0.f;
@@ -764,7 +769,7 @@ __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void
       }
     }
   };
-  constexpr bool FP_FIRST = NW == 4 && !(HPL == 2 && NB16 >= 4);   // (not where the registers are all taken)
+  constexpr bool FP_FIRST = !ROWW && NW == 4 && !(HPL == 2 && NB16 >= 4);   // (not where the registers are all taken)
   const int wr0 = (int)((long long)slot * nfp / sb), wr1 = (int)((long long)(slot + 1) * nfp / sb);
   const int nkv = wr1 - wr0;                       // rows of this block with bf16 Keys and Values
   const int nlag = lag_here ? G : 0;               // rows of the newest page (list indices nkv ..)
@@ -893,6 +898,14 @@ __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void
     }
   };
 
+  float own[HPL][8];        // the rows' sums for this lane group's heads, channels 8j..8j+7
+  if (roww) {                   // (one branch against the other, so that these sums do not live through the page loop)
+    fp_reset();
+    if (nkv > 0) fp_rows(0, nkv);             // Sink and window rows, while the others stream their pages
+    if (lag_here) __syncthreads();            // (the block's other wavefronts meet this barrier below)
+    if (nlag > 0) fp_rows(nkv, nkv + nlag);   // the newest page's rows, now that their logits are there
+    fp_reduce_own(own);
+  } else {
   if (p0 < p1) {
     const int32_t* pt = p.page_table + (size_t)b * p.max_pages;
     const size_t rec_stride = (size_t)p.n_kv_heads * R::bytes;
@@ -972,60 +985,75 @@ __global__ __launch_bounds__(64 * NW, (decode_waves_per_simd<NB16, HPL>())) void
   if (lag_here) __syncthreads();   // lagx is complete (the condition is the same for the whole block)
 
   // ---- the full-precision rows that are still to do, then what was saved is folded in
-  float own[HPL][8];        // their sums for this lane group's heads, channels 8j..8j+7
-  fp_reset();
-  if constexpr (FP_FIRST) {
-    if (!kv_done && kv0 < kv1) fp_rows(kv0, kv1);
-    if (lg0 < lg1) fp_rows(lg0, lg1);
+  if constexpr (ROWW) {
+    fp_reset();
+#pragma unroll
+    for (int e = 0; e < HPL; ++e)
+#pragma unroll
+      for (int k = 0; k < 8; ++k) own[e][k] = 0.f;
   } else {
-    if (t0 < t1) fp_rows(t0, t1);
-  }
-  fp_reduce_own(own);
-  if constexpr (FP_FIRST) {
-    if (kv_done) {
+    fp_reset();
+    if constexpr (FP_FIRST) {
+      if (!kv_done && kv0 < kv1) fp_rows(kv0, kv1);
+      if (lg0 < lg1) fp_rows(lg0, lg1);
+    } else {
+      if (t0 < t1) fp_rows(t0, t1);
+    }
+    fp_reduce_own(own);
+    if constexpr (FP_FIRST) {
+      if (kv_done) {
 #pragma unroll
-      for (int e = 0; e < HPL; ++e) {
-        const float M = fmaxf(mw[e], kvm[e]);                       // kvm is finite: the saved part had rows
-        const float fa = __builtin_amdgcn_exp2f(mw[e] - M), fb = __builtin_amdgcn_exp2f(kvm[e] - M);
+        for (int e = 0; e < HPL; ++e) {
+          const float M = fmaxf(mw[e], kvm[e]);                       // kvm is finite: the saved part had rows
+          const float fa = __builtin_amdgcn_exp2f(mw[e] - M), fb = __builtin_amdgcn_exp2f(kvm[e] - M);
 #pragma unroll
-        for (int k = 0; k < 8; ++k) own[e][k] = fmaf(own[e][k], fa, kvacc[e][k] * fb);
-        lw[e] = fmaf(lw[e], fa, kvl[e] * fb);
-        mw[e] = M;
+          for (int k = 0; k < 8; ++k) own[e][k] = fmaf(own[e][k], fa, kvacc[e][k] * fb);
+          lw[e] = fmaf(lw[e], fa, kvl[e] * fb);
+          mw[e] = M;
+        }
       }
     }
   }
 
-  // ================= merge the 2*NW partials (wavefronts x {pages, full-precision rows}), write the result ====
+  }   // (wavefronts that do pages)
+
+  // ================= merge the partials (wavefronts x {pages, full-precision rows}), write the result ====
+  // slots: pages of wavefront w in slot w; rows in slot NW + w, or in slot NW when one wavefront did them all
+  constexpr int NPART = ROWW ? NW + 1 : 2 * NW;
   float lsum[HPL], zsum[HPL], lwsum[HPL];
 #pragma unroll
   for (int e = 0; e < HPL; ++e) { lsum[e] = row_sum(pw.l_run[e]); zsum[e] = row_sum(pw.z_run[e]); lwsum[e] = row_sum(lw[e]); }
   __syncthreads();   // every wavefront is done with its scratch
-  MergeScratch<HPL, NW>& mg = smem.mg;
+  MergeScratch<HPL, NT>& mg = smem.mg;
+  if (!roww) {
 #pragma unroll
-  for (int e = 0; e < HPL; ++e) {
-    const int hd = gi * HPL + e;
+    for (int e = 0; e < HPL; ++e) {
+      const int hd = gi * HPL + e;
 #pragma unroll
-    for (int Td = 0; Td < 8; ++Td) mg.acc[w][hd][16 * Td + j] = fmaf(pw.acc[e][Td], pw.acc_unit[e], zsum[e]);
-    if (j == 0) { mg.m[w][hd] = pw.m_run[e]; mg.l[w][hd] = lsum[e]; mg.m[NW + w][hd] = mw[e]; mg.l[NW + w][hd] = lwsum[e]; }
+      for (int Td = 0; Td < 8; ++Td) mg.acc[w][hd][16 * Td + j] = fmaf(pw.acc[e][Td], pw.acc_unit[e], zsum[e]);
+      if (j == 0) { mg.m[w][hd] = pw.m_run[e]; mg.l[w][hd] = lsum[e]; }
+    }
   }
+  if (!ROWW || roww) {
+    const int rs = ROWW ? NW : NW + w;
 #pragma unroll
-  for (int e = 0; e < HPL; ++e) {
-    const int hd = gi * HPL + e;
+    for (int e = 0; e < HPL; ++e) {
+      const int hd = gi * HPL + e;
+      if (j == 0) { mg.m[rs][hd] = mw[e]; mg.l[rs][hd] = lwsum[e]; }
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      mg.acc[NW + w][hd][8 * j + k] = own[e][k];
+      for (int k = 0; k < 8; ++k) mg.acc[rs][hd][8 * j + k] = own[e][k];
     }
   }
   __syncthreads();
   float* part = p.ws + (((size_t)b * p.n_kv_heads + h) * p.n_splits + slot) * (size_t)g * WS_STRIDE;
-  for (int o = tid; o < g * D; o += 64 * NW) {
+  for (int o = tid; o < g * D; o += 64 * NT) {
     const int hd = o >> 7, d = o & 127;
     float M = -INFINITY;
 #pragma unroll
-    for (int ww = 0; ww < 2 * NW; ++ww) M = fmaxf(M, mg.m[ww][hd]);
+    for (int ww = 0; ww < NPART; ++ww) M = fmaxf(M, mg.m[ww][hd]);
     float a = 0.f, L = 0.f;
 #pragma unroll
-    for (int ww = 0; ww < 2 * NW; ++ww) {
+    for (int ww = 0; ww < NPART; ++ww) {
       const float f = __builtin_amdgcn_exp2f(mg.m[ww][hd] - M);   // exp2(-inf) = 0 for idle partials
       a = fmaf(mg.acc[ww][hd][d], f, a);
       L = fmaf(mg.l[ww][hd], f, L);
