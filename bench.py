@@ -86,6 +86,10 @@ def recorded_traffic(workload):
 def gpu_clocks(busy):
     """Clock speeds rocm-smi reports while `busy()` keeps the GPU loaded (a child process; None if unusable)."""
     import subprocess
+    # under a profiler every child inherits its preloaded library (which touches the GPU before the child's own
+    # exec of the script interpreter): no child processes then
+    if "rocprof" in os.environ.get("LD_PRELOAD", "") or any(k.startswith("ROCPROF") for k in os.environ):
+        return None
     try:
         pr = subprocess.Popen(["rocm-smi", "-d", "0", "--showclocks", "--json"], stdout=subprocess.PIPE,
                               stderr=subprocess.DEVNULL, text=True)

@@ -329,11 +329,19 @@ int launch_split(const kitty_layout* L, const kitty_cache* C, const void* q, flo
     using I1 = std::integral_constant<int, 1>; using I2 = std::integral_constant<int, 2>;
     using I4 = std::integral_constant<int, 4>; using I8 = std::integral_constant<int, 8>;
     // 8-wavefront blocks of the variants that fit 168 registers get a ninth wavefront for the full-precision rows
+    // (32k workload -1 %, 8k workload -12 %); not with the Value Local window, whose rows can only follow the
+    // pages (+2 % there)
     constexpr bool ROWW_OK = NB <= 2 && !V4;
+    const bool row_wave = !L->v_local;
     auto go_rows = [&](auto fu) {
       constexpr bool FU = decltype(fu)::value;
-      if constexpr (ROWW_OK) hipLaunchKernelGGL((decode_split_kernel<NB, 1, 8, FU, V4, true>), grid, dim3(64 * 9), 0, st, P);
-      else go(I1{}, I8{}, fu);
+      if constexpr (ROWW_OK) {
+        if (row_wave) {
+          hipLaunchKernelGGL((decode_split_kernel<NB, 1, 8, FU, V4, true>), grid, dim3(64 * 9), 0, st, P);
+          return;
+        }
+      }
+      go(I1{}, I8{}, fu);
     };
     if (fused) {
       if (wide) { if (big) go(I2{}, I8{}, std::true_type{}); else go(I2{}, I4{}, std::true_type{}); }

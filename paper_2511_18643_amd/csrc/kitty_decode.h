@@ -776,7 +776,7 @@ __global__ __launch_bounds__(64 * (NW + (ROWW ? 1 : 0)), (ROWW ? 3 : decode_wave
   // runs of this wavefront: of the whole list, or (rows first) of its two parts
   const int per = (nkv + nlag + NW - 1) / NW;
   const int t0 = w * per, t1 = min(t0 + per, nkv + nlag);
-  const int perk = (nkv + NW - 1) / NW, perl = (nlag + NW - 1) / NW;
+  const int perk = (nkv + NW - 1) / NW, perl = (nlag + NT - 1) / NT;   // (the newest page's rows: every wavefront)
   const int kv0 = w * perk, kv1 = min(kv0 + perk, nkv);
   const int lg0 = nkv + min(w * perl, nlag), lg1 = nkv + min((w + 1) * perl, nlag);
   float kvacc[HPL][8], kvm[HPL], kvl[HPL];         // rows first: what is carried through the page loop
@@ -903,7 +903,7 @@ __global__ __launch_bounds__(64 * (NW + (ROWW ? 1 : 0)), (ROWW ? 3 : decode_wave
     fp_reset();
     if (nkv > 0) fp_rows(0, nkv);             // Sink and window rows, while the others stream their pages
     if (lag_here) __syncthreads();            // (the block's other wavefronts meet this barrier below)
-    if (nlag > 0) fp_rows(nkv, nkv + nlag);   // the newest page's rows, now that their logits are there
+    if (lg0 < lg1) fp_rows(lg0, lg1);         // its share of the newest page's rows, now that their logits are there
     fp_reduce_own(own);
   } else {
   if (p0 < p1) {
@@ -987,10 +987,8 @@ __global__ __launch_bounds__(64 * (NW + (ROWW ? 1 : 0)), (ROWW ? 3 : decode_wave
   // ---- the full-precision rows that are still to do, then what was saved is folded in
   if constexpr (ROWW) {
     fp_reset();
-#pragma unroll
-    for (int e = 0; e < HPL; ++e)
-#pragma unroll
-      for (int k = 0; k < 8; ++k) own[e][k] = 0.f;
+    if (lg0 < lg1) fp_rows(lg0, lg1);       // the newest page's rows are shared by all wavefronts of the block
+    fp_reduce_own(own);
   } else {
     fp_reset();
     if constexpr (FP_FIRST) {
@@ -1018,8 +1016,8 @@ __global__ __launch_bounds__(64 * (NW + (ROWW ? 1 : 0)), (ROWW ? 3 : decode_wave
   }   // (wavefronts that do pages)
 
   // ================= merge the partials (wavefronts x {pages, full-precision rows}), write the result ====
-  // slots: pages of wavefront w in slot w; rows in slot NW + w, or in slot NW when one wavefront did them all
-  constexpr int NPART = ROWW ? NW + 1 : 2 * NW;
+  // slots: pages of wavefront w in slot w, its rows in slot NW + w; with a row wavefront that one's rows in slot
+  // NW and, when the newest page's rows are read here, the others' shares of those in slots NW + 1 + w
   float lsum[HPL], zsum[HPL], lwsum[HPL];
 #pragma unroll
   for (int e = 0; e < HPL; ++e) { lsum[e] = row_sum(pw.l_run[e]); zsum[e] = row_sum(pw.z_run[e]); lwsum[e] = row_sum(lw[e]); }
@@ -1034,8 +1032,8 @@ __global__ __launch_bounds__(64 * (NW + (ROWW ? 1 : 0)), (ROWW ? 3 : decode_wave
       if (j == 0) { mg.m[w][hd] = pw.m_run[e]; mg.l[w][hd] = lsum[e]; }
     }
   }
-  if (!ROWW || roww) {
-    const int rs = ROWW ? NW : NW + w;
+  if (!ROWW || roww || lag_here) {
+    const int rs = ROWW ? (roww ? NW : NW + 1 + w) : NW + w;
 #pragma unroll
     for (int e = 0; e < HPL; ++e) {
       const int hd = gi * HPL + e;
@@ -1046,6 +1044,8 @@ __global__ __launch_bounds__(64 * (NW + (ROWW ? 1 : 0)), (ROWW ? 3 : decode_wave
   }
   __syncthreads();
   float* part = p.ws + (((size_t)b * p.n_kv_heads + h) * p.n_splits + slot) * (size_t)g * WS_STRIDE;
+  auto merge_out = [&](auto npc) {     // npc: how many partial slots are in use (a compile-time constant)
+  constexpr int NPART = decltype(npc)::value;
   for (int o = tid; o < g * D; o += 64 * NT) {
     const int hd = o >> 7, d = o & 127;
     float M = -INFINITY;
@@ -1067,6 +1067,13 @@ __global__ __launch_bounds__(64 * (NW + (ROWW ? 1 : 0)), (ROWW ? 3 : decode_wave
       part[hd * WS_STRIDE + d] = a;
       if (d == 0) { part[hd * WS_STRIDE + D] = M; part[hd * WS_STRIDE + D + 1] = L; }
     }
+  }
+  };
+  if constexpr (ROWW) {
+    if (lag_here) merge_out(std::integral_constant<int, 2 * NW + 1>{});
+    else merge_out(std::integral_constant<int, NW + 1>{});
+  } else {
+    merge_out(std::integral_constant<int, 2 * NW>{});
   }
   if constexpr (FUSED) {
     if (keep_dst) *reinterpret_cast<uint4*>(keep_dst) = keep_val;
