@@ -331,7 +331,7 @@ int launch_split(const kitty_layout* L, const kitty_cache* C, const void* q, flo
     // 8-wavefront blocks of the variants that fit 168 registers get a ninth wavefront for the full-precision rows
     // (32k workload -1 %, 8k workload -12 %); not with the Value Local window, whose rows can only follow the
     // pages (+2 % there)
-    constexpr bool ROWW_OK = NB <= 2 && !V4;
+    constexpr bool ROWW_OK = V4 ? NB == 0 : NB <= 2;
     const bool row_wave = !L->v_local;
     auto go_rows = [&](auto fu) {
       constexpr bool FU = decltype(fu)::value;
