@@ -961,14 +961,18 @@ __global__ __launch_bounds__(64 * (NW + (ROWW ? 1 : 0)), (ROWW ? 3 : decode_wave
       }
       pw.stage_meta(m0);
       wave_lds_fence();
-      // The two wavefronts that share a SIMD take the higher issue priority in turn, page by page: with equal
-      // priorities the older one wins every conflict and ends its (equal) share of the pages ~6 % earlier,
-      // leaving the block to wait for the younger one.
-      int turn = w / 4;
+      // The two wavefronts that share a SIMD take the higher issue priority in turn: with equal priorities the
+      // older one (w < 4) wins every conflict and ends its equal share of the pages ~7 % earlier, leaving the block
+      // to wait for the younger one.  The younger one gets the higher priority on three pages out of four (plain
+      // alternation leaves it 6-7 us behind on the 32k workload; two out of three measures the same, five out of
+      // six and more, or always, worse).  4-wavefront blocks share their SIMDs with another block's wavefronts and
+      // simply alternate.
+      int turn = 0;
       int k = 0;
       for (; idx < p1q; idx += NW) {
         const bool has_nx = idx + NW < p1;
-        if (turn & 1) __builtin_amdgcn_s_setprio(1); else __builtin_amdgcn_s_setprio(0);
+        const bool high = NW == 4 ? (turn & 1) != 0 : (w >= 4 ? (turn & 3) != 0 : (turn & 3) == 0);
+        if (high) __builtin_amdgcn_s_setprio(1); else __builtin_amdgcn_s_setprio(0);
         ++turn;
         ++k;
         // Where the reloaded ids are first used decides where the compiler waits for them.  Used in this rare
