@@ -52,15 +52,17 @@ def test_sink_without_window():
     assert err <= TOL_FP32
 
 
-@pytest.mark.parametrize("fused,max_pages,n_splits", [(False, 4, 0), (True, 4, 0), (True, 40, 1), (True, 4, 2)])
-def test_decode_loop_from_empty_matches_unit_oracle(fused, max_pages, n_splits):
+@pytest.mark.parametrize("fused,max_pages,n_splits,VL", [(False, 4, 0, 128), (True, 4, 0, 128), (True, 40, 1, 128), (True, 4, 2, 128),
+                                                         (True, 40, 1, 0), (False, 40, 1, 0)])
+def test_decode_loop_from_empty_matches_unit_oracle(fused, max_pages, n_splits, VL):
     """Token-by-token decode from an empty cache through the Sink, the first pages and the Local window,
     either as kitty_append_token + kitty_decode_attention or as the single kitty_decode_step call.  Sequences
     start at different lengths so that Sink fill, flushes and the first Value-lagging page fall on different
-    steps.  State, flushed records (bit-exact) and outputs are checked against the unit oracles."""
+    steps.  State, flushed records (bit-exact) and outputs are checked against the unit oracles.  VL = 0: Sink and
+    the single window only (with 40 pages per sequence: the 8-wavefront blocks with a row wavefront)."""
     import torch
     from paper_2511_18643_amd import kitty
-    S, VL = 32, 128
+    S = 32
     w = small(batch=4)
     start = [0, 31, 32 + 127, 32 + 128 + 120]
     k0, v0 = H.gen_sequences(w, start)
