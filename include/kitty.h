@@ -163,8 +163,11 @@ int kitty_decode_merge(const kitty_layout* layout, const kitty_cache* cache, voi
 /* One decode step of one layer in a single call: kitty_append_token(k_new, v_new, fresh_page_ids) followed by
  * kitty_decode_attention(q -> out) (Sec. 4.3 steps 1-3), with the same arguments and results as those two
  * calls.  When the plan has one page range per (sequence, kv-head) both halves run in one kernel launch (each
- * block appends its own (sequence, kv-head) share, flushing a full window first, then attends); otherwise the
- * two calls are made one after the other.  Requires residual_window == page_size. */
+ * block appends its own (sequence, kv-head) share, flushing a full window first, then attends).  With several
+ * ranges there are two launches: the streaming kernel attends over the state the append will leave (the block of
+ * a (sequence, kv-head)'s last range flushes a full window first; the new token is read from k_new / v_new), and
+ * the merge launch then stores the token and advances the sequence state.  Requires residual_window ==
+ * page_size. */
 int kitty_decode_step(const kitty_layout* layout, const kitty_cache* cache, const void* k_new,
                       const void* v_new, const int32_t* fresh_page_ids, const void* q, void* out,
                       float sm_scale, int32_t n_splits, int32_t out_dtype, void* workspace,

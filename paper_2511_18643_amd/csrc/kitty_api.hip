@@ -283,7 +283,8 @@ struct StepArgs {   // the append half of a fused step
 };
 
 // Launches the streaming kernel.  With `out` non-null and a one-range plan the kernel stores the result itself;
-// with `step` non-null (one-range plans only) it also performs the append first.
+// with `step` non-null it also performs the append first (with several ranges: the flush only; the merge launch
+// that follows stores the token and advances the state).
 int launch_split(const kitty_layout* L, const kitty_cache* C, const void* q, float sm_scale, int32_t n_splits,
                  void* workspace, size_t workspace_bytes, void* out, int32_t out_dtype, void* hip_stream, bool* merged,
                  const StepArgs* step) {
@@ -299,7 +300,6 @@ int launch_split(const kitty_layout* L, const kitty_cache* C, const void* q, flo
   P.out_dtype = out_dtype;
   if (merged) *merged = P.direct_out != 0;
   if (step) {
-    if (!P.direct_out) return KITTY_ERR_INVALID_ARG;   // callers check the plan first
     P.k_new = static_cast<const uint16_t*>(step->k_new);
     P.v_new = static_cast<const uint16_t*>(step->v_new);
     P.fresh_page_ids = step->fresh_page_ids;
@@ -323,7 +323,7 @@ int launch_split(const kitty_layout* L, const kitty_cache* C, const void* q, flo
     constexpr bool V4 = decltype(v4)::value;
     auto go = [&](auto hpl, auto nw, auto fu) {
       constexpr int HPL = decltype(hpl)::value, NW = decltype(nw)::value;
-      constexpr bool FU = decltype(fu)::value;
+      constexpr int FU = decltype(fu)::value;
       hipLaunchKernelGGL((decode_split_kernel<NB, HPL, NW, FU, V4>), grid, dim3(64 * NW), 0, st, P);
     };
     using I1 = std::integral_constant<int, 1>; using I2 = std::integral_constant<int, 2>;
@@ -334,7 +334,7 @@ int launch_split(const kitty_layout* L, const kitty_cache* C, const void* q, flo
     constexpr bool ROWW_OK = V4 ? NB == 0 : NB <= 2;
     const bool row_wave = !L->v_local;
     auto go_rows = [&](auto fu) {
-      constexpr bool FU = decltype(fu)::value;
+      constexpr int FU = decltype(fu)::value;
       if constexpr (ROWW_OK) {
         if (row_wave) {
           hipLaunchKernelGGL((decode_split_kernel<NB, 1, 8, FU, V4, true>), grid, dim3(64 * 9), 0, st, P);
@@ -343,13 +343,16 @@ int launch_split(const kitty_layout* L, const kitty_cache* C, const void* q, flo
       }
       go(I1{}, I8{}, fu);
     };
-    if (fused) {
-      if (wide) { if (big) go(I2{}, I8{}, std::true_type{}); else go(I2{}, I4{}, std::true_type{}); }
-      else      { if (big) go_rows(std::true_type{}); else go(I1{}, I4{}, std::true_type{}); }
-    } else {
-      if (wide) { if (big) go(I2{}, I8{}, std::false_type{}); else go(I2{}, I4{}, std::false_type{}); }
-      else      { if (big) go_rows(std::false_type{}); else go(I1{}, I4{}, std::false_type{}); }
-    }
+    using F0 = std::integral_constant<int, 0>;   // attention only
+    using F1 = std::integral_constant<int, 1>;   // fused step, one range: the kernel also stores the token and advances the state
+    using F2 = std::integral_constant<int, 2>;   // fused step, several ranges: the merge launch does that
+    auto pick = [&](auto fu) {
+      if (wide) { if (big) go(I2{}, I8{}, fu); else go(I2{}, I4{}, fu); }
+      else      { if (big) go_rows(fu); else go(I1{}, I4{}, fu); }
+    };
+    if (!fused) pick(F0{});
+    else if (P.direct_out) pick(F1{});
+    else pick(F2{});
     return launch_status();
   });
 }
@@ -395,15 +398,30 @@ int kitty_decode_step(const kitty_layout* L, const kitty_cache* C, const void* k
   if (!k_new || !v_new || !fresh_page_ids || !C->page_pool || !C->page_table) return KITTY_ERR_INVALID_ARG;
   if (reinterpret_cast<uintptr_t>(k_new) % 16 || reinterpret_cast<uintptr_t>(v_new) % 16) return KITTY_ERR_INVALID_ARG;
   if (!out || (out_dtype != 0 && out_dtype != 1) || n_splits < 0) return KITTY_ERR_INVALID_ARG;
-  int32_t ns, mp;
-  plan_splits(L, C->batch, C->max_pages, n_splits, &ns, &mp);
-  if (ns != 1) {   // several ranges per sequence: a flushed page would have to cross blocks; take the two-call path
-    rc = kitty_append_token(L, C, k_new, v_new, fresh_page_ids, hip_stream);
-    if (rc) return rc;
-    return kitty_decode_attention(L, C, q, out, sm_scale, n_splits, out_dtype, workspace, workspace_bytes, hip_stream);
-  }
   const StepArgs step{k_new, v_new, fresh_page_ids};
-  return launch_split(L, C, q, sm_scale, n_splits, workspace, workspace_bytes, out, out_dtype, hip_stream, nullptr, &step);
+  bool merged = false;
+  rc = launch_split(L, C, q, sm_scale, n_splits, workspace, workspace_bytes, out, out_dtype, hip_stream, &merged, &step);
+  if (rc || merged) return rc;
+  // several ranges: the merge launch also stores the token and advances the state
+  DecodeParams P;
+  rc = fill_decode_params(L, C, n_splits, workspace, workspace_bytes, &P);
+  if (rc) return rc;
+  if (L->n_q_heads > 65535 * 8 || C->batch > 65535) return KITTY_ERR_UNSUPPORTED;
+  P.out = out;
+  P.out_dtype = out_dtype;
+  P.k_new = static_cast<const uint16_t*>(k_new);
+  P.v_new = static_cast<const uint16_t*>(v_new);
+  P.fresh_page_ids = fresh_page_ids;
+  P.page_table_w = C->page_table;
+  P.n_pages_w = C->n_pages;
+  P.resid_k_w = static_cast<uint16_t*>(C->resid_k);
+  P.resid_v_w = static_cast<uint16_t*>(C->resid_v);
+  P.n_resid_w = C->n_resid;
+  P.sink_k_w = static_cast<uint16_t*>(C->sink_k);
+  P.sink_v_w = static_cast<uint16_t*>(C->sink_v);
+  P.n_sink_w = C->n_sink;
+  hipLaunchKernelGGL(decode_merge_step_kernel, dim3(L->n_q_heads, C->batch), dim3(128), 0, static_cast<hipStream_t>(hip_stream), P);
+  return launch_status();
 }
 
 const char* kitty_strerror(int code) {

@@ -619,14 +619,17 @@ constexpr int decode_waves_per_simd() { return 2; }
 // ROWW: one more wavefront (index NW) that only does the block's full-precision rows, concurrently with the page
 // loop of the others, instead of every wavefront doing a share of them after its pages.  A ninth wavefront puts
 // three on one SIMD, so the variant exists where the kernel fits 168 registers.
-template <int NB16, int HPL, int NW, bool FUSED, bool V4, bool ROWW = false>
+// FUSED: 0 = attention only; 1 = append first, one range per (sequence, kv-head); 2 = append first, several ranges
+// (the merge launch stores the token and advances the state)
+template <int NB16, int HPL, int NW, int FUSED, bool V4, bool ROWW = false>
 __global__ __launch_bounds__(64 * (NW + (ROWW ? 1 : 0)), (ROWW ? 3 : decode_waves_per_simd<NB16, HPL>())) void decode_split_kernel(DecodeParams p) {
   using R = Rec<NB16, V4>;
   constexpr int RPH = 4 / HPL;
   constexpr int NH = 4 * HPL;              // heads handled by the block
   constexpr int NT = NW + (ROWW ? 1 : 0);  // wavefronts of the block
 
-  __shared__ DecodeSmem<NB16, HPL, NT, FUSED> smem;
+  constexpr bool DEFER = FUSED == 2;
+  __shared__ DecodeSmem<NB16, HPL, NT, FUSED != 0> smem;
 
   const int slot = blockIdx.x, h = blockIdx.y;
   const int b = p.seq_order ? p.seq_order[blockIdx.z] : (int)blockIdx.z;
@@ -653,57 +656,68 @@ __global__ __launch_bounds__(64 * (NW + (ROWW ? 1 : 0)), (ROWW ? 3 : decode_wave
   // the kernel, so that nobody waits for the round trip; attention reads the token from k_new / v_new itself
   uint4 keep_val = make_uint4(0, 0, 0, 0);
   uint16_t* keep_dst = nullptr;
+  // Fused append.  Every block of the sequence works out the state after the step from the state before it.  With
+  // one range per (sequence, kv-head) the block also stores the token and takes part in advancing the state; with
+  // several ranges (defer_state) the block of the last active range, which alone reads the newest page, flushes a
+  // full window into it, and the token and the state are left to the merge launch that follows.
+  int32_t pid = -1;
   if constexpr (FUSED) {
-    const int32_t pid = p.fresh_page_ids[b];
+    pid = p.fresh_page_ids[b];
     knew_h = p.k_new + pair * D;
     vnew_h = p.v_new + pair * D;
     if (ns_old < p.sink_cap) {    // the Sink is not full: the token goes there and nothing else changes
-      if (tid < 32) {
-        const int part = tid & 15;
-        keep_dst = (tid < 16 ? p.sink_k_w : p.sink_v_w) + (pair * p.sink_cap + ns_old) * D + part * 8;
-      }
       newsink = ns_old;
       ns = ns_old + 1;
     } else {
       flush = nr_old >= G;
       ok = !flush || (np_old < p.max_pages && pid >= 0 && pid < p.n_pool_pages);
-      uint16_t* wkw = p.resid_k_w + pair * (size_t)(G * D);
       if (ok) {
+        if (flush) { np = np_old + 1; r = 1; newrow = 0; }
+        else { r = nr_old + 1; newrow = nr_old; }
+      }
+    }
+  }
+  const int nfp = ns + r;       // rows read in full precision for both Keys and Values: Sink, then window
+  const int sb = active_splits(np, nfp, p.n_splits, p.min_pages);
+  int ticket = 0;
+  if constexpr (FUSED) {
+    if (!DEFER || slot == sb - 1) {
+      if (newsink >= 0) {
+        if (!DEFER && tid < 32)
+          keep_dst = (tid < 16 ? p.sink_k_w : p.sink_v_w) + (pair * p.sink_cap + ns_old) * D + (tid & 15) * 8;
+      } else if (ok) {
+        uint16_t* wkw = p.resid_k_w + pair * (size_t)(G * D);
         if (flush) {
           uint8_t* rec = p.pool_w + ((size_t)pid * p.n_kv_heads + h) * (size_t)R::bytes;
           const uint16_t* wv_old = p.resid_v_w + resid_v_offset(b, h, p.n_kv_heads, p.v_local, np_old);
           quantize_page<NB16, V4>(smem.quant, wkw, wv_old, D, rec, p.rank_metric);
-          __threadfence();          // the record is read back by this block's wavefronts
+          // The record is read back by this block's wavefronts only, which share the compute unit and its
+          // first-level cache: the barrier's workgroup-scope release/acquire is all the ordering needed.  (A
+          // device-scope fence here writes the whole second-level cache back: +35 us on a step with a flush.)
           __syncthreads();
           fresh_pid = pid;
-          np = np_old + 1;
-          r = 1;
-          newrow = 0;
-        } else {
-          r = nr_old + 1;
-          newrow = nr_old;
         }
-        if (tid < 32) {             // keep the token for the following steps
-          const int part = tid & 15;
+        if (!DEFER && tid < 32) {             // keep the token for the following steps
           uint16_t* wvw = p.resid_v_w + resid_v_offset(b, h, p.n_kv_heads, p.v_local, np);
-          keep_dst = (tid < 16 ? wkw : wvw) + (size_t)newrow * D + part * 8;
+          keep_dst = (tid < 16 ? wkw : wvw) + (size_t)newrow * D + (tid & 15) * 8;
         }
       }
     }
+    // Every block of the sequence has to see the old state, so the state is advanced by the block that is last to
+    // have read it: a ticket is taken here (its answer is not needed before the end of the kernel, which hides
+    // the round trip of the atomic), and the holder of the last ticket stores the new state when it is done.
+    if (!DEFER) {
+      __syncthreads();            // all wavefronts of this block have read the state (they branched on it above)
+      if (tid == 0) ticket = atomicAdd(&p.n_resid_w[b], 1 << TICKET_SHIFT);
+      // (fetched behind the barrier, which waits for every outstanding load of the wavefront)
+      if (keep_dst) keep_val = *reinterpret_cast<const uint4*>((tid < 16 ? knew_h : vnew_h) + (tid & 15) * 8);
+    }
   }
-  // Every block of the sequence has to see the old state, so the state is advanced by the block that is last to
-  // have read it: a ticket is taken here (its answer is not needed before the end of the kernel, which hides
-  // the round trip of the atomic), and the holder of the last ticket stores the new state when it is done.
-  int ticket = 0;
-  if constexpr (FUSED) {
-    __syncthreads();            // all wavefronts of this block have read the state (they branched on it above)
-    if (tid == 0) ticket = atomicAdd(&p.n_resid_w[b], 1 << TICKET_SHIFT);
-    // (fetched behind the barrier, which waits for every outstanding load of the wavefront)
-    if (keep_dst) keep_val = *reinterpret_cast<const uint4*>((tid < 16 ? knew_h : vnew_h) + (tid & 15) * 8);
-  }
-  const int nfp = ns + r;       // rows read in full precision for both Keys and Values: Sink, then window
-  const int sb = active_splits(np, nfp, p.n_splits, p.min_pages);
-  if (slot >= sb) {   // nothing to attend over (never the case in a fused step that appended a token)
+  if (slot >= sb) {   // no share of this sequence for this range
+    if (DEFER) {   // the merge that follows does not look at the state: leave a neutral partial
+      float* part = p.ws + (((size_t)b * p.n_kv_heads + h) * p.n_splits + slot) * (size_t)g * WS_STRIDE;
+      for (int o = tid; o < g * WS_STRIDE; o += 64 * NT) part[o] = (o % WS_STRIDE) == D ? -INFINITY : 0.f;
+    }
     if (p.direct_out && slot == 0) {   // empty sequence: the result is defined as zeros
       for (int o = tid; o < g * D; o += 64 * NT) {
         const size_t oi = ((size_t)b * p.n_q_heads + (size_t)h * g) * D + o;
@@ -1081,14 +1095,14 @@ __global__ __launch_bounds__(64 * (NW + (ROWW ? 1 : 0)), (ROWW ? 3 : decode_wave
   }
   if constexpr (FUSED) {
     if (keep_dst) *reinterpret_cast<uint4*>(keep_dst) = keep_val;
-    if (tid == 0) {
+    if (tid == 0 && !DEFER) {
       if ((ticket >> TICKET_SHIFT) == p.n_kv_heads - 1) {   // every block of this sequence has read the old state
         int new_nr = nr_old;
         if (newsink >= 0) {
           p.n_sink_w[b] = ns_old + 1;
         } else if (ok) {
           if (flush) {
-            p.page_table_w[(size_t)b * p.max_pages + np_old] = fresh_pid;
+            p.page_table_w[(size_t)b * p.max_pages + np_old] = pid;
             p.n_pages_w[b] = np_old + 1;
             new_nr = 1;
           } else {
@@ -1148,6 +1162,66 @@ __global__ __launch_bounds__(128) void decode_merge_kernel(DecodeParams p) {
   const size_t oi = ((size_t)b * p.n_q_heads + hq) * D + d;
   if (p.out_dtype == 0) reinterpret_cast<uint16_t*>(p.out)[oi] = f32_to_bf16_rne(o);
   else reinterpret_cast<float*>(p.out)[oi] = o;
+}
+
+// The merge launch of a fused step with several ranges: every slot of the workspace holds a partial (neutral ones
+// for ranges a sequence does not use), so the merge does not look at the sequence state, and the block of the
+// sequence's first query head then does what is left of kitty_append_token: it stores the new token of every
+// kv-head and advances the state (the flush, if one was due, was done by the streaming kernel).
+__global__ __launch_bounds__(128) void decode_merge_step_kernel(DecodeParams p) {
+  const int hq = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
+  const int g = p.gqa, h = hq / g, hd = hq % g;
+  const float* base = p.ws + (((size_t)b * p.n_kv_heads + h) * p.n_splits) * (size_t)g * WS_STRIDE + (size_t)hd * WS_STRIDE;
+  const size_t slot_stride = (size_t)g * WS_STRIDE;
+  float M = -INFINITY;
+  for (int s = 0; s < p.n_splits; ++s) M = fmaxf(M, base[s * slot_stride + D]);
+  float a = 0.f, L = 0.f;
+  if (M > -INFINITY) {
+    for (int s = 0; s < p.n_splits; ++s) {
+      const float f = __builtin_amdgcn_exp2f(base[s * slot_stride + D] - M);
+      a = fmaf(base[s * slot_stride + d], f, a);
+      L = fmaf(base[s * slot_stride + D + 1], f, L);
+    }
+  }
+  const float o = L > 0.f ? a / L : 0.f;
+  const size_t oi = ((size_t)b * p.n_q_heads + hq) * D + d;
+  if (p.out_dtype == 0) reinterpret_cast<uint16_t*>(p.out)[oi] = f32_to_bf16_rne(o);
+  else reinterpret_cast<float*>(p.out)[oi] = o;
+
+  if (hq != 0) return;
+  // ---- the state before the step, read by this block only
+  const int np_old = page_count(p, b);
+  const int nr_old = min(p.n_resid[b], G);
+  const int ns_old = p.sink_cap ? min(p.n_sink[b], p.sink_cap) : 0;
+  const int32_t pid = p.fresh_page_ids[b];
+  const bool to_sink = ns_old < p.sink_cap;
+  const bool flush = !to_sink && nr_old >= G;
+  const bool ok = !flush || (np_old < p.max_pages && pid >= 0 && pid < p.n_pool_pages);
+  __syncthreads();
+  if (!to_sink && !ok) return;                     // no page for a full window: the token is dropped, as in kitty_append_token
+  const int np_new = np_old + (flush ? 1 : 0);
+  const int row = to_sink ? ns_old : (flush ? 0 : nr_old);
+  for (int i = d; i < p.n_kv_heads * 32; i += 128) {
+    const int hh = i >> 5, part = i & 15, isv = (i >> 4) & 1;
+    const size_t pr = (size_t)b * p.n_kv_heads + hh;
+    const uint4 val = *reinterpret_cast<const uint4*>((isv ? p.v_new : p.k_new) + pr * D + part * 8);
+    uint16_t* dst;
+    if (to_sink) dst = (isv ? p.sink_v_w : p.sink_k_w) + (pr * p.sink_cap + row) * D;
+    else dst = isv ? p.resid_v_w + resid_v_offset(b, hh, p.n_kv_heads, p.v_local, np_new) + (size_t)row * D
+                   : p.resid_k_w + pr * (size_t)(G * D) + (size_t)row * D;
+    *reinterpret_cast<uint4*>(dst + part * 8) = val;
+  }
+  if (d == 0) {
+    if (to_sink) {
+      p.n_sink_w[b] = ns_old + 1;
+    } else {
+      if (flush) {
+        p.page_table_w[(size_t)b * p.max_pages + np_old] = pid;
+        p.n_pages_w[b] = np_old + 1;
+      }
+      p.n_resid_w[b] = flush ? 1 : nr_old + 1;
+    }
+  }
 }
 
 }  // namespace kitty
