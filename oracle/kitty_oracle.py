@@ -28,7 +28,8 @@ Readings taken where the paper is silent (each is listed in the design notes too
     a zero scale gives code 0.
   * ranking: score descending, channel index ascending; boosted channels take slots in
     ascending channel order.  rank_metric 0 = sum_t |x| (Eq. 2 without the rank-irrelevant
-    1/T, accumulated in fp64), rank_metric 1 = fp32(mx - mn).
+    1/T, accumulated in fp64, which is exact under the condition `assert_exact_abs_sum` checks),
+    rank_metric 1 = fp32(mx - mn).
   * token set of Eq. (2) = the G tokens of the page being quantized.
   * byte image of a page record: see `RecordLayout` (the layout is this build's own; the
     paper's logical tensors are recovered from it by `to_paper_tensors`).
@@ -117,9 +118,27 @@ def _asym_quant(x: np.ndarray, mn: np.ndarray, mx: np.ndarray, qmax: np.ndarray)
     return r.astype(np.uint8), scale_h, zero_h
 
 
+def assert_exact_abs_sum(x: np.ndarray) -> None:
+    """The fp64 sum of a channel's |x| must be exact, so that it does not depend on the order of the additions
+    (any reduction tree then gives the same ranking).  bf16 values carry 8 significant bits; the sum of up to
+    2^7 of them whose nonzero magnitudes lie within 38 binades of each other needs at most 38 + 8 + 7 = 53 bits,
+    which is what fp64 holds.  Pages outside that condition are outside what this oracle defines."""
+    a = np.abs(np.asarray(x, dtype=np.float64))
+    if a.shape[0] > 128:
+        raise ValueError("exactness of the channel score is only shown for up to 128 tokens per page")
+    _, e = np.frexp(a)
+    big = np.where(a > 0, e, np.iinfo(np.int32).min).max(axis=0)
+    small = np.where(a > 0, e, np.iinfo(np.int32).max).min(axis=0)
+    span = np.where(big >= small, big.astype(np.int64) - small.astype(np.int64), 0)
+    if np.any(span > 38):
+        raise ValueError("a channel's nonzero magnitudes span more than 38 binades: its fp64 sum of |x| "
+                         "is not guaranteed exact")
+
+
 def channel_scores(x: np.ndarray, rank_metric: int) -> np.ndarray:
     """Importance score of each channel of a page x[G][D] (Eq. 2; or the range variant)."""
     if rank_metric == 0:
+        assert_exact_abs_sum(x)
         return np.abs(x.astype(np.float64)).sum(axis=0)          # sum_t |x|, fp64
     if rank_metric == 1:
         mn = x.min(axis=0).astype(np.float32)
@@ -353,19 +372,23 @@ def to_paper_tensors(rec: np.ndarray, n_boost: int):
 
 
 def dequant_paper_tensors(t2, th, idx, scale, zero, n_boost):
-    """Alg. 1 written out on the paper's tensors: returns K[G][D] fp32."""
+    """K[G][D] (fp32) from the paper's logical page tensors (Sec. 4.1; what Alg. 1 computes).
+
+    Channel by channel: the dense tensor gives every channel's low two bits; a channel whose entry in the index
+    map is a real slot (not the sentinel) adds four times the two bits found in that row of the compact tensor;
+    the resulting integer is mapped back with the channel's scale and zero-point."""
     d, gb = t2.shape
-    g = gb * 4
-    shifts = (2 * (np.arange(g) % 4)).astype(np.uint8)
-    x_low = (np.repeat(t2, 4, axis=1) >> shifts[None, :]) & np.uint8(3)           # (D, G)
-    mask = idx < n_boost
-    x_high = np.zeros((d, g), dtype=np.uint8)
-    if n_boost:
-        rows = np.repeat(th, 4, axis=1)[np.minimum(idx, n_boost - 1).astype(np.int64), :]
-        x_high = np.where(mask[:, None], (rows >> shifts[None, :]) & np.uint8(3), 0).astype(np.uint8)
-    x = (x_low | (x_high << np.uint8(2))).astype(np.float32)
-    k = (x * scale.astype(np.float32)[:, None]).astype(np.float32) + zero.astype(np.float32)[:, None]
-    return k.T
+    k = np.empty((4 * gb, d), dtype=np.float32)
+
+    def fields(row):          # the four 2-bit fields of every byte, lowest bits first: G values in token order
+        return ((row[:, None] >> (2 * np.arange(4, dtype=np.uint8))[None, :]) & np.uint8(3)).reshape(-1).astype(np.int32)
+
+    for c in range(d):
+        code = fields(t2[c])
+        if idx[c] < n_boost:
+            code = code + 4 * fields(th[int(idx[c])])
+        k[:, c] = (code.astype(np.float32) * np.float32(scale[c])).astype(np.float32) + np.float32(zero[c])
+    return k
 
 
 # --------------------------------------------------------------------------------------

@@ -615,3 +615,180 @@ def test_v4_attention_closer_to_exact_than_v2():
         u.prefill(k, v)
         err[bits] = np.abs(u.attention(q, 0.0884)[0] - exact).max()
     assert err[4] < err[2]
+
+
+# ------------------------------------------------------------------ ranking metrics on a page built by hand
+def _metric_page():
+    """Five groups of 16 channels whose order differs under every plausible score:
+                          mean|x|   max-min    max     max|x|    sum x
+      A  0..15  constant +5        5        0        5       5       +640
+      B 16..31  alternating +-6    6       12        6       6          0
+      C 32..47  alternating -7.5/+5.5  6.5  13      5.5     7.5      -128
+      D 48..63  constant -7        7        0       -7       7       -896
+      E 64..79  one token +8, rest 0   1/16  8       8       8         +8
+      rest      alternating +-0.25
+    All values are exact in bf16."""
+    x = np.zeros((128, 128), np.float32)
+    t = np.arange(128)
+    x[:, 80:] = np.where(t % 2 == 0, 0.25, -0.25)[:, None]
+    x[:, 0:16] = 5.0
+    x[:, 16:32] = np.where(t % 2 == 0, 6.0, -6.0)[:, None]
+    x[:, 32:48] = np.where(t % 2 == 0, -7.5, 5.5)[:, None]
+    x[:, 48:64] = -7.0
+    x[:, 64:80] = 0.0
+    x[77, 64:80] = 8.0
+    assert np.array_equal(ko.bf16_bits_to_f32(ko.f32_to_bf16_bits(x)), x)
+    return x
+
+
+A_, B_, C_, D_, E_ = (list(range(16 * i, 16 * i + 16)) for i in range(5))
+
+
+def test_rank_metrics_on_a_hand_built_page():
+    """Eq. (2) ranks by mean |x|; the range variant by max - min.  Expected sets are written out, not computed."""
+    x = _metric_page()
+    # metric 0 (mean |x|): D (7) > C (6.5) > B (6) > A (5)
+    assert ko.quantize_k_page(x, 16, 0).ch.tolist() == D_
+    assert ko.quantize_k_page(x, 32, 0).ch.tolist() == C_ + D_
+    assert ko.quantize_k_page(x, 64, 0).ch.tolist() == A_ + B_ + C_ + D_
+    # metric 1 (max - min): C (13) > B (12) > E (8) > rest (0.5) > A, D (0)
+    assert ko.quantize_k_page(x, 16, 1).ch.tolist() == C_
+    assert ko.quantize_k_page(x, 32, 1).ch.tolist() == B_ + C_
+    assert ko.quantize_k_page(x, 64, 1).ch.tolist() == B_ + C_ + E_ + list(range(80, 96))
+    # the scores themselves, as closed-form values
+    s0, s1 = ko.channel_scores(x, 0), ko.channel_scores(x, 1)
+    assert [s0[c] / 128 for c in (0, 16, 32, 48, 64, 80)] == [5.0, 6.0, 6.5, 7.0, 0.0625, 0.25]
+    assert [s1[c] for c in (0, 16, 32, 48, 64, 80)] == [0.0, 12.0, 13.0, 0.0, 8.0, 0.5]
+    # the channel list that reaches the record is the same list
+    rec = ko.pack_record(ko.quantize_k_page(x, 16, 1), ko.quantize_v_page(x))
+    lay = ko.RecordLayout(16)
+    assert rec[lay.ch_off:lay.ch_off + 16].tolist() == C_
+    with pytest.raises(ValueError):
+        ko.channel_scores(x, 2)
+
+
+# ------------------------------------------------------------------ boosted channels are plain 4-bit channels
+def _check_nearest_level(x, codes, scale_h, zero_h, qmax):
+    """Independent definition of an asymmetric min/max quantizer with 2^b levels, for one group (a Key channel
+    or a Value token): the levels are zero + scale * k, k = 0..qmax; every element must carry the code of the
+    level nearest to it.  Evaluated in fp64, which is exact here: scale has 11 significant bits and k 4, and
+    every term lies within 2^40 of the others.  The oracle works in fp32 (two roundings of relative size 2^-24
+    on a value of at most qmax), so where two levels are almost equally near, either may be taken."""
+    x = x.astype(np.float64)
+    s, z = float(scale_h), float(zero_h)
+    mn, mx = x.min(), x.max()
+    assert z == mn                                             # bf16 inputs in fp16's normal range: exact
+    want = (mx - mn) / qmax
+    assert abs(s - want) <= want * 2.0 ** -11 * (1 + 1e-6)     # nearest fp16 to the quotient
+    if s == 0:
+        assert np.all(codes == 0)
+        return 0
+    dist = np.abs(x[:, None] - (z + s * np.arange(qmax + 1))[None, :])
+    best = dist.min(axis=1)
+    mine = dist[np.arange(len(x)), codes.astype(int)]
+    slack = 1e-5 * s
+    assert np.all(mine - best <= slack)
+    assert codes.max() == qmax and codes.min() == 0            # both ends are reached (min and max of the group)
+    return int(np.sum(codes.astype(int) != dist.argmin(axis=1)))
+
+
+@pytest.mark.parametrize("metric", [0, 1])
+def test_boosted_channels_equal_a_plain_4bit_quantizer(metric):
+    x = page(41)
+    kp = ko.quantize_k_page(x, 16, metric)
+    boosted = set(kp.ch.tolist())
+    off = 0
+    for c in range(128):
+        off += _check_nearest_level(x[:, c], kp.codes[:, c], kp.scale[c], kp.zero[c], 15 if c in boosted else 3)
+    assert off <= 16                                           # exact ties only (bf16 data sits on a coarse grid): < 0.1 %
+    # the same channel quantized on its own, in a page where it is the only boosted one, gets the same codes
+    for c in list(boosted)[:4]:
+        alone = np.zeros_like(x)
+        alone[:, c] = x[:, c]
+        k1 = ko.quantize_k_page(alone, 16, metric)
+        assert c in k1.ch
+        assert np.array_equal(k1.codes[:, c], kp.codes[:, c]) and k1.scale[c] == kp.scale[c] and k1.zero[c] == kp.zero[c]
+
+
+def test_all_channels_boosted_is_a_plain_4bit_page_and_none_is_a_plain_2bit_page():
+    """The two ends of the boost range (the K4V2- and K2V2-like points of Table 2)."""
+    x = page(42)
+    k4 = ko.quantize_k_page(x, 128, 0)
+    assert k4.ch.tolist() == list(range(128))
+    off = sum(_check_nearest_level(x[:, c], k4.codes[:, c], k4.scale[c], k4.zero[c], 15) for c in range(128))
+    assert off <= 16
+    k2 = ko.quantize_k_page(x, 0, 0)
+    assert len(k2.ch) == 0 and k2.hi.max() == 0
+    off = sum(_check_nearest_level(x[:, c], k2.codes[:, c], k2.scale[c], k2.zero[c], 3) for c in range(128))
+    assert off <= 16
+    # records: no boost plane at all without boosted channels (9344 bytes: 4096 + 512 + 128 + 4096 + 512), and a
+    # full second plane of 4096 bytes when every channel is boosted
+    vp = ko.quantize_v_page(page(43, outliers=()))
+    r0, r128 = ko.pack_record(k2, vp), ko.pack_record(k4, vp)
+    l0, l128 = ko.RecordLayout(0), ko.RecordLayout(128)
+    assert len(r0) == 9344 and l0.ks_off == l0.kb_off == 4096
+    assert len(r128) == 9344 + 4096 and l128.ks_off - l128.kb_off == 4096
+    # with every channel boosted the boost plane is the dense plane's layout applied to the high bits in channel order
+    t2, th, idx = ko.to_paper_tensors(r128, 128)
+    assert idx.tolist() == list(range(128)) and th.shape == (128, 32)
+    assert np.array_equal(ko.dequant_paper_tensors(t2, th, idx, k4.scale, k4.zero, 128), ko.dequant_k(k4))
+    # and the 2-bit page dequantizes from the dense tensor alone (every index is the sentinel)
+    t2, th, idx = ko.to_paper_tensors(r0, 0)
+    assert th.shape[0] == 0 and np.all(idx == 0)
+    assert np.array_equal(ko.dequant_paper_tensors(t2, th, idx, k2.scale, k2.zero, 0), ko.dequant_k(k2))
+
+
+def test_value_codes_are_nearest_levels():
+    x = page(44, outliers=())
+    for bits, qmax in ((2, 3), (4, 15)):
+        vp = ko.quantize_v_page(x, bits)
+        off = sum(_check_nearest_level(x[t], vp.codes[t], vp.scale[t], vp.zero[t], qmax) for t in range(128))
+        assert off <= 16
+
+
+def test_alg1_on_paper_tensors_worked_by_hand():
+    """Alg. 1 on a page small enough to do by hand: 2 channels x 4 tokens, channel 1 boosted into slot 0.
+    Dense bytes hold four tokens, first token in the low bits; codes = low + 4 * high; K = code * scale + zero."""
+    t2 = np.array([[0b11_10_01_00], [0b00_01_10_11]], np.uint8)      # channel 0: 0,1,2,3   channel 1: 3,2,1,0
+    th = np.array([[0b01_00_11_10]], np.uint8)                        # slot 0 (channel 1): 2,3,0,1
+    idx = np.array([1, 0], np.uint8)                                  # channel 0 -> sentinel (= n_boost), channel 1 -> slot 0
+    scale = np.array([0.5, 0.25], np.float16)
+    zero = np.array([-1.0, 2.0], np.float16)
+    k = ko.dequant_paper_tensors(t2, th, idx, scale, zero, 1)
+    assert k.shape == (4, 2)
+    assert k[:, 0].tolist() == [-1.0, -0.5, 0.0, 0.5]                 # codes 0,1,2,3
+    assert k[:, 1].tolist() == [2.0 + 0.25 * c for c in (3 + 8, 2 + 12, 1 + 0, 0 + 4)]
+
+
+# ------------------------------------------------------------------ readings: rounding step, exactness of the score
+def test_rounding_step_reading_on_a_constructed_tie():
+    """Channel with min 0 and max 2.8125 at 2 bits: scale = 0.9375 exactly, and x = 2.34375 lies exactly half way
+    between levels 2 and 3.  The reading taken multiplies by fp32(1 / scale) = 1.0666667, which lands just above
+    2.5 and gives 3; dividing would give 2.5 exactly and round to the even code 2.  Both are nearest levels; this
+    pins which one the oracle (and therefore the record) holds.  Apart from such exact ties the two readings agree
+    (counted on workload data by oracle/reading_a5_division_vs_reciprocal.py)."""
+    x = np.zeros((128, 128), np.float32)
+    x[0, 9], x[1, 9], x[2, 9] = 2.8125, 2.34375, 0.9375 * 1.5         # a second tie: 1.5 steps
+    kp = ko.quantize_k_page(x, 0, 0)
+    assert float(kp.scale[9]) == 0.9375 and float(kp.zero[9]) == 0.0
+    assert abs(2.34375 / 0.9375 - 2.5) == 0 and abs(2.34375 - 2 * 0.9375) == abs(2.34375 - 3 * 0.9375)
+    assert int(kp.codes[1, 9]) == 3
+    assert int(kp.codes[2, 9]) == 2                                   # 1.5 -> 1.5000001 -> 2 under both readings
+    assert int(kp.codes[0, 9]) == 3
+
+
+def test_channel_score_refuses_pages_whose_sum_may_be_inexact():
+    x = page(45)
+    ko.assert_exact_abs_sum(x)                                        # ordinary data passes
+    y = x.copy()
+    y[0, 3] = 2.0 ** 30
+    y[1, 3] = 2.0 ** -10                                              # 40 binades apart in one channel
+    with pytest.raises(ValueError):
+        ko.channel_scores(y, 0)
+    ko.channel_scores(y, 1)                                           # the range metric has no such condition
+    z = x.copy()
+    z[0, 3] = 2.0 ** 20                                               # 38 binades or fewer: still exact
+    z[1, 3] = 2.0 ** -17
+    s = ko.channel_scores(z, 0)
+    from fractions import Fraction
+    assert Fraction(float(s[3])) == sum(Fraction(abs(float(v))) for v in z[:, 3])
