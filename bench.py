@@ -112,7 +112,7 @@ def run_c5(args):
     would: fresh id = run base + pages so far, computed on the device once per step."""
     import torch
     from paper_2511_18643_amd import kitty, synth
-    from tests import helpers as H
+    from paper_2511_18643_amd import devcache as H
     dev = "cuda"
     w = synth.WORKLOADS["c5"]
     layers = args.layers or synth.C5_LAYERS
@@ -341,7 +341,7 @@ def main():
         sys.exit(2)
     import torch
     from paper_2511_18643_amd import kitty, synth
-    from tests import helpers as H
+    from paper_2511_18643_amd import devcache as H
 
     kitty.lib()      # fails loudly if libkitty.so is missing
     assert torch.cuda.is_available(), "bench.py needs a GPU"

@@ -41,7 +41,9 @@ typedef struct kitty_layout {
   int32_t n_q_heads;       /* query heads                                                                */
   int32_t n_kv_heads;      /* KV heads; n_q_heads / n_kv_heads must be 1, 2, 4 or 8                      */
   int32_t rank_metric;     /* channel ranking: 0 = mean |x| over the page (Eq. 2), 1 = max - min         */
-  int32_t sink_tokens;     /* S: initial tokens kept in full precision for K and V (Fig. 1, Sec. 3.1): 0..128 */
+  int32_t sink_tokens;     /* S: initial tokens kept in full precision for K and V (Fig. 1, Sec. 3.1): 0..128.  The
+                              paper leaves S free (default 32); this library stops at one page's worth and answers
+                              KITTY_ERR_UNSUPPORTED beyond it                                              */
   int32_t v_local;         /* Value Local window (Fig. 1, Sec. 4.3 step 1): 0 = off, 128 = the Values of the newest
                               page are read in full precision until the next page forms; needs R = 128       */
   int32_t v_bits;          /* bits per Value code: 2 (the method; 0 means 2) or 4 (the K2V4 / K4V4-like points of the
@@ -78,10 +80,15 @@ typedef struct kitty_cache {
  * fp16 scale and zero-point per token. */
 size_t kitty_page_bytes(const kitty_layout* layout /*host*/);
 
-/* Bytes of a record the method has to move (record minus alignment padding).  0 if unsupported. */
+/* Bytes of a record the method has to move (record minus the padding of the channel list): the sizes of the
+ * tensors Sec. 4.1 lists, D*G/4 + n_boost*G/4 code bytes, fp16 scale and zero-point per channel and per token,
+ * and one index byte per boosted channel.  This build's own accounting helper (used by the benchmark for the
+ * algorithmic byte count); no passage of the paper defines it.  0 if unsupported. */
 size_t kitty_page_payload_bytes(const kitty_layout* layout /*host*/);
 
-/* Split plan used by the decode calls.  n_splits_req = 0 picks a plan from the sizes and the
+/* Split plan used by the decode calls (this build's own: the paper runs one unsplit kernel per stage, Sec. 4.3
+ * step 2; splitting the token axis is what fills 256 compute units when there are few (sequence, kv-head)
+ * pairs).  n_splits_req = 0 picks a plan from the sizes and the
  * GPU's compute-unit count; otherwise n_splits_req ranges are used.  On return *n_splits is the
  * number of page ranges per (sequence, kv-head) and *min_pages the fewest pages a range covers:
  * a sequence with np pages uses min(n_splits, max(1, np / min_pages)) ranges of near-equal
@@ -148,14 +155,17 @@ int kitty_decode_attention(const kitty_layout* layout, const kitty_cache* cache,
                            void* out, float sm_scale, int32_t n_splits, int32_t out_dtype,
                            void* workspace, size_t workspace_bytes, void* hip_stream);
 
-/* First half of kitty_decode_attention: every page range (and the window) of every (sequence,
+/* First half of kitty_decode_attention (Sec. 4.3 step 2: the logits, softmax and Value sum of Eq. 1 over the pages
+ * of Sec. 4.1, dequantized as in Alg. 1): every page range (and the window) of every (sequence,
  * kv-head) is reduced to a partial (running max, sum of weights, weighted Value sum) in the
  * workspace.  This is the kernel that streams the cache. */
 int kitty_decode_split(const kitty_layout* layout, const kitty_cache* cache, const void* q,
                        float sm_scale, int32_t n_splits, void* workspace, size_t workspace_bytes,
                        void* hip_stream);
 
-/* Second half: log-sum-exp merge of the partials and the store of `out`. */
+/* Second half: log-sum-exp merge of the partials and the store of `out`.  The merge is the exact identity
+ * softmax(x) = sum_i w_i softmax(x_i) over disjoint chunks x_i of the logits of Eq. 1 (this build's own step; the
+ * paper does not split). */
 int kitty_decode_merge(const kitty_layout* layout, const kitty_cache* cache, void* out,
                        int32_t n_splits, int32_t out_dtype, const void* workspace,
                        size_t workspace_bytes, void* hip_stream);
@@ -173,7 +183,7 @@ int kitty_decode_step(const kitty_layout* layout, const kitty_cache* cache, cons
                       float sm_scale, int32_t n_splits, int32_t out_dtype, void* workspace,
                       size_t workspace_bytes, void* hip_stream);
 
-/* Static description of an error code. */
+/* Static description of an error code (this build's own; no passage of the paper). */
 const char* kitty_strerror(int code);
 
 #ifdef __cplusplus

@@ -398,15 +398,19 @@ int kitty_decode_step(const kitty_layout* L, const kitty_cache* C, const void* k
   if (!k_new || !v_new || !fresh_page_ids || !C->page_pool || !C->page_table) return KITTY_ERR_INVALID_ARG;
   if (reinterpret_cast<uintptr_t>(k_new) % 16 || reinterpret_cast<uintptr_t>(v_new) % 16) return KITTY_ERR_INVALID_ARG;
   if (!out || (out_dtype != 0 && out_dtype != 1) || n_splits < 0) return KITTY_ERR_INVALID_ARG;
+  // Everything either launch could reject is checked here, before the first one: once the streaming kernel is
+  // enqueued (it may flush a window into the fresh page) the merge launch that stores the token and advances the
+  // state must follow.
+  DecodeParams P;
+  rc = fill_decode_params(L, C, n_splits, workspace, workspace_bytes, &P);
+  if (rc) return rc;
+  if (!q || reinterpret_cast<uintptr_t>(q) % 16) return KITTY_ERR_INVALID_ARG;
+  if (L->n_kv_heads > 65535 || C->batch > 65535) return KITTY_ERR_UNSUPPORTED;   // grid limits of both launches
   const StepArgs step{k_new, v_new, fresh_page_ids};
   bool merged = false;
   rc = launch_split(L, C, q, sm_scale, n_splits, workspace, workspace_bytes, out, out_dtype, hip_stream, &merged, &step);
   if (rc || merged) return rc;
   // several ranges: the merge launch also stores the token and advances the state
-  DecodeParams P;
-  rc = fill_decode_params(L, C, n_splits, workspace, workspace_bytes, &P);
-  if (rc) return rc;
-  if (L->n_q_heads > 65535 * 8 || C->batch > 65535) return KITTY_ERR_UNSUPPORTED;
   P.out = out;
   P.out_dtype = out_dtype;
   P.k_new = static_cast<const uint16_t*>(k_new);

@@ -102,6 +102,20 @@ def _check(rc: int, where: str) -> None:
         raise KittyError(rc, where)
 
 
+def _out_dtype(layout: KittyLayout, cache: "Cache", out, where: str) -> int:
+    """out_dtype code of an output tensor; anything but contiguous bf16 / fp32 of the full shape is refused here,
+    because the kernels write batch * n_q_heads * D elements of the announced width."""
+    if out.dtype == torch.bfloat16:
+        code = 0
+    elif out.dtype == torch.float32:
+        code = 1
+    else:
+        raise TypeError(f"{where}: out must be a bfloat16 or float32 tensor, not {out.dtype}")
+    if out.numel() != cache.batch * layout.n_q_heads * layout.head_dim or not out.is_contiguous():
+        raise ValueError(f"{where}: out must be a contiguous [batch][n_q_heads][head_dim] tensor")
+    return code
+
+
 def kitty_page_bytes(layout: KittyLayout) -> int:
     return int(lib().kitty_page_bytes(C.byref(layout)))
 
@@ -175,7 +189,7 @@ def kitty_decode_attention(layout: KittyLayout, cache: Cache, q, out, sm_scale: 
                            n_splits: int = 0, stream=None) -> None:
     """out: bf16 or fp32 tensor [batch][n_q_heads][D]; its dtype selects out_dtype."""
     cs = cache.struct()
-    out_dtype = 0 if out.dtype == torch.bfloat16 else 1
+    out_dtype = _out_dtype(layout, cache, out, "kitty_decode_attention")
     rc = lib().kitty_decode_attention(C.byref(layout), C.byref(cs), _ptr(q), _ptr(out), sm_scale, n_splits,
                                       out_dtype, _ptr(workspace), workspace.numel() * workspace.element_size(),
                                       _stream(stream))
@@ -186,7 +200,7 @@ def kitty_decode_step(layout: KittyLayout, cache: Cache, k_new, v_new, fresh_pag
                       workspace, n_splits: int = 0, stream=None) -> None:
     """kitty_append_token + kitty_decode_attention in one call (one launch when the plan has one range)."""
     cs = cache.struct()
-    out_dtype = 0 if out.dtype == torch.bfloat16 else 1
+    out_dtype = _out_dtype(layout, cache, out, "kitty_decode_step")
     rc = lib().kitty_decode_step(C.byref(layout), C.byref(cs), _ptr(k_new), _ptr(v_new), _ptr(fresh_page_ids),
                                  _ptr(q), _ptr(out), sm_scale, n_splits, out_dtype, _ptr(workspace),
                                  workspace.numel() * workspace.element_size(), _stream(stream))
@@ -203,7 +217,7 @@ def kitty_decode_split(layout: KittyLayout, cache: Cache, q, sm_scale: float, wo
 
 def kitty_decode_merge(layout: KittyLayout, cache: Cache, out, workspace, n_splits: int = 0, stream=None) -> None:
     cs = cache.struct()
-    out_dtype = 0 if out.dtype == torch.bfloat16 else 1
+    out_dtype = _out_dtype(layout, cache, out, "kitty_decode_merge")
     rc = lib().kitty_decode_merge(C.byref(layout), C.byref(cs), _ptr(out), n_splits, out_dtype, _ptr(workspace),
                                   workspace.numel() * workspace.element_size(), _stream(stream))
     _check(rc, "kitty_decode_merge")
