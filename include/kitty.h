@@ -183,6 +183,22 @@ int kitty_decode_step(const kitty_layout* layout, const kitty_cache* cache, cons
                       float sm_scale, int32_t n_splits, int32_t out_dtype, void* workspace,
                       size_t workspace_bytes, void* hip_stream);
 
+/* kitty_decode_attention for callers that cannot allocate device memory or hand over a workspace: code running
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and
+ * errors as kitty_decode_attention, except that the partial results of the page ranges go to a fixed array of
+ * KITTY_STATIC_WORKSPACE_BYTES inside the library's device image instead of a caller buffer; every GPU the
+ * library runs on holds its own copy of that array until the process ends.  The call allocates and frees nothing.
+ *   - A plan that needs more than the array holds (kitty_decode_workspace_bytes(layout, batch, max_pages,
+ *     n_splits) > KITTY_STATIC_WORKSPACE_BYTES) is refused with KITTY_ERR_WORKSPACE; nothing is enqueued.
+ *   - All calls on one GPU share that GPU's array: calls that may run concurrently there (different streams,
+ *     different host threads) race on it and must be serialised by the caller.  Nothing in the array needs to
+ *     start at zero (every slot a merge reads was written by the same call), so a call may follow any other.
+ *   - The array's address is looked up on the first call made on each device (not an allocation); if that lookup
+ *     fails the call returns KITTY_ERR_HIP. */
+#define KITTY_STATIC_WORKSPACE_BYTES (4 * 1024 * 1024)
+int kitty_decode_attention_static(const kitty_layout* layout, const kitty_cache* cache, const void* q, void* out,
+                                  float sm_scale, int32_t n_splits, int32_t out_dtype, void* hip_stream);
+
 /* Static description of an error code (this build's own; no passage of the paper). */
 const char* kitty_strerror(int code);
 

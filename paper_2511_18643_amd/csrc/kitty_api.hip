@@ -1,6 +1,7 @@
 // Host side of libkitty: argument validation, split planning and kernel launches (gfx950).
 #include "../../include/kitty.h"
 
+#include <mutex>
 #include <type_traits>
 
 #include "kitty_decode.h"
@@ -170,6 +171,31 @@ int fill_decode_params(const kitty_layout* L, const kitty_cache* C, int32_t n_sp
   return KITTY_OK;
 }
 
+}  // namespace
+
+// ---- workspace of kitty_decode_attention_static: a fixed array in the library's device image -------------------
+// In host code the array's name is only a handle for hipGetSymbolAddress; the address each GPU holds its copy at
+// is looked up once per device (with that device current) and kept, and only that pointer is ever given to a
+// kernel.
+static __device__ __align__(256) float scratch[KITTY_STATIC_WORKSPACE_BYTES / sizeof(float)];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+float* scratch_ptr[MAX_DEVICES];   // device address of `scratch` on each GPU, nullptr until first use there
+std::mutex scratch_mutex;
+
+int static_workspace(float** ws) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return KITTY_ERR_HIP;
+  std::lock_guard<std::mutex> guard(scratch_mutex);
+  if (!scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return KITTY_ERR_HIP;
+    scratch_ptr[dev] = static_cast<float*>(ptr);
+  }
+  *ws = scratch_ptr[dev];
+  return KITTY_OK;
+}
 }  // namespace
 
 extern "C" {
@@ -426,6 +452,24 @@ int kitty_decode_step(const kitty_layout* L, const kitty_cache* C, const void* k
   P.n_sink_w = C->n_sink;
   hipLaunchKernelGGL(decode_merge_step_kernel, dim3(L->n_q_heads, C->batch), dim3(128), 0, static_cast<hipStream_t>(hip_stream), P);
   return launch_status();
+}
+
+int kitty_decode_attention_static(const kitty_layout* L, const kitty_cache* C, const void* q, void* out, float sm_scale,
+                                  int32_t n_splits, int32_t out_dtype, void* hip_stream) {
+  int rc = check_layout(L);
+  if (rc) return rc;
+  rc = check_cache(L, C);
+  if (rc) return rc;
+  if (n_splits < 0 || !q || reinterpret_cast<uintptr_t>(q) % 16 || !out || (out_dtype != 0 && out_dtype != 1))
+    return KITTY_ERR_INVALID_ARG;
+  if (L->n_kv_heads > 65535 || C->batch > 65535) return KITTY_ERR_UNSUPPORTED;
+  const size_t need = kitty_decode_workspace_bytes(L, C->batch, C->max_pages, n_splits);
+  if (need > (size_t)KITTY_STATIC_WORKSPACE_BYTES) return KITTY_ERR_WORKSPACE;
+  float* ws = nullptr;
+  rc = static_workspace(&ws);
+  if (rc) return rc;
+  return kitty_decode_attention(L, C, q, out, sm_scale, n_splits, out_dtype, ws, (size_t)KITTY_STATIC_WORKSPACE_BYTES,
+                                hip_stream);
 }
 
 const char* kitty_strerror(int code) {

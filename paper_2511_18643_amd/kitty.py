@@ -21,8 +21,9 @@ ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = -1, -2, -3, -4
 EXPORTS = (
     "kitty_page_bytes", "kitty_page_payload_bytes", "kitty_decode_plan", "kitty_decode_workspace_bytes",
     "kitty_quantize_pages", "kitty_append_token", "kitty_decode_attention", "kitty_decode_split",
-    "kitty_decode_merge", "kitty_decode_step", "kitty_strerror",
+    "kitty_decode_merge", "kitty_decode_step", "kitty_decode_attention_static", "kitty_strerror",
 )
+STATIC_WORKSPACE_BYTES = 4 * 1024 * 1024
 
 
 class KittyLayout(C.Structure):
@@ -75,6 +76,8 @@ def lib() -> C.CDLL:
         L.kitty_decode_merge.argtypes = [LP, CP, vp, i32, i32, vp, sz, vp]
         L.kitty_decode_step.restype = C.c_int
         L.kitty_decode_step.argtypes = [LP, CP, vp, vp, vp, vp, vp, C.c_float, i32, i32, vp, sz, vp]
+        L.kitty_decode_attention_static.restype = C.c_int
+        L.kitty_decode_attention_static.argtypes = [LP, CP, vp, vp, C.c_float, i32, i32, vp]
         L.kitty_strerror.restype = C.c_char_p
         L.kitty_strerror.argtypes = [C.c_int]
         _lib = L
@@ -194,6 +197,16 @@ def kitty_decode_attention(layout: KittyLayout, cache: Cache, q, out, sm_scale: 
                                       out_dtype, _ptr(workspace), workspace.numel() * workspace.element_size(),
                                       _stream(stream))
     _check(rc, "kitty_decode_attention")
+
+
+def kitty_decode_attention_static(layout: KittyLayout, cache: Cache, q, out, sm_scale: float, n_splits: int = 0,
+                                  stream=None) -> None:
+    """kitty_decode_attention with the library's own fixed workspace (no allocation, no workspace argument)."""
+    cs = cache.struct()
+    out_dtype = _out_dtype(layout, cache, out, "kitty_decode_attention_static")
+    rc = lib().kitty_decode_attention_static(C.byref(layout), C.byref(cs), _ptr(q), _ptr(out), sm_scale, n_splits,
+                                             out_dtype, _stream(stream))
+    _check(rc, "kitty_decode_attention_static")
 
 
 def kitty_decode_step(layout: KittyLayout, cache: Cache, k_new, v_new, fresh_page_ids, q, out, sm_scale: float,
