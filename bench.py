@@ -126,53 +126,18 @@ def run_c5(args):
     payload, rec_bytes = kitty.kitty_page_payload_bytes(layout), kitty.kitty_page_bytes(layout)
     lengths = synth.sequence_lengths(w)
     total = args.warmup + steps
-    np0 = [(n - S + 127) // 128 - 1 for n in lengths]            # the first S tokens sit in the Sink
-    r0 = [n - S - 128 * p for n, p in zip(lengths, np0)]
-    np_end = [(n - S + total + 127) // 128 - 1 for n in lengths]
-    max_pages = max(np_end) + 1
-    base = np.concatenate([[0], np.cumsum([p + 1 for p in np_end])]).astype(np.int64)   # one spare page per run
-    n_pool = int(base[-1])
+    plan = H.VarLenPlan(lengths, total, S)
+    np0, r0, max_pages, base, n_pool = plan.np0, plan.r0, plan.max_pages, plan.base, plan.n_pool
 
     t0 = time.time()
     nsrc = 2
     Ls = max(lengths) + 128 * layers
-    ksrc = np.zeros((nsrc, hkv, Ls, 128), np.uint16)
-    vsrc = np.zeros_like(ksrc)
-    for sb in range(nsrc):
-        for h in range(hkv):
-            ksrc[sb, h], vsrc[sb, h] = synth.kv_block(w, sb, h, Ls)
+    ksrc, vsrc = H.varlen_sources(w, nsrc, Ls)
     kt, vt = H.bf16_tensor(ksrc, dev), H.bf16_tensor(vsrc, dev)
     gen_s = time.time() - t0
 
     tq0 = time.time()
-    ids = torch.tensor([base[b] + i for b in range(B) for i in range(np0[b])], dtype=torch.int32, device=dev)
-    pt = torch.zeros((B, max_pages), dtype=torch.int32)
-    for b in range(B):
-        pt[b, :np0[b]] = torch.arange(np0[b], dtype=torch.int32) + int(base[b])
-    caches = []
-    for layer in range(layers):
-        c = kitty.Cache(layout, B, max_pages, n_pool, device=dev)
-        offs = torch.tensor([(b % nsrc) * hkv * Ls * 128 + (S + (layer + i) * 128) * 128 for b in range(B) for i in range(np0[b])],
-                            dtype=torch.int64, device=dev)
-        kitty.kitty_quantize_pages(layout, kt, vt, 128 * 128, Ls * 128, 128, ids, ids.numel(), c.pool, n_pool,
-                                   src_page_offsets=offs)
-        c.page_table.copy_(pt)
-        c.n_pages.copy_(torch.tensor(np0, dtype=torch.int32))
-        c.n_resid.copy_(torch.tensor(r0, dtype=torch.int32))
-        for b in range(B):
-            a = S + (layer + np0[b]) * 128
-            c.resid_k[b, :, :r0[b]] = kt[b % nsrc, :, a:a + r0[b]]
-            if VL:      # the window's half, and the bf16 Value rows of the newest page in the other half
-                c.resid_v[b, :, np0[b] & 1, :r0[b]] = vt[b % nsrc, :, a:a + r0[b]]
-                c.resid_v[b, :, (np0[b] - 1) & 1] = vt[b % nsrc, :, a - 128:a]
-            else:
-                c.resid_v[b, :, :r0[b]] = vt[b % nsrc, :, a:a + r0[b]]
-            if S:
-                c.sink_k[b] = kt[b % nsrc, :, :S]
-                c.sink_v[b] = vt[b % nsrc, :, :S]
-        if S:
-            c.n_sink.fill_(S)
-        caches.append(c)
+    caches = [H.varlen_layer_cache(layout, w, plan, kt, vt, layer, S, VL, dev) for layer in range(layers)]
     # dispatch order: longest sequences first (every sequence grows by one token per step, so the order holds)
     if not args.no_seq_order:
         order = torch.argsort(caches[0].n_pages * 128 + caches[0].n_resid, descending=True).to(torch.int32)

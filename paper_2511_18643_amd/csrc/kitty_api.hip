@@ -373,8 +373,15 @@ int launch_split(const kitty_layout* L, const kitty_cache* C, const void* q, flo
     using F1 = std::integral_constant<int, 1>;   // fused step, one range: the kernel also stores the token and advances the state
     using F2 = std::integral_constant<int, 2>;   // fused step, several ranges: the merge launch does that
     auto pick = [&](auto fu) {
-      if (wide) { if (big) go(I2{}, I8{}, fu); else go(I2{}, I4{}, fu); }
-      else      { if (big) go_rows(fu); else go(I1{}, I4{}, fu); }
+      if (wide) {
+        // (eight-head groups with every channel boosted: 4-wavefront blocks only, one wavefront per SIMD, because
+        // their two-pass contractions need more than 256 registers)
+        if constexpr (NB == 8) go(I2{}, I4{}, fu);
+        else if (big) go(I2{}, I8{}, fu);
+        else go(I2{}, I4{}, fu);
+      } else {
+        if (big) go_rows(fu); else go(I1{}, I4{}, fu);
+      }
     };
     if (!fused) pick(F0{});
     else if (P.direct_out) pick(F1{});

@@ -301,24 +301,34 @@ union __attribute__((aligned(16))) DecodeSmem {
 // 8*(j&1)..8*(j&1)+7, i.e. its first four values have weight 1 and its last four weight 4; it divides its
 // values by that weight before taking the integer image (two bits of the image's precision), and keeps sums
 // and maxima of unweighted values by recombining the two halves.
-// Groups of eight query heads (HPL == 2) carry two terms (16-bit images, plain unpack); see THIRD_PASS.
+// Groups of eight query heads (HPL == 2): see TRK / TRV below.
 template <int NB16, int HPL, bool V4 = false>
 struct PageWorker {
-  // Eight-head groups: a third byte term needs 24 matrix rows, i.e. a second MFMA pass over the same code
-  // operand.  Measured on the 128k-context workload it costs 20 % of the kernel's throughput (the matrix
-  // pipe and the register file become the limiters) for a maximum error of 1e-4 instead of 8e-4 there (up to
-  // 1.4e-3 on short sequences whose outlier channels are not boosted), both within the 2e-3 bound; it is
-  // therefore compiled out.
-  static constexpr bool THIRD_PASS = false;
-  static constexpr int TR = (HPL == 1 || THIRD_PASS) ? 3 : 2;     // byte terms per value
-  // cheap unpack; relies on the precision of three terms (with two-term images it was measured on the Value
-  // side alone: 2.5e-3 instead of 9e-4 maximum error for eight-head groups, and no faster)
-  static constexpr bool WEIGHTED = TR == 3;
+  // Byte terms per value of the two fixed-point images: q*scale on the Key side, p*scale on the Value side.
+  // Four-head groups carry three terms (20-bit images) in 12 of the 16 matrix rows.  Eight-head groups have room
+  // for two terms per head in one matrix (16-bit images); a third term needs 24 rows, i.e. a second MFMA pass over
+  // the same code operand.  On the Key side the 16-bit image is not enough: its step is set by the largest
+  // |q*scale| of a head, and one dominant query element on an outlier channel coarsens the other 127 channels
+  // until the logits are off by 1e-2 (measured: output error up to 1.4e-2 on short contexts, 8e-4 to 1.8e-3 on
+  // ordinary data).  KEY_TERMS_G8 / VALUE_TERMS_G8 choose the terms of the eight-head kernels.
+#ifndef KITTY_G8_KEY_TERMS
+#define KITTY_G8_KEY_TERMS 3
+#endif
+#ifndef KITTY_G8_VALUE_TERMS
+#define KITTY_G8_VALUE_TERMS 3
+#endif
+  static constexpr int TRK = HPL == 1 ? 3 : KITTY_G8_KEY_TERMS;     // byte terms of q*scale
+  static constexpr int TRV = HPL == 1 ? 3 : (V4 ? 2 : KITTY_G8_VALUE_TERMS);   // byte terms of p*scale (4-bit Values: no second pass)
+  // cheap unpack (one shift, four masks; elements 4..7 and 12..15 of a word come out times 4): relies on the
+  // precision of three terms, because the other operand gives up two bits of its image for the inverse weights
+  static constexpr bool WEIGHTED_K = TRK == 3, WEIGHTED_V = TRV == 3;
   // weights of the lane's first and last four values (Key side: channels; Value side: tokens) and their log2
-  static constexpr float wA = 1.f, wB = WEIGHTED ? 4.f : 1.f, oA = 0.f, oB = WEIGHTED ? 2.f : 0.f;
-  static constexpr bool TWO_PASS = HPL == 2 && THIRD_PASS;
-  static_assert(!(V4 && TWO_PASS), "the high Value plane has no second-pass accumulator");
-  static constexpr float NLIM = TR == 3 ? 1048000.0f : 32000.0f;   // bound of the integer images
+  static constexpr float wKA = 1.f, wKB = WEIGHTED_K ? 4.f : 1.f;
+  static constexpr float wVA = 1.f, wVB = WEIGHTED_V ? 4.f : 1.f, oVA = 0.f, oVB = WEIGHTED_V ? 2.f : 0.f;
+  static constexpr bool TWO_PASS_K = HPL == 2 && TRK == 3, TWO_PASS_V = HPL == 2 && TRV == 3;
+  static_assert(!(V4 && TWO_PASS_V), "the high Value plane has no second-pass accumulator");
+  static constexpr float NLIM_K = TRK == 3 ? 1048000.0f : 32000.0f;   // bound of the integer images
+  static constexpr float NLIM_V = TRV == 3 ? 1048000.0f : 32000.0f;
 
   // Matrix row of term t of head hd.  Four heads: rows 4hd + t of one matrix.  Eight heads: terms 0, 1 in
   // rows 2hd + t of the first matrix, term 2 in row 4(hd/2) + hd%2 of a second matrix (rows 16..31) that a
@@ -362,13 +372,14 @@ struct PageWorker {
     const uint32_t rw[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-      const float inv_w = 1.0f / (2 * k < 4 ? wA : wB);
+      const float inv_w = 1.0f / (2 * k < 4 ? wKA : wKB);
       qv[e][2 * k] = live ? __uint_as_float(rw[k] << 16) * scale * inv_w : 0.f;
       qv[e][2 * k + 1] = live ? __uint_as_float(rw[k] & 0xffff0000u) * scale * inv_w : 0.f;
     }
   }
 
-  __device__ __forceinline__ v4i unpack(uint32_t w) const { return WEIGHTED ? unpack16_w(w) : unpack16(w); }
+  __device__ __forceinline__ v4i unpack_k(uint32_t w) const { return WEIGHTED_K ? unpack16_w(w) : unpack16(w); }
+  __device__ __forceinline__ v4i unpack_v(uint32_t w) const { return WEIGHTED_V ? unpack16_w(w) : unpack16(w); }
 
   // stage a page's fp16 arrays in LDS (each lane group holds one of the four)
   __device__ __forceinline__ void stage_meta(const uint4& meta) {
@@ -376,8 +387,9 @@ struct PageWorker {
   }
 
   // Phases A-C: integer logits of the 128 tokens of the page in `pg` (k_scale, k_zero staged in LDS).
-  // The logit of head gi*HPL + e and token 16T + j is inv_alpha[e] * join(dq[T]...) + bias[e] (log2 domain).
-  __device__ __forceinline__ void logits(const PageRegs<NB16, V4>& pg, v4i (&dq)[8], v4i (&dqx)[TWO_PASS ? 8 : 1],
+  // The logit of head gi*HPL + e and token 16T + j is inv_alpha[e] * nl[e][T] + bias[e] (log2 domain).  The byte
+  // terms are joined here, tile by tile, so that only one integer per (head, tile) lives on into the softmax.
+  __device__ __forceinline__ void logits(const PageRegs<NB16, V4>& pg, int (&nl)[HPL][8],
                                          float (&inv_alpha)[HPL], float (&bias)[HPL]) {
     // ================= A: integer image of q*s, bias q.z =================
     float ks[8], kz[8];
@@ -395,19 +407,19 @@ struct PageWorker {
         bsA = fmaf(qv[e][k], kz[k], bsA);
         bsB = fmaf(qv[e][k + 4], kz[k + 4], bsB);
       }
-      float amax = fmaxf(amaxA * wA, amaxB * wB), bsum = fmaf(bsA, wA, bsB * wB);   // wA = wB = 1 if not WEIGHTED
+      float amax = fmaxf(amaxA * wKA, amaxB * wKB), bsum = fmaf(bsA, wKA, bsB * wKB);   // both weights are 1 with the plain unpack
       amax = fmaxf(row_max_nonneg(amax), 1e-30f);
       bias[e] = row_sum(bsum);
-      const float alpha = NLIM * __builtin_amdgcn_rcpf(amax);
-      inv_alpha[e] = amax * (1.0f / NLIM);
+      const float alpha = NLIM_K * __builtin_amdgcn_rcpf(amax);
+      inv_alpha[e] = amax * (1.0f / NLIM_K);
       uint32_t u[8];
 #pragma unroll
       for (int k = 0; k < 8; ++k) u[k] = __float_as_uint(fmaf(qs[k], alpha, MAGIC));
-      uint2 tw[TR];
-      split_terms<TR>(u, tw);
+      uint2 tw[TRK];
+      split_terms<TRK>(u, tw);
       const int hd = gi * HPL + e;
 #pragma unroll
-      for (int t = 0; t < TR; ++t) *reinterpret_cast<uint2*>(&ws.abuf[term_row(hd, t)][8 * j]) = tw[t];
+      for (int t = 0; t < TRK; ++t) *reinterpret_cast<uint2*>(&ws.abuf[term_row(hd, t)][8 * j]) = tw[t];
       if constexpr (NB16 > 0) {
         *reinterpret_cast<uint4*>(&ws.nbuf[hd][8 * j]) = make_uint4(u[0], u[1], u[2], u[3]);
         *reinterpret_cast<uint4*>(&ws.nbuf[hd][8 * j + 4]) = make_uint4(u[4], u[5], u[6], u[7]);
@@ -420,7 +432,7 @@ struct PageWorker {
       for (int s = 0; s < NB16; ++s) {
         const uint32_t ch = pg.chv[s];
         // weight the dense plane applies to this channel: 1, 4, 1, 4 for elements 0-3, 4-7, 8-11, 12-15
-        const uint32_t sh = WEIGHTED ? ((ch >> 1) & 2u) : 0u;
+        const uint32_t sh = WEIGHTED_K ? ((ch >> 1) & 2u) : 0u;
 #pragma unroll
         for (int e = 0; e < HPL; ++e) {
           const int hd = gi * HPL + e;
@@ -428,76 +440,86 @@ struct PageWorker {
           nn = ((nn - 0x4b400000u) << sh) + 0x4b400000u;   // undo the division: exact multiple
           ws.bbuf[term_row(hd, 0)][16 * s + j] = (uint8_t)nn;
           ws.bbuf[term_row(hd, 1)][16 * s + j] = (uint8_t)((nn + T1_ADD) >> 8);
-          if constexpr (TR == 3) ws.bbuf[term_row(hd, 2)][16 * s + j] = (uint8_t)((nn + T2_ADD) >> 16);
+          if constexpr (TRK == 3) ws.bbuf[term_row(hd, 2)][16 * s + j] = (uint8_t)((nn + T2_ADD) >> 16);
         }
       }
       wave_lds_fence();
     }
     // ================= C: logits for 128 tokens x heads on the int8 matrix cores =================
+    // Two halves of four token tiles each (dense plane, then the boost plane's contribution to the same tiles,
+    // then the join of the byte terms), so that at most four tiles' accumulators are alive at a time.
     const v4i a0 = *reinterpret_cast<const v4i*>(a_ptr);
     const v4i a1 = *reinterpret_cast<const v4i*>(a_ptr + 64);
     v4i a0x = {0, 0, 0, 0}, a1x = {0, 0, 0, 0};
-    if constexpr (TWO_PASS) {
+    if constexpr (TWO_PASS_K) {
       a0x = *reinterpret_cast<const v4i*>(a_ptr + A_PASS);
       a1x = *reinterpret_cast<const v4i*>(a_ptr + A_PASS + 64);
     }
 #pragma unroll
-    for (int T = 0; T < 8; ++T) {
-      const uint4 ld = pg.kd[T >> 1];
-      const uint32_t w0 = (T & 1) ? ld.z : ld.x, w1 = (T & 1) ? ld.w : ld.y;
-      const v4i b0 = unpack(w0), b1 = unpack(w1);
-      v4i c = {0, 0, 0, 0};
-      c = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0, b0, c, 0, 0, 0);
-      c = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1, b1, c, 0, 0, 0);
-      dq[T] = c;
-      if constexpr (TWO_PASS) {
-        v4i cx = {0, 0, 0, 0};
-        cx = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0x, b0, cx, 0, 0, 0);
-        cx = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1x, b1, cx, 0, 0, 0);
-        dqx[T] = cx;
-      }
-    }
-    if constexpr (NB16 > 0) {
+    for (int u = 0; u < 2; ++u) {
+      v4i dq[4], dqx[TWO_PASS_K ? 4 : 1];
 #pragma unroll
-      for (int s = 0; s < NB16; ++s) {
-        // tile 4u+kb of the boost plane lives in the lanes of k-block kb: feed A only to that block
-        v4i ab[4], abx[TWO_PASS ? 4 : 1];
-#pragma unroll
-        for (int kb = 0; kb < 4; ++kb) {
-          ab[kb] = *reinterpret_cast<const v4i*>(b_ptr[kb] + (gi == kb ? 16 * s : 0));
-          if constexpr (TWO_PASS) abx[kb] = *reinterpret_cast<const v4i*>(b_ptr[kb] + (gi == kb ? B_PASS + 16 * s : 0));
+      for (int t = 0; t < 4; ++t) {
+        const int T = 4 * u + t;
+        const uint4 ld = pg.kd[T >> 1];
+        const uint32_t w0 = (T & 1) ? ld.z : ld.x, w1 = (T & 1) ? ld.w : ld.y;
+        const v4i b0 = unpack_k(w0), b1 = unpack_k(w1);
+        v4i c = {0, 0, 0, 0};
+        c = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0, b0, c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1, b1, c, 0, 0, 0);
+        dq[t] = c;
+        if constexpr (TWO_PASS_K) {
+          v4i cx = {0, 0, 0, 0};
+          cx = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0x, b0, cx, 0, 0, 0);
+          cx = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1x, b1, cx, 0, 0, 0);
+          dqx[t] = cx;
         }
+      }
+      if constexpr (NB16 > 0) {
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
+        for (int s = 0; s < NB16; ++s) {
+          // tile 4u+kb of the boost plane lives in the lanes of k-block kb: feed A only to that block
           const v4i bb = unpack16_x4(u ? pg.kb[s].y : pg.kb[s].x);
 #pragma unroll
           for (int kb = 0; kb < 4; ++kb) {
-            dq[4 * u + kb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ab[kb], bb, dq[4 * u + kb], 0, 0, 0);
-            if constexpr (TWO_PASS)
-              dqx[4 * u + kb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(abx[kb], bb, dqx[4 * u + kb], 0, 0, 0);
+            const v4i ab = *reinterpret_cast<const v4i*>(b_ptr[kb] + (gi == kb ? 16 * s : 0));
+            dq[kb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ab, bb, dq[kb], 0, 0, 0);
+            if constexpr (TWO_PASS_K) {
+              const v4i abx = *reinterpret_cast<const v4i*>(b_ptr[kb] + (gi == kb ? B_PASS + 16 * s : 0));
+              dqx[kb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(abx, bb, dqx[kb], 0, 0, 0);
+            }
           }
         }
       }
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int e = 0; e < HPL; ++e) nl[e][4 * u + t] = joined_k(dq[t], dqx[TWO_PASS_K ? t : 0], e);
     }
   }
 
-  __device__ __forceinline__ int joined(const v4i& c, const v4i& cx, int e) const {
+  __device__ __forceinline__ int joined_k(const v4i& c, const v4i& cx, int e) const {
     if constexpr (HPL == 1) return join_terms(c[0], c[1], c[2]);
-    else if constexpr (TWO_PASS) return join_terms(c[2 * e], c[2 * e + 1], cx[e]);
+    else if constexpr (TWO_PASS_K) return join_terms(c[2 * e], c[2 * e + 1], cx[e]);
+    else return join_terms(c[2 * e], c[2 * e + 1]);
+  }
+  __device__ __forceinline__ int joined_v(const v4i& c, const v4i& cx, int e) const {
+    if constexpr (HPL == 1) return join_terms(c[0], c[1], c[2]);
+    else if constexpr (TWO_PASS_V) return join_terms(c[2 * e], c[2 * e + 1], cx[e]);
     else return join_terms(c[2 * e], c[2 * e + 1]);
   }
 
   // Logits only (log2 domain, float) of the page in `pg`, stored as x[token][head]: used for the newest page
   // when its Values are still read in full precision (they are then handled with the other bf16 rows).
   __device__ __forceinline__ void logits_to(const PageRegs<NB16, V4>& pg, float (*x)[4 * HPL]) {
-    v4i dq[8], dqx[TWO_PASS ? 8 : 1];
+    int nl[HPL][8];
     float inv_alpha[HPL], bias[HPL];
-    logits(pg, dq, dqx, inv_alpha, bias);
+    logits(pg, nl, inv_alpha, bias);
 #pragma unroll
     for (int e = 0; e < HPL; ++e)
 #pragma unroll
       for (int T = 0; T < 8; ++T)
-        x[16 * T + j][gi * HPL + e] = fmaf((float)joined(dq[T], dqx[TWO_PASS ? T : 0], e), inv_alpha[e], bias[e]);
+        x[16 * T + j][gi * HPL + e] = fmaf((float)nl[e][T], inv_alpha[e], bias[e]);
   }
 
   // Processes the page held in `pg` (its fp16 arrays already staged in LDS).  The pieces of the wavefront's
@@ -506,9 +528,9 @@ struct PageWorker {
   __device__ __forceinline__ void process(PageRegs<NB16, V4>& pg, RecRef rec_nx, bool has_nx) {
     uint4 meta_nx = make_uint4(0, 0, 0, 0);
     if (has_nx) meta_nx = load_meta<NB16>(rec_nx, lo);
-    v4i dq[8], dqx[TWO_PASS ? 8 : 1];
+    int nlg[HPL][8];
     float inv_alpha[HPL], bias[HPL];
-    logits(pg, dq, dqx, inv_alpha, bias);
+    logits(pg, nlg, inv_alpha, bias);
     if (has_nx) load_k<NB16, V4>(pg, rec_nx, lo);   // the Key planes of this page are in the matrix pipeline now
     // ================= D: online softmax; lane (j, gi) owns token 16T + j of heads gi*HPL + e ==========
     float vs[8], vz[8];
@@ -521,9 +543,7 @@ struct PageWorker {
       int nl[8], mxi = INT_MIN;
 #pragma unroll
       for (int T = 0; T < 8; ++T) {
-        if constexpr (HPL == 1) nl[T] = join_terms(dq[T][0], dq[T][1], dq[T][2]);
-        else if constexpr (TWO_PASS) nl[T] = join_terms(dq[T][2 * e], dq[T][2 * e + 1], dqx[T][e]);
-        else nl[T] = join_terms(dq[T][2 * e], dq[T][2 * e + 1]);
+        nl[T] = nlg[e][T];
         mxi = max(mxi, nl[T]);
       }
       mxi = row_max_i32(mxi);
@@ -531,7 +551,7 @@ struct PageWorker {
       corr[e] = __builtin_amdgcn_exp2f(m_run[e] - m_new);
       m_run[e] = m_new;
       // the weights of the Value-side unpack are taken out of p through the exponent
-      const float cA = bias[e] - (m_new + oA), cB = bias[e] - (m_new + oB);
+      const float cA = bias[e] - (m_new + oVA), cB = bias[e] - (m_new + oVB);
       float ps[8], psA = 0.f, psB = 0.f, zsA = 0.f, zsB = 0.f, pmA = 0.f, pmB = 0.f;
 #pragma unroll
       for (int T = 0; T < 4; ++T) {
@@ -542,30 +562,30 @@ struct PageWorker {
         ps[T] = pa * vs[T]; ps[T + 4] = pb * vs[T + 4];
         pmA = fmaxf(pmA, ps[T]); pmB = fmaxf(pmB, ps[T + 4]);
       }
-      float psum = fmaf(psA, wA, psB * wB), zsum = fmaf(zsA, wA, zsB * wB), pmax = fmaxf(pmA * wA, pmB * wB);
+      float psum = fmaf(psA, wVA, psB * wVB), zsum = fmaf(zsA, wVA, zsB * wVB), pmax = fmaxf(pmA * wVA, pmB * wVB);
       l_run[e] = fmaf(l_run[e], corr[e], psum);     // (corr comes out of v_exp: not for fma_in_place)
       z_run[e] = fmaf(z_run[e], corr[e], zsum);
-      // (the floor keeps the running sums, which are held in units of pmax / NLIM, far from overflow; a page
+      // (the floor keeps the running sums, which are held in units of pmax / NLIM_V, far from overflow; a page
       // whose weights are all below it contributes less than 1e-12 of the total)
       pmax = fmaxf(row_max_nonneg(pmax), 1e-12f);
-      const float beta = NLIM * __builtin_amdgcn_rcpf(pmax);
+      const float beta = NLIM_V * __builtin_amdgcn_rcpf(pmax);
       rescale[e] = corr[e] * acc_unit[e] * beta;       // old unit -> new unit, and the softmax correction
-      acc_unit[e] = pmax * (1.0f / NLIM);
+      acc_unit[e] = pmax * (1.0f / NLIM_V);
       uint32_t u[8];
 #pragma unroll
       for (int T = 0; T < 8; ++T) u[T] = __float_as_uint(fmaf(ps[T], beta, MAGIC));
-      uint2 tw[TR];
-      split_terms<TR>(u, tw);
+      uint2 tw[TRV];
+      split_terms<TRV>(u, tw);
       const int hd = gi * HPL + e;
 #pragma unroll
-      for (int t = 0; t < TR; ++t) *reinterpret_cast<uint2*>(&ws.pbuf[term_row(hd, t)][8 * j]) = tw[t];
+      for (int t = 0; t < TRV; ++t) *reinterpret_cast<uint2*>(&ws.pbuf[term_row(hd, t)][8 * j]) = tw[t];
     }
     wave_lds_fence();
     // ================= E: weighted Value sum on the int8 matrix cores =================
     const v4i pa0 = *reinterpret_cast<const v4i*>(p_ptr);
     const v4i pa1 = *reinterpret_cast<const v4i*>(p_ptr + 64);
     v4i pa0x = {0, 0, 0, 0}, pa1x = {0, 0, 0, 0};
-    if constexpr (TWO_PASS) {
+    if constexpr (TWO_PASS_V) {
       pa0x = *reinterpret_cast<const v4i*>(p_ptr + A_PASS);
       pa1x = *reinterpret_cast<const v4i*>(p_ptr + A_PASS + 64);
     }
@@ -573,24 +593,24 @@ struct PageWorker {
     for (int Td = 0; Td < 8; ++Td) {
       const uint4 ld = pg.vd[Td >> 1];
       const uint32_t w0 = (Td & 1) ? ld.z : ld.x, w1 = (Td & 1) ? ld.w : ld.y;
-      const v4i b0 = unpack(w0), b1 = unpack(w1);
+      const v4i b0 = unpack_v(w0), b1 = unpack_v(w1);
       v4i c = {0, 0, 0, 0}, cx = {0, 0, 0, 0}, chi = {0, 0, 0, 0};
       c = __builtin_amdgcn_mfma_i32_16x16x64_i8(pa0, b0, c, 0, 0, 0);
       c = __builtin_amdgcn_mfma_i32_16x16x64_i8(pa1, b1, c, 0, 0, 0);
       if constexpr (V4) {   // the high two bits of 4-bit Values: same contraction, weight 4
         const uint4 lh = pg.vh[Td >> 1];
-        const v4i h0 = unpack((Td & 1) ? lh.z : lh.x), h1 = unpack((Td & 1) ? lh.w : lh.y);
+        const v4i h0 = unpack_v((Td & 1) ? lh.z : lh.x), h1 = unpack_v((Td & 1) ? lh.w : lh.y);
         chi = __builtin_amdgcn_mfma_i32_16x16x64_i8(pa0, h0, chi, 0, 0, 0);
         chi = __builtin_amdgcn_mfma_i32_16x16x64_i8(pa1, h1, chi, 0, 0, 0);
       }
-      if constexpr (TWO_PASS) {
+      if constexpr (TWO_PASS_V) {
         cx = __builtin_amdgcn_mfma_i32_16x16x64_i8(pa0x, b0, cx, 0, 0, 0);
         cx = __builtin_amdgcn_mfma_i32_16x16x64_i8(pa1x, b1, cx, 0, 0, 0);
       }
 #pragma unroll
       for (int e = 0; e < HPL; ++e) {
-        int ne = joined(c, cx, e);
-        if constexpr (V4) ne += 4 * joined(chi, cx, e);
+        int ne = joined_v(c, cx, e);
+        if constexpr (V4) ne += 4 * joined_v(chi, cx, e);
         fma_in_place(acc[e][Td], rescale[e], (float)ne);
       }
     }
@@ -607,8 +627,10 @@ struct PageWorker {
 // Block = NW wavefronts (4 or 8); wavefront w takes pages p0+w, p0+w+NW, ... of the range and a slice of
 // the range's share of the rows held in full precision (Sink, window).
 // wavefronts per SIMD the kernel is compiled for (register budget 512 / n)
+// (eight-head groups with every channel boosted need more than 256 registers for their two-pass contractions:
+// they run in 4-wavefront blocks with one wavefront per SIMD)
 template <int NB16, int HPL>
-constexpr int decode_waves_per_simd() { return 2; }
+constexpr int decode_waves_per_simd() { return (HPL == 2 && NB16 == 8) ? 1 : 2; }
 
 // FUSED: the block first performs this (sequence, kv-head)'s share of kitty_append_token (flush a full window
 // into the fresh page, store the new token), then attends over the result; needs one range per (sequence,

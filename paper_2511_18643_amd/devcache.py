@@ -126,3 +126,70 @@ def gpu_full_cache(w, lengths, k, v, max_pages, sink, v_local, poison=True, v_bi
                                    src_page_offsets=torch.tensor(offs, dtype=torch.int64, device="cuda"))
     torch.cuda.synchronize()
     return layout, c
+
+
+# ---------------------------------------------------------------------------------------------------
+# Variable-length batch of the 36-layer decode loop: one cache per layer, page ids handed out per sequence
+# from a contiguous run (as a serving engine's allocator would)
+# ---------------------------------------------------------------------------------------------------
+class VarLenPlan:
+    """Page bookkeeping of a variable-length batch that will run `total_steps` decode steps: pages and window
+    rows of every sequence at the start, row length of the page table, the first page id of every sequence's
+    run (one spare page per run) and the pool size."""
+
+    def __init__(self, lengths, total_steps, sink=0):
+        self.lengths = list(lengths)
+        self.np0 = [(n - sink + 127) // 128 - 1 for n in lengths]           # the first `sink` tokens sit in the Sink
+        self.r0 = [n - sink - 128 * p for n, p in zip(lengths, self.np0)]
+        np_end = [(n - sink + total_steps + 127) // 128 - 1 for n in lengths]
+        self.max_pages = max(np_end) + 1
+        self.base = np.concatenate([[0], np.cumsum([p + 1 for p in np_end])]).astype(np.int64)
+        self.n_pool = int(self.base[-1])
+
+
+def varlen_sources(w, n_src, n_tokens):
+    """bf16 bits [n_src][Hkv][n_tokens][D] of K and V: the distinct synthetic sequences a batch is tiled from."""
+    ksrc = np.zeros((n_src, w.n_kv_heads, n_tokens, 128), np.uint16)
+    vsrc = np.zeros_like(ksrc)
+    for sb in range(n_src):
+        for h in range(w.n_kv_heads):
+            ksrc[sb, h], vsrc[sb, h] = synth.kv_block(w, sb, h, n_tokens)
+    return ksrc, vsrc
+
+
+def varlen_layer_cache(layout, w, plan, kt, vt, layer, sink=0, v_local=0, device="cuda"):
+    """Cache of one layer: sequence b holds tokens [128*layer, 128*layer + length) of source sequence b % n_src
+    (kt, vt: bf16 tensors [n_src][Hkv][Ls][D] on the device), prefilled through kitty_quantize_pages."""
+    import torch
+    from . import kitty
+    B, hkv = w.batch, w.n_kv_heads
+    nsrc, Ls = kt.shape[0], kt.shape[2]
+    S, VL = sink, v_local
+    c = kitty.Cache(layout, B, plan.max_pages, plan.n_pool, device=device)
+    ids = torch.tensor([plan.base[b] + i for b in range(B) for i in range(plan.np0[b])], dtype=torch.int32, device=device)
+    offs = torch.tensor([(b % nsrc) * hkv * Ls * 128 + (S + (layer + i) * 128) * 128 for b in range(B) for i in range(plan.np0[b])],
+                        dtype=torch.int64, device=device)
+    if ids.numel():
+        kitty.kitty_quantize_pages(layout, kt, vt, 128 * 128, Ls * 128, 128, ids, ids.numel(), c.pool, plan.n_pool,
+                                   src_page_offsets=offs)
+    pt = torch.zeros((B, plan.max_pages), dtype=torch.int32)
+    for b in range(B):
+        pt[b, :plan.np0[b]] = torch.arange(plan.np0[b], dtype=torch.int32) + int(plan.base[b])
+    c.page_table.copy_(pt)
+    c.n_pages.copy_(torch.tensor(plan.np0, dtype=torch.int32))
+    c.n_resid.copy_(torch.tensor(plan.r0, dtype=torch.int32))
+    for b in range(B):
+        a = S + (layer + plan.np0[b]) * 128
+        r = plan.r0[b]
+        c.resid_k[b, :, :r] = kt[b % nsrc, :, a:a + r]
+        if VL:      # the window's half, and the bf16 Value rows of the newest page in the other half
+            c.resid_v[b, :, plan.np0[b] & 1, :r] = vt[b % nsrc, :, a:a + r]
+            c.resid_v[b, :, (plan.np0[b] - 1) & 1] = vt[b % nsrc, :, a - 128:a]
+        else:
+            c.resid_v[b, :, :r] = vt[b % nsrc, :, a:a + r]
+        if S:
+            c.sink_k[b] = kt[b % nsrc, :, :S]
+            c.sink_v[b] = vt[b % nsrc, :, :S]
+    if S:
+        c.n_sink.fill_(S)
+    return c

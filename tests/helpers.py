@@ -5,8 +5,8 @@ from __future__ import annotations
 import numpy as np
 
 from oracle import kitty_oracle as ko
-from paper_2511_18643_amd.devcache import (bf16_tensor, gen_sequences, gpu_cache, gpu_decode,  # noqa: F401
-                                           gpu_full_cache)
+from paper_2511_18643_amd.devcache import (VarLenPlan, bf16_tensor, gen_sequences, gpu_cache,  # noqa: F401
+                                           gpu_decode, gpu_full_cache, varlen_layer_cache, varlen_sources)
 
 
 def oracle_cache(w, lengths, k, v, max_pages, v_bits=2):
