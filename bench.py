@@ -58,6 +58,8 @@ def parse():
                     help="128: Values of the newest page are read from the bf16 Local window")
     ap.add_argument("--no-seq-order", action="store_true", help="c5 only: dispatch sequences in batch order instead of longest first")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-others", action="store_true",
+                    help="default run only: leave out the summary of the other workloads (c2, c4, c5)")
     ap.add_argument("--cpu-pairs", type=int, default=0, help="(sequence, kv-head) pairs in the oracle sample (0 = auto)")
     return ap.parse_args()
 
@@ -72,15 +74,24 @@ def step_bytes(payload, n_pages, n_resid, w, sink=0, v_local=0):
 
 
 def recorded_traffic(workload):
-    """HBM bytes per decode_split launch from the committed rocprofv3 counter summary (None if absent)."""
-    path = os.path.join(ROOT, "profiles", f"decode_split_{workload}_traffic.txt")
+    """HBM bytes per decode_split launch as the committed rocprofv3 counter summary of this workload holds them
+    (two --pmc runs of this command, FETCH_SIZE then WRITE_SIZE, scaled by a plain copy of known size).  It is a
+    recorded figure, not one measured in the present run (counters need the profiler), so it comes with its
+    source and with the algorithmic bytes of the run it was taken in."""
+    rel = f"profiles/decode_split_{workload}_traffic.txt"
+    got = {}
     try:
-        for line in open(path):
-            if line.startswith("traffic_bytes_per_launch"):
-                return int(float(line.split("=")[1]))
+        for line in open(os.path.join(ROOT, rel)):
+            for key in ("traffic_bytes_per_launch", "algorithmic_bytes_per_launch"):
+                if line.startswith(key):
+                    got[key] = int(float(line.split("=")[1].split()[0]))
     except OSError:
         pass
-    return None
+    if "traffic_bytes_per_launch" not in got:
+        return {"traffic": None}
+    return {"traffic": got["traffic_bytes_per_launch"],
+            "traffic_source": f"recorded in {rel} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command), not measured in this run",
+            "traffic_run_algorithmic_bytes": got.get("algorithmic_bytes_per_launch")}
 
 
 def gpu_clocks(busy):
@@ -239,7 +250,8 @@ def run_c5(args):
     if not args.no_cpu_baseline:
         from oracle import kitty_oracle as ko
         order = np.argsort(lengths)
-        sample_b = [int(x) for x in order[::max(len(order) // 32, 1)]] + [int(order[-1])]   # every 4th length + the longest
+        n_seq = args.cpu_pairs or 32
+        sample_b = [int(x) for x in order[::max(len(order) // n_seq, 1)]] + [int(order[-1])]   # evenly over the lengths + the longest
         sample = [(b, h) for b in sample_b for h in (0, hkv - 1)]
         g = w.gqa
         out32 = torch.empty((B, hq, 128), dtype=torch.float32, device=dev)
@@ -269,7 +281,7 @@ def run_c5(args):
         max_err = worst
         cpu = {"value": round(sample_bytes / wall / 1e9, 4), "unit": "GB/s",
                "cores": max(1, int(round(cpu_used / max(wall, 1e-9)))), "kind": "oracle",
-               "sample": f"layer 0, {len(sample)} (sequence, kv-head) pairs (every fourth sequence by length, and the longest; "
+               "sample": f"layer 0, {len(sample)} (sequence, kv-head) pairs ({len(sample_b)} sequences spread evenly over the lengths, the longest among them; "
                          f"first and last kv-head) after the decode loop, all {g} query heads each, {wall:.1f} s wall "
                          f"(decode attention only)"}
 
@@ -296,7 +308,9 @@ def run_c5(args):
         "max_abs_err_vs_oracle_sample": max_err,
         "setup_s": {"generate": round(gen_s, 1), "prefill_quantize_all_layers": round(prefill_s, 2)},
     }
-    print(json.dumps(res))
+    del caches, kt, vt
+    torch.cuda.empty_cache()
+    return res
 
 
 def main():
@@ -305,16 +319,58 @@ def main():
         print("bench.py: this build runs on one GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
         sys.exit(2)
     import torch
-    from paper_2511_18643_amd import kitty, synth
-    from paper_2511_18643_amd import devcache as H
+    from paper_2511_18643_amd import kitty
 
     kitty.lib()      # fails loudly if libkitty.so is missing
     assert torch.cuda.is_available(), "bench.py needs a GPU"
-    dev = "cuda"
     if args.workload == "c5":
-        return run_c5(args)
+        print(json.dumps(run_c5(args)))
+        return
+    default_run = args.workload == "c3" and args.n_boost < 0 and args.v_bits == 2 and not (args.sink_tokens or args.v_local) \
+        and not args.no_others
+    res = run_layer(args, args.workload, headline=True)
+    if default_run:
+        res["other_workloads"] = other_workloads(args)
+    print(json.dumps(res))
+
+
+def compact(res):
+    """The figures of a full result line that the summary of the other workloads keeps."""
+    rf = res["roofline"]
+    return {"workload": res["config"]["workload"], "n_splits": res["config"]["n_splits"], "steps": res["steps"],
+            "algorithmic_bytes_per_launch": rf["algorithmic_bytes_per_launch"], "kernel_ms": rf["avg_launch_ms"],
+            "kernel_gbps": rf["achieved"], "frac": rf["frac"], "ms_per_step": res["ms_per_step"],
+            "step_gbps": res["value"], "decode_tokens_per_s": res["decode_tokens_per_s"],
+            "max_abs_err_vs_oracle_sample": res["max_abs_err_vs_oracle_sample"],
+            "oracle_sample": (res.get("cpu_baseline") or {}).get("sample")}
+
+
+def other_workloads(args):
+    """The configurations that are not the headline, each at its full size with fewer steps: the 8k and the 128k
+    layer (same step, same timing as the headline, live oracle check on a few pairs) and the 36-layer
+    variable-length loop; the page quantizer's figures come from the headline run's own prefill shape."""
+    import copy
+    import torch
+    out = {}
+    for name, pairs in (("c2", 16), ("c4", 2)):
+        a = copy.copy(args)
+        a.steps, a.warmup, a.cpu_pairs, a.prewarm_ms = min(args.steps or 200, 100), min(args.warmup, 10), pairs, 150.0
+        out[name] = compact(run_layer(a, name, headline=False))
+        torch.cuda.empty_cache()
+    a = copy.copy(args)
+    a.steps, a.warmup, a.layers, a.prewarm_ms, a.cpu_pairs = min(args.steps or 16, 16), 2, 0, 150.0, 6
+    out["c5"] = compact(run_c5(a))
+    return out
+
+
+def run_layer(args, wname, headline):
+    """One attention layer's decode step on workload `wname` (c2, c3 or c4); see the module docstring."""
+    import torch
+    from paper_2511_18643_amd import kitty, synth
+    from paper_2511_18643_amd import devcache as H
+    dev = "cuda"
     args.steps = args.steps or 200
-    w = synth.WORKLOADS[args.workload]
+    w = synth.WORKLOADS[wname]
     if args.n_boost >= 0:
         w = synth.scaled(w, n_boost=args.n_boost)
     S, VL = args.sink_tokens, args.v_local
@@ -475,41 +531,50 @@ def main():
     torch.cuda.synchronize()
     kern_ms = ev0.elapsed_time(ev1) / n_kern
     kern_gbps = kbytes / n_kern / (kern_ms * 1e-3) / 1e9
-    # spread of single launches (each bracketed by its own event pair; includes ~2 us of event overhead)
-    pairs_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(100)]
-    for i, (a, b_) in enumerate(pairs_ev):
-        a.record()
-        kitty.kitty_decode_split(layout, caches[i % n_copies], qs[i % n_rot], w.sm_scale, ws, args.n_splits)
-        b_.record()
-    torch.cuda.synchronize()
-    single = np.sort(np.array([a.elapsed_time(b_) for a, b_ in pairs_ev]))
-    spread = {"p10_ms": round(float(single[10]), 5), "median_ms": round(float(single[50]), 5),
-              "p90_ms": round(float(single[90]), 5)}
-
-    def busy():
-        for i in range(16):
-            kitty.kitty_decode_split(layout, caches[i % n_copies], qs[0], w.sm_scale, ws, args.n_splits)
+    spread, clocks, quant = None, None, None
+    if headline:
+        # spread of single launches (each bracketed by its own event pair; includes ~2 us of event overhead)
+        pairs_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(100)]
+        for i, (a, b_) in enumerate(pairs_ev):
+            a.record()
+            kitty.kitty_decode_split(layout, caches[i % n_copies], qs[i % n_rot], w.sm_scale, ws, args.n_splits)
+            b_.record()
         torch.cuda.synchronize()
-    clocks = gpu_clocks(busy)
+        single = np.sort(np.array([a.elapsed_time(b_) for a, b_ in pairs_ev]))
+        spread = {"p10_ms": round(float(single[10]), 5), "median_ms": round(float(single[50]), 5),
+                  "p90_ms": round(float(single[90]), 5)}
 
-    # ---- page quantizer on its own (prefill rate), for the record: every sequence reads its own copy of the
-    # source tokens, so that the input comes from HBM and not from the last-level cache ---------------
-    reps_src = (B + nsrc - 1) // nsrc
-    kt_all, vt_all = kt.repeat(reps_src, 1, 1, 1)[:B].contiguous(), vt.repeat(reps_src, 1, 1, 1)[:B].contiguous()
-    offs_all = torch.tensor([b * hkv * L * 128 + i * 128 * 128 for b in range(B) for i in range(n_pages0)],
-                            dtype=torch.int64, device=dev)
-    quant_ms = []
-    for _ in range(3):
-        ev0.record()
-        kitty.kitty_quantize_pages(layout, kt_all, vt_all, 128 * 128, L * 128, 128, ids, B * n_pages0, caches[0].pool,
-                                   caches[0].n_pool_pages, src_page_offsets=offs_all)
-        ev1.record()
-        torch.cuda.synchronize()
-        quant_ms.append(ev0.elapsed_time(ev1))
-    quant_ms = min(quant_ms)
-    quant_pages = B * n_pages0 * hkv
-    del kt_all, vt_all
-    # restore: the records just rewritten are identical (same inputs), nothing else to do
+        def busy():
+            for i in range(16):
+                kitty.kitty_decode_split(layout, caches[i % n_copies], qs[0], w.sm_scale, ws, args.n_splits)
+            torch.cuda.synchronize()
+        clocks = gpu_clocks(busy)
+
+        # ---- page quantizer on its own (the prefill of this workload: every page of every sequence and kv-head).
+        # Every sequence reads its own copy of the source tokens, so that the input comes from HBM and not from
+        # the last-level cache.  Bound: HBM; algorithmic bytes per (page, kv-head) = 2 x 32 KiB of bf16 in + the
+        # record's payload out. -------------------------------------------------------------------------------
+        reps_src = (B + nsrc - 1) // nsrc
+        kt_all, vt_all = kt.repeat(reps_src, 1, 1, 1)[:B].contiguous(), vt.repeat(reps_src, 1, 1, 1)[:B].contiguous()
+        offs_all = torch.tensor([b * hkv * L * 128 + i * 128 * 128 for b in range(B) for i in range(n_pages0)],
+                                dtype=torch.int64, device=dev)
+        quant_ms = []
+        for _ in range(5):
+            ev0.record()
+            kitty.kitty_quantize_pages(layout, kt_all, vt_all, 128 * 128, L * 128, 128, ids, B * n_pages0, caches[0].pool,
+                                       caches[0].n_pool_pages, src_page_offsets=offs_all)
+            ev1.record()
+            torch.cuda.synchronize()
+            quant_ms.append(ev0.elapsed_time(ev1))
+        quant_ms = float(np.median(quant_ms))
+        quant_pages = B * n_pages0 * hkv
+        del kt_all, vt_all
+        # (the records just rewritten are identical: same inputs)
+        qbytes = quant_pages * (65536 + payload)
+        quant = {"kernel": "quantize_pages_kernel", "bound": "hbm", "page_heads": quant_pages, "ms": round(quant_ms, 4),
+                 "algorithmic_bytes_per_launch": int(qbytes), "achieved": round(qbytes / (quant_ms * 1e-3) / 1e9, 1),
+                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(qbytes / (quant_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                 "input_gbps": round(quant_pages * 65536 / (quant_ms * 1e-3) / 1e9, 1)}
 
     if args.calib_copy_mib:
         src_c = torch.ones(args.calib_copy_mib << 20, dtype=torch.uint8, device=dev)
@@ -590,6 +655,9 @@ def main():
                       f"{wall:.1f} s wall (decode attention only; oracle quantization of the sample took {oracle_quant_s:.1f} s)",
         }
 
+    traffic = {"traffic": None}
+    if args.n_boost < 0 and not full_scheme and args.v_bits == 2:
+        traffic = recorded_traffic(w.name)
     res = {
         "metric": "decode_attn_effective_hbm_gbps", "value": round(gbps, 1), "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
@@ -608,20 +676,17 @@ def main():
         "decode_tokens_per_s": round(tokens_per_s, 1),
         "roofline": {
             "bound": "hbm", "kernel": "decode_split_kernel", "achieved": round(kern_gbps, 1), "peak": HBM_PEAK_GBPS,
-            "unit": "GB/s", "frac": round(kern_gbps / HBM_PEAK_GBPS, 4), "traffic": recorded_traffic(w.name) if args.n_boost < 0 and not full_scheme and args.v_bits == 2 else None,
+            "unit": "GB/s", "frac": round(kern_gbps / HBM_PEAK_GBPS, 4),
             "avg_launch_ms": round(kern_ms, 5), "algorithmic_bytes_per_launch": int(kbytes / n_kern),
-            "single_launch": spread,
+            "single_launch": spread, **traffic,
         },
         "cpu_baseline": cpu,
         "max_abs_err_vs_oracle_sample": max_err,
-        "quantize_pages": {"pages": quant_pages, "ms": round(quant_ms, 4),
-                           "input_gbps": round(quant_pages * 65536 / (quant_ms * 1e-3) / 1e9, 1),
-                           "traffic_gbps": round(quant_pages * (65536 + rec_bytes) / (quant_ms * 1e-3) / 1e9, 1),
-                           "frac_of_hbm_peak": round(quant_pages * (65536 + rec_bytes) / (quant_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)},
+        "quantize_pages": quant,
         "clocks_under_load": clocks,
         "setup_s": {"generate": round(gen_s, 1), "prefill_quantize_all_copies": round(quant_s, 2)},
     }
-    print(json.dumps(res))
+    return res
 
 
 if __name__ == "__main__":

@@ -193,7 +193,15 @@ __device__ __forceinline__ uint32_t gather_byte(uint32_t a, uint32_t b, uint32_t
 // byte split (n = t0 + 256 t1 + 65536 t2, each t in [-128,127]) are single adds on the same bits.
 constexpr float MAGIC = 12582912.0f;            // 1.5 * 2^23 = 0x4b400000
 constexpr uint32_t T1_ADD = 0x80u;              // byte 1 of (bits + 0x80)            = t1
-constexpr uint32_t T2_ADD = 0x8080u - 0x400000u;  // byte 2 of (bits + 0x8080 - 0x400000) = t2
+// Three terms: the carries are added in the float domain, for free, by rounding with the constant 1.5*2^23 + 0x8080
+// instead: the bits are then v = 0x4b408080 + n, and with |n| < 2^20 - 0x8080
+//     t0 = byte 0 of v, top bit flipped        t1 = byte 1 of v, top bit flipped        t2 = byte 2 of v - 0x40.
+// Bytes cannot be subtracted without borrows, so the third term is carried as 8 * t2 = (byte 2 << 3) mod 256 (the
+// 0x40 becomes 512 and drops out; t2 lies in [-16, 15]) with weight 8192 instead of 65536.
+constexpr float MAGIC3 = 12582912.0f + 32896.0f;
+constexpr uint32_t MAGIC3_BITS = 0x4b408080u;
+constexpr float NLIM3 = 1015000.0f;             // keeps |n| + 0x8080 below 2^20, i.e. t2 within five bits
+template <int TR> constexpr float image_magic() { return TR == 3 ? MAGIC3 : MAGIC; }
 
 template <int TR>
 __device__ __forceinline__ void split_terms(const uint32_t (&u)[8], uint2 (&w)[TR]) {
@@ -213,25 +221,30 @@ __device__ __forceinline__ void split_terms(const uint32_t (&u)[8], uint2 (&w)[T
     w[1].x = __builtin_amdgcn_perm(up[1], up[0], 0x07050301u);
     w[1].y = __builtin_amdgcn_perm(up[3], up[2], 0x07050301u);
   } else {
-    uint32_t t1[8], t2[8];
+    // u holds the bits v (see MAGIC3).  A 4x4 byte transpose per four values: seven byte permutes for the three
+    // byte planes, then the fix-ups on whole words.
+    uint32_t t[3][2];
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      t1[k] = u[k] + T1_ADD;
-      t2[k] = u[k] + T2_ADD;
+    for (int hlf = 0; hlf < 2; ++hlf) {
+      const uint32_t a = u[4 * hlf], b = u[4 * hlf + 1], c = u[4 * hlf + 2], d = u[4 * hlf + 3];
+      const uint32_t lo01 = __builtin_amdgcn_perm(b, a, 0x05010400u);   // a.b0 b.b0 a.b1 b.b1
+      const uint32_t lo23 = __builtin_amdgcn_perm(d, c, 0x05010400u);
+      const uint32_t hi01 = __builtin_amdgcn_perm(b, a, 0x0c0c0602u);   // a.b2 b.b2 0 0
+      const uint32_t hi23 = __builtin_amdgcn_perm(d, c, 0x0c0c0602u);
+      t[0][hlf] = __builtin_amdgcn_perm(lo23, lo01, 0x05040100u) ^ 0x80808080u;
+      t[1][hlf] = __builtin_amdgcn_perm(lo23, lo01, 0x07060302u) ^ 0x80808080u;
+      t[2][hlf] = (__builtin_amdgcn_perm(hi23, hi01, 0x05040100u) << 3) & 0xf8f8f8f8u;
     }
-    w[0].x = gather_byte<0>(u[0], u[1], u[2], u[3]);
-    w[0].y = gather_byte<0>(u[4], u[5], u[6], u[7]);
-    w[1].x = gather_byte<1>(t1[0], t1[1], t1[2], t1[3]);
-    w[1].y = gather_byte<1>(t1[4], t1[5], t1[6], t1[7]);
-    w[2].x = gather_byte<2>(t2[0], t2[1], t2[2], t2[3]);
-    w[2].y = gather_byte<2>(t2[4], t2[5], t2[6], t2[7]);
+    w[0] = make_uint2(t[0][0], t[0][1]);
+    w[1] = make_uint2(t[1][0], t[1][1]);
+    w[2] = make_uint2(t[2][0], t[2][1]);
   }
 }
 
-// t0 + 256 t1 + 65536 t2 as two shift-adds (v_lshl_add_u32); the empty asm keeps the compiler from
-// re-associating them into two shifts and a three-way add
-__device__ __forceinline__ int join_terms(int t0, int t1, int t2) {
-  uint32_t hi = ((uint32_t)t2 << 8) + (uint32_t)t1;
+// t0 + 256 t1 + 8192 t2x (t2x = 8 t2, see MAGIC3) as two shift-adds (v_lshl_add_u32); the empty asm keeps the
+// compiler from re-associating them into two shifts and a three-way add
+__device__ __forceinline__ int join_terms(int t0, int t1, int t2x) {
+  uint32_t hi = ((uint32_t)t2x << 5) + (uint32_t)t1;
   asm volatile("" : "+v"(hi));
   return (int)((hi << 8) + (uint32_t)t0);
 }
@@ -267,7 +280,11 @@ __device__ __forceinline__ void wave_lds_fence() {
 // 16-byte reads of the sixteen rows fall into different banks.
 template <int NB16, int HPL>
 struct WaveScratch {
-  uint32_t nbuf[4 * HPL][D];                     // integer image (raw bits) of q*s per (head, channel), for the boost gather
+  // integer image (raw bits) of q*s per (head, channel), for the boost gather.  The four lane groups gather the same
+  // channels from the rows of their own heads at once: the row pitch moves those rows 8 banks apart (a pitch of
+  // D words would put all four on the same banks).
+  static constexpr int NPITCH = D + (HPL == 1 ? 8 : 4);
+  uint32_t nbuf[4 * HPL][NPITCH];
   uint8_t abuf[16 * HPL][144];                         // rows (head, term) x channel; one 16-row matrix per pass
   uint8_t bbuf[16 * HPL][16 * (NB16 ? NB16 : 1) + 16];  // rows (head, term) x boost slot
   uint8_t pbuf[16 * HPL][144];                         // rows (head, term) x position
@@ -327,8 +344,8 @@ struct PageWorker {
   static constexpr float wVA = 1.f, wVB = WEIGHTED_V ? 4.f : 1.f, oVA = 0.f, oVB = WEIGHTED_V ? 2.f : 0.f;
   static constexpr bool TWO_PASS_K = HPL == 2 && TRK == 3, TWO_PASS_V = HPL == 2 && TRV == 3;
   static_assert(!(V4 && TWO_PASS_V), "the high Value plane has no second-pass accumulator");
-  static constexpr float NLIM_K = TRK == 3 ? 1048000.0f : 32000.0f;   // bound of the integer images
-  static constexpr float NLIM_V = TRV == 3 ? 1048000.0f : 32000.0f;
+  static constexpr float NLIM_K = TRK == 3 ? NLIM3 : 32000.0f;   // bound of the integer images
+  static constexpr float NLIM_V = TRV == 3 ? NLIM3 : 32000.0f;
 
   // Matrix row of term t of head hd.  Four heads: rows 4hd + t of one matrix.  Eight heads: terms 0, 1 in
   // rows 2hd + t of the first matrix, term 2 in row 4(hd/2) + hd%2 of a second matrix (rows 16..31) that a
@@ -414,7 +431,7 @@ struct PageWorker {
       inv_alpha[e] = amax * (1.0f / NLIM_K);
       uint32_t u[8];
 #pragma unroll
-      for (int k = 0; k < 8; ++k) u[k] = __float_as_uint(fmaf(qs[k], alpha, MAGIC));
+      for (int k = 0; k < 8; ++k) u[k] = __float_as_uint(fmaf(qs[k], alpha, image_magic<TRK>()));
       uint2 tw[TRK];
       split_terms<TRK>(u, tw);
       const int hd = gi * HPL + e;
@@ -437,10 +454,17 @@ struct PageWorker {
         for (int e = 0; e < HPL; ++e) {
           const int hd = gi * HPL + e;
           uint32_t nn = ws.nbuf[hd][ch];
-          nn = ((nn - 0x4b400000u) << sh) + 0x4b400000u;   // undo the division: exact multiple
-          ws.bbuf[term_row(hd, 0)][16 * s + j] = (uint8_t)nn;
-          ws.bbuf[term_row(hd, 1)][16 * s + j] = (uint8_t)((nn + T1_ADD) >> 8);
-          if constexpr (TRK == 3) ws.bbuf[term_row(hd, 2)][16 * s + j] = (uint8_t)((nn + T2_ADD) >> 16);
+          if constexpr (TRK == 3) {
+            // undo the division (an exact multiple, and still within the image's bound: a channel of weight 4
+            // was scaled to a quarter of it), then the same three bytes as split_terms
+            nn = ((nn - MAGIC3_BITS) << sh) + MAGIC3_BITS;
+            ws.bbuf[term_row(hd, 0)][16 * s + j] = (uint8_t)(nn ^ 0x80u);
+            ws.bbuf[term_row(hd, 1)][16 * s + j] = (uint8_t)((nn >> 8) ^ 0x80u);
+            ws.bbuf[term_row(hd, 2)][16 * s + j] = (uint8_t)((nn >> 16) << 3);
+          } else {
+            ws.bbuf[term_row(hd, 0)][16 * s + j] = (uint8_t)nn;
+            ws.bbuf[term_row(hd, 1)][16 * s + j] = (uint8_t)((nn + T1_ADD) >> 8);
+          }
         }
       }
       wave_lds_fence();
@@ -573,7 +597,7 @@ struct PageWorker {
       acc_unit[e] = pmax * (1.0f / NLIM_V);
       uint32_t u[8];
 #pragma unroll
-      for (int T = 0; T < 8; ++T) u[T] = __float_as_uint(fmaf(ps[T], beta, MAGIC));
+      for (int T = 0; T < 8; ++T) u[T] = __float_as_uint(fmaf(ps[T], beta, image_magic<TRV>()));
       uint2 tw[TRV];
       split_terms<TRV>(u, tw);
       const int hd = gi * HPL + e;
@@ -759,7 +783,7 @@ __global__ __launch_bounds__(64 * (NW + (ROWW ? 1 : 0)), (ROWW ? 3 : decode_wave
   // logits of the newest page, [token][head]: kept in the (by then idle) gather table of the wavefront that
   // computes them, which is the one whose turn the page is
   float (*lagx)[NH] = reinterpret_cast<float (*)[NH]>(&smem.w[lag_here ? (p1q - p0) % NW : 0].nbuf[0][0]);
-  static_assert(sizeof(ws.nbuf) == sizeof(float) * G * NH, "lagx aliases nbuf");
+  static_assert(sizeof(ws.nbuf) >= sizeof(float) * G * NH, "lagx aliases nbuf");
   const size_t qrow = ((size_t)b * p.n_q_heads + (size_t)h * g);
   PageWorker<NB16, HPL, V4> pw(ws, l);
 
