@@ -122,6 +122,25 @@ int kitty_quantize_pages(const kitty_layout* layout, const void* k_src, const vo
                          const int64_t* src_page_offsets, const int32_t* dst_page_ids,
                          int32_t n_pages, void* page_pool, int32_t n_pool_pages, void* hip_stream);
 
+/* Prefill-side fusion of the page quantizer with the projection that produces its input (Sec. 4.3 step 3 applied
+ * where the tokens of a page are produced; the system evaluation of Sec. 5.5 prefills prompts before decoding):
+ * for every source page i and kv-head h
+ *     K[t][c] = bf16( sum_j x[o_i + t][j] * w_k[h*D + c][j] ),   V likewise with w_v,      t < G, c < D, o_i = src_token_offsets[i]
+ * on the bf16 matrix cores with fp32 accumulation (the order of the additions is not specified: results equal a
+ * reference bit for bit whenever the sums are exact in fp32, else to the last bf16 digit), rounded to bf16 to
+ * nearest even, and quantized into page dst_page_ids[i] exactly as kitty_quantize_pages would quantize those
+ * bf16 values.  The bf16 K and V never reach device memory.
+ *   x                  device bf16, token row t at x + t*x_token_stride (elements), `hidden` features per row,
+ *                      16-byte aligned rows (x_token_stride a multiple of 8); hidden must be a multiple of 32.
+ *   w_k, w_v           device bf16 [n_kv_heads*D][hidden], row-major (the layout of a linear layer's weight):
+ *                      row h*D + c produces channel c of kv-head h.  No positional rotation or normalisation is
+ *                      applied between the projection and the quantizer.
+ *   src_token_offsets  device int64 [n_pages]; dst_page_ids, page_pool, n_pool_pages as in kitty_quantize_pages. */
+int kitty_project_quantize_pages(const kitty_layout* layout, const void* x, int64_t x_token_stride, int32_t hidden,
+                                 const void* w_k, const void* w_v, const int64_t* src_token_offsets,
+                                 const int32_t* dst_page_ids, int32_t n_pages, void* page_pool, int32_t n_pool_pages,
+                                 void* hip_stream);
+
 /* Insert one new token per sequence (Sec. 4.3 steps 1 and 3, seen from the following step).
  *   k_new, v_new     device bf16 [batch][n_kv_heads][D].
  *   fresh_page_ids   device int32 [batch]; entry b is consumed only if sequence b flushes.

@@ -5,6 +5,7 @@
 #include <type_traits>
 
 #include "kitty_decode.h"
+#include "kitty_prefill.h"
 
 namespace {
 
@@ -258,6 +259,42 @@ int kitty_quantize_pages(const kitty_layout* L, const void* k_src, const void* v
     constexpr int NB = decltype(nb)::value;
     constexpr bool V4 = decltype(v4)::value;
     hipLaunchKernelGGL((quantize_pages_kernel<NB, V4>), dim3(n_pages, L->n_kv_heads), dim3(256), 0, st, P);
+    return launch_status();
+  });
+}
+
+int kitty_project_quantize_pages(const kitty_layout* L, const void* x, int64_t x_token_stride, int32_t hidden,
+                                 const void* w_k, const void* w_v, const int64_t* src_token_offsets,
+                                 const int32_t* dst_page_ids, int32_t n_pages, void* page_pool, int32_t n_pool_pages,
+                                 void* hip_stream) {
+  int rc = check_layout(L);
+  if (rc) return rc;
+  if (n_pages < 0 || n_pool_pages < 0) return KITTY_ERR_INVALID_ARG;
+  if (n_pages == 0) return KITTY_OK;
+  if (!x || !w_k || !w_v || !src_token_offsets || !dst_page_ids || !page_pool) return KITTY_ERR_INVALID_ARG;
+  if (reinterpret_cast<uintptr_t>(x) % 16 || reinterpret_cast<uintptr_t>(w_k) % 16 || reinterpret_cast<uintptr_t>(w_v) % 16 ||
+      reinterpret_cast<uintptr_t>(page_pool) % 128)
+    return KITTY_ERR_INVALID_ARG;
+  if (hidden <= 0 || x_token_stride < hidden || x_token_stride % 8) return KITTY_ERR_INVALID_ARG;
+  if (hidden % PJ_KC) return KITTY_ERR_UNSUPPORTED;
+  if (L->n_kv_heads > 65535) return KITTY_ERR_UNSUPPORTED;
+  ProjectParams P;
+  P.x = static_cast<const uint16_t*>(x);
+  P.w_k = static_cast<const uint16_t*>(w_k);
+  P.w_v = static_cast<const uint16_t*>(w_v);
+  P.x_token_stride = x_token_stride;
+  P.src_token_offsets = src_token_offsets;
+  P.dst_page_ids = dst_page_ids;
+  P.pool = static_cast<uint8_t*>(page_pool);
+  P.hidden = hidden;
+  P.n_kv_heads = L->n_kv_heads;
+  P.n_pool_pages = n_pool_pages;
+  P.rank_metric = L->rank_metric;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  return dispatch_variant(L, [&](auto nb, auto v4) {
+    constexpr int NB = decltype(nb)::value;
+    constexpr bool V4 = decltype(v4)::value;
+    hipLaunchKernelGGL((project_quantize_pages_kernel<NB, V4>), dim3(n_pages, L->n_kv_heads), dim3(256), 0, st, P);
     return launch_status();
   });
 }

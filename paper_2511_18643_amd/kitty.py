@@ -20,7 +20,7 @@ ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = -1, -2, -3, -4
 
 EXPORTS = (
     "kitty_page_bytes", "kitty_page_payload_bytes", "kitty_decode_plan", "kitty_decode_workspace_bytes",
-    "kitty_quantize_pages", "kitty_append_token", "kitty_decode_attention", "kitty_decode_split",
+    "kitty_quantize_pages", "kitty_project_quantize_pages", "kitty_append_token", "kitty_decode_attention", "kitty_decode_split",
     "kitty_decode_merge", "kitty_decode_step", "kitty_decode_attention_static", "kitty_strerror",
 )
 STATIC_WORKSPACE_BYTES = 4 * 1024 * 1024
@@ -66,6 +66,8 @@ def lib() -> C.CDLL:
         L.kitty_decode_workspace_bytes.argtypes = [LP, i32, i32, i32]
         L.kitty_quantize_pages.restype = C.c_int
         L.kitty_quantize_pages.argtypes = [LP, vp, vp, i64, i64, i64, vp, vp, i32, vp, i32, vp]
+        L.kitty_project_quantize_pages.restype = C.c_int
+        L.kitty_project_quantize_pages.argtypes = [LP, vp, i64, i32, vp, vp, vp, vp, i32, vp, i32, vp]
         L.kitty_append_token.restype = C.c_int
         L.kitty_append_token.argtypes = [LP, CP, vp, vp, vp, vp]
         L.kitty_decode_attention.restype = C.c_int
@@ -179,6 +181,15 @@ def kitty_quantize_pages(layout: KittyLayout, k_src, v_src, page_stride: int, he
                                     token_stride, _ptr(src_page_offsets), _ptr(dst_page_ids), n_pages,
                                     _ptr(page_pool), n_pool_pages, _stream(stream))
     _check(rc, "kitty_quantize_pages")
+
+
+def kitty_project_quantize_pages(layout: KittyLayout, x, x_token_stride: int, hidden: int, w_k, w_v,
+                                 src_token_offsets, dst_page_ids, n_pages: int, page_pool, n_pool_pages: int,
+                                 stream=None) -> None:
+    rc = lib().kitty_project_quantize_pages(C.byref(layout), _ptr(x), x_token_stride, hidden, _ptr(w_k), _ptr(w_v),
+                                            _ptr(src_token_offsets), _ptr(dst_page_ids), n_pages, _ptr(page_pool),
+                                            n_pool_pages, _stream(stream))
+    _check(rc, "kitty_project_quantize_pages")
 
 
 def kitty_append_token(layout: KittyLayout, cache: Cache, k_new, v_new, fresh_page_ids, stream=None) -> None:

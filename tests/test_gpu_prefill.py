@@ -1,0 +1,106 @@
+"""kitty_project_quantize_pages: Key/Value projection of 128-token tiles fused with the page quantizer.  The oracle
+side projects on the CPU in fp64, rounds to bf16 and runs its page quantizer on those values."""
+import numpy as np
+import pytest
+
+from oracle import kitty_oracle as ko
+from paper_2511_18643_amd import synth
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+def _exact_inputs(n_tokens, hidden, hkv, seed):
+    """Inputs whose projections are exact in fp32 whatever the order of the additions: x in eighths, weights in
+    sixteenths (a few output channels times 8: the persistent high-magnitude Key channels), |x|, |w| <= 1, so every
+    partial sum is a multiple of 1/128 below 2^11."""
+    r = np.random.default_rng(seed)
+    x = r.integers(-8, 9, size=(n_tokens, hidden)).astype(np.float32) / 8.0
+    wk = r.integers(-8, 9, size=(hkv * 128, hidden)).astype(np.float32) / 16.0
+    wv = r.integers(-8, 9, size=(hkv * 128, hidden)).astype(np.float32) / 16.0
+    big = r.choice(hkv * 128, size=6 * hkv, replace=False)
+    wk[big] = np.clip(wk[big] * 8.0, -1.0, 1.0)
+    return x, wk, wv
+
+
+def _oracle_records(x, wk, wv, offsets, hkv, n_boost, metric):
+    k = ko.f32_to_bf16_bits((x.astype(np.float64) @ wk.astype(np.float64).T).astype(np.float32))   # [tokens][hkv*128]
+    v = ko.f32_to_bf16_bits((x.astype(np.float64) @ wv.astype(np.float64).T).astype(np.float32))
+    recs = []
+    for o in offsets:
+        for h in range(hkv):
+            kp = ko.quantize_k_page(ko.bf16_bits_to_f32(k[o:o + 128, 128 * h:128 * (h + 1)]), n_boost, metric)
+            vp = ko.quantize_v_page(ko.bf16_bits_to_f32(v[o:o + 128, 128 * h:128 * (h + 1)]))
+            recs.append(ko.pack_record(kp, vp))
+    return np.stack(recs).reshape(len(offsets), hkv, -1), k, v
+
+
+@pytest.mark.parametrize("n_boost,metric,hidden", [(16, 0, 256), (32, 1, 256), (0, 0, 64), (128, 0, 512)])
+def test_projected_pages_are_bit_exact_when_the_sums_are_exact(n_boost, metric, hidden):
+    import torch
+    from paper_2511_18643_amd import kitty
+    hkv = 2
+    # two sequences stored back to back (3 and 2 pages), a gap of 40 tokens between them, pages written in a
+    # permuted order into a poisoned pool
+    offsets = [0, 128, 256, 424, 552]
+    n_tokens = 680
+    x, wk, wv = _exact_inputs(n_tokens, hidden, hkv, 7 + n_boost)
+    want, _, _ = _oracle_records(x, wk, wv, offsets, hkv, n_boost, metric)
+    layout = kitty.make_layout(4 * hkv, hkv, n_boost, 128, metric)
+    rb = kitty.kitty_page_bytes(layout)
+    pool = torch.full((7, hkv, rb), 0xA5, dtype=torch.uint8, device="cuda")
+    ids = [4, 0, 6, 2, 1]
+    xt = H.bf16_tensor(ko.f32_to_bf16_bits(x))
+    wkt, wvt = H.bf16_tensor(ko.f32_to_bf16_bits(wk)), H.bf16_tensor(ko.f32_to_bf16_bits(wv))
+    assert np.array_equal(ko.bf16_bits_to_f32(ko.f32_to_bf16_bits(x)), x)        # the inputs are bf16 values
+    kitty.kitty_project_quantize_pages(layout, xt, hidden, hidden, wkt, wvt,
+                                       torch.tensor(offsets, dtype=torch.int64, device="cuda"),
+                                       torch.tensor(ids, dtype=torch.int32, device="cuda"), len(ids), pool, 7)
+    torch.cuda.synchronize()
+    got = pool.cpu().numpy()
+    for i, pid in enumerate(ids):
+        for h in range(hkv):
+            assert np.array_equal(got[pid, h], want[i, h]), (i, h)
+    for pid in (3, 5):                                                       # pages nobody wrote keep the poison
+        assert np.all(got[pid] == 0xA5)
+
+
+def test_projected_cache_gives_the_oracle_attention_with_gaussian_weights():
+    """Gaussian activations and weights (sums no longer exact: the last bf16 digit of a projected value may differ
+    from the CPU's, which can move a channel's minimum or maximum and with it a whole column of codes): most record
+    bytes still agree, and decode attention over the fused-prefill cache stays within the stated bound of the oracle
+    that projects on the CPU."""
+    import torch
+    from paper_2511_18643_amd import kitty
+    hkv, g, hidden, n_pages = 2, 4, 1024, 6
+    r = np.random.default_rng(99)
+    x = ko.bf16_bits_to_f32(ko.f32_to_bf16_bits(r.standard_normal((n_pages * 128, hidden)).astype(np.float32)))
+    wk = r.standard_normal((hkv * 128, hidden)).astype(np.float32) / np.sqrt(hidden)
+    wk[r.choice(hkv * 128, size=12, replace=False)] *= 8.0
+    wv = r.standard_normal((hkv * 128, hidden)).astype(np.float32) / np.sqrt(hidden)
+    wk, wv = (ko.bf16_bits_to_f32(ko.f32_to_bf16_bits(a)) for a in (wk, wv))
+    offsets = [128 * i for i in range(n_pages)]
+    want, k_bits, v_bits = _oracle_records(x, wk, wv, offsets, hkv, 16, 0)
+    layout = kitty.make_layout(g * hkv, hkv, 16, 128, 0)
+    c = kitty.Cache(layout, 1, n_pages, n_pages)
+    kitty.kitty_project_quantize_pages(layout, H.bf16_tensor(ko.f32_to_bf16_bits(x)), hidden, hidden,
+                                       H.bf16_tensor(ko.f32_to_bf16_bits(wk)), H.bf16_tensor(ko.f32_to_bf16_bits(wv)),
+                                       torch.tensor(offsets, dtype=torch.int64, device="cuda"),
+                                       torch.arange(n_pages, dtype=torch.int32, device="cuda"), n_pages, c.pool, n_pages)
+    torch.cuda.synchronize()
+    got = c.pool.cpu().numpy()
+    same = float((got == want).mean())
+    assert same >= 0.9, same
+    # attention: the oracle holds the CPU-projected pages; one window token so that the window path runs too
+    w = synth.scaled(synth.WORKLOADS["c2"], batch=1, n_q_heads=g * hkv, n_kv_heads=hkv)
+    oc = ko.KittyCacheOracle(1, hkv, g * hkv, 16, 128, n_pages, n_pages, 0)
+    oc.pool[:] = want
+    oc.page_table[0] = np.arange(n_pages); oc.n_pages[0] = n_pages; oc.n_resid[0] = 1
+    oc.resid_k[0, :, 0] = k_bits[5, :].reshape(hkv, 128); oc.resid_v[0, :, 0] = v_bits[5, :].reshape(hkv, 128)
+    c.page_table[0] = torch.arange(n_pages, dtype=torch.int32, device="cuda")
+    c.n_pages.fill_(n_pages); c.n_resid.fill_(1)
+    c.resid_k[0, :, 0] = H.bf16_tensor(oc.resid_k[0, :, 0]); c.resid_v[0, :, 0] = H.bf16_tensor(oc.resid_v[0, :, 0])
+    q = synth.query(w)
+    out = H.gpu_decode(layout, c, q, w.sm_scale, 0, fp32=True)
+    err = float(np.abs(out - oc.decode_attention(q, w.sm_scale)).max())
+    assert err <= 2e-3, err
