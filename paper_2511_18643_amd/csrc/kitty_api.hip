@@ -241,7 +241,7 @@ int kitty_quantize_pages(const kitty_layout* L, const void* k_src, const void* v
     return KITTY_ERR_INVALID_ARG;
   if (token_stride < D || token_stride % 8 || head_stride % 8 || (!src_page_offsets && page_stride % 8))
     return KITTY_ERR_INVALID_ARG;
-  if (L->n_kv_heads > 65535) return KITTY_ERR_UNSUPPORTED;
+  if ((int64_t)n_pages * L->n_kv_heads > INT32_MAX) return KITTY_ERR_UNSUPPORTED;
   QuantPagesParams P;
   P.k_src = static_cast<const uint16_t*>(k_src);
   P.v_src = static_cast<const uint16_t*>(v_src);
@@ -258,7 +258,7 @@ int kitty_quantize_pages(const kitty_layout* L, const void* k_src, const void* v
   return dispatch_variant(L, [&](auto nb, auto v4) {
     constexpr int NB = decltype(nb)::value;
     constexpr bool V4 = decltype(v4)::value;
-    hipLaunchKernelGGL((quantize_pages_kernel<NB, V4>), dim3(n_pages, L->n_kv_heads), dim3(256), 0, st, P);
+    hipLaunchKernelGGL((quantize_pages_kernel<NB, V4>), dim3((unsigned)((int64_t)n_pages * L->n_kv_heads)), dim3(256), 0, st, P);
     return launch_status();
   });
 }

@@ -29,8 +29,11 @@ struct ProjectParams {
   int32_t hidden, n_kv_heads, n_pool_pages, rank_metric;
 };
 
-constexpr int PJ_KC = 32;                 // input features per staged chunk
-constexpr int PJ_PITCH = PJ_KC + 8;       // bf16 elements between staged rows (80 bytes: 16-byte reads of 32 rows spread over all banks)
+#ifndef KITTY_PJ_KC
+#define KITTY_PJ_KC 64
+#endif
+constexpr int PJ_KC = KITTY_PJ_KC;       // input features per staged chunk (a chunk's matrix work has to cover the latency of the next chunk's loads)
+constexpr int PJ_PITCH = PJ_KC + 8;       // bf16 elements between staged rows (16 bytes of padding: 16-byte reads of 32 rows spread over all banks)
 constexpr int PJ_TILE_PITCH = D + 8;      // bf16 elements between token rows of the projected tile
 
 struct ProjectSmem {
@@ -48,7 +51,7 @@ struct ProjectSmem {
 };
 
 template <int NB16, bool V4>
-__global__ __launch_bounds__(256, 1) void project_quantize_pages_kernel(ProjectParams p) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void project_quantize_pages_kernel(ProjectParams p) {
   __shared__ ProjectSmem smem;
   const int page = blockIdx.x, h = blockIdx.y;
   const int32_t pid = p.dst_page_ids[page];
@@ -59,22 +62,36 @@ __global__ __launch_bounds__(256, 1) void project_quantize_pages_kernel(ProjectP
   const uint16_t* wk = p.w_k + (size_t)h * D * p.hidden;
   const uint16_t* wv = p.w_v + (size_t)h * D * p.hidden;
 
-  // global -> registers -> LDS: thread t fetches 32 bytes of token row t/2 and 64 bytes of weight row t
-  // (rows 0..127 Key channels, 128..255 Value channels)
-  const uint16_t* xrow = xs + (size_t)(tid >> 1) * p.x_token_stride + (tid & 1) * 16;
-  const uint16_t* wrow = (tid < D ? wk + (size_t)tid * p.hidden : wv + (size_t)(tid - D) * p.hidden);
-  uint4 gx[2], gw[4];
+  // global -> registers -> LDS in 16-byte pieces; consecutive threads take consecutive pieces of a row, so that a
+  // wavefront's load covers whole cache lines (a row of a chunk is PR pieces; X has G rows, W has 2*D rows: Key
+  // channels, then Value channels)
+  constexpr int PR = PJ_KC / 8, NX = G * PR / 256, NWV = 2 * D * PR / 256;
+  static_assert(NX >= 1, "chunk too small for 256 threads");
+  uint4 gx[NX], gw[NWV];
   auto fetch = [&](int k0) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i) gx[i] = *reinterpret_cast<const uint4*>(xrow + k0 + 8 * i);
+    for (int i = 0; i < NX; ++i) {
+      const int idx = tid + 256 * i, row = idx / PR, pc = idx % PR;
+      gx[i] = *reinterpret_cast<const uint4*>(xs + (size_t)row * p.x_token_stride + k0 + 8 * pc);
+    }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) gw[i] = *reinterpret_cast<const uint4*>(wrow + k0 + 8 * i);
+    for (int i = 0; i < NWV; ++i) {
+      const int idx = tid + 256 * i, row = idx / PR, pc = idx % PR;
+      const uint16_t* wr = row < D ? wk + (size_t)row * p.hidden : wv + (size_t)(row - D) * p.hidden;
+      gw[i] = *reinterpret_cast<const uint4*>(wr + k0 + 8 * pc);
+    }
   };
   auto stash = [&]() {
 #pragma unroll
-    for (int i = 0; i < 2; ++i) *reinterpret_cast<uint4*>(&smem.stage.x[tid >> 1][(tid & 1) * 16 + 8 * i]) = gx[i];
+    for (int i = 0; i < NX; ++i) {
+      const int idx = tid + 256 * i;
+      *reinterpret_cast<uint4*>(&smem.stage.x[idx / PR][8 * (idx % PR)]) = gx[i];
+    }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4*>(&smem.stage.w[tid][8 * i]) = gw[i];
+    for (int i = 0; i < NWV; ++i) {
+      const int idx = tid + 256 * i;
+      *reinterpret_cast<uint4*>(&smem.stage.w[idx / PR][8 * (idx % PR)]) = gw[i];
+    }
   };
 
   v16f acc[4][2];

@@ -363,7 +363,8 @@ struct QuantPagesParams {
 template <int NB16, bool V4>
 __global__ __launch_bounds__(256, 4) void quantize_pages_kernel(QuantPagesParams p) {
   __shared__ QuantSmem smem;
-  const int i = blockIdx.x, h = blockIdx.y;
+  // one-dimensional grid, heads fastest: the heads of a page run side by side (a token-major source keeps their rows adjacent)
+  const int h = blockIdx.x % p.n_kv_heads, i = blockIdx.x / p.n_kv_heads;
   const int32_t pid = p.dst_page_ids[i];
   if (pid < 0 || pid >= p.n_pool_pages) return;
   const int64_t off = (p.src_page_offsets ? p.src_page_offsets[i] : (int64_t)i * p.page_stride) + (int64_t)h * p.head_stride;
