@@ -479,6 +479,16 @@ struct PageWorker {
       a0x = *reinterpret_cast<const v4i*>(a_ptr + A_PASS);
       a1x = *reinterpret_cast<const v4i*>(a_ptr + A_PASS + 64);
     }
+    // boost operands: read once for both halves where the registers allow it (four-head groups, 16 boosted
+    // channels), else once per half
+    constexpr bool AB_ONCE = HPL == 1 && NB16 == 1;
+    v4i ab_all[AB_ONCE ? NB16 : 1][4];
+    if constexpr (AB_ONCE) {
+#pragma unroll
+      for (int s = 0; s < NB16; ++s)
+#pragma unroll
+        for (int kb = 0; kb < 4; ++kb) ab_all[s][kb] = *reinterpret_cast<const v4i*>(b_ptr[kb] + (gi == kb ? 16 * s : 0));
+    }
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
       v4i dq[4], dqx[TWO_PASS_K ? 4 : 1];
@@ -506,7 +516,9 @@ struct PageWorker {
           const v4i bb = unpack16_x4(u ? pg.kb[s].y : pg.kb[s].x);
 #pragma unroll
           for (int kb = 0; kb < 4; ++kb) {
-            const v4i ab = *reinterpret_cast<const v4i*>(b_ptr[kb] + (gi == kb ? 16 * s : 0));
+            v4i ab;
+            if constexpr (AB_ONCE) ab = ab_all[s][kb];
+            else ab = *reinterpret_cast<const v4i*>(b_ptr[kb] + (gi == kb ? 16 * s : 0));
             dq[kb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ab, bb, dq[kb], 0, 0, 0);
             if constexpr (TWO_PASS_K) {
               const v4i abx = *reinterpret_cast<const v4i*>(b_ptr[kb] + (gi == kb ? B_PASS + 16 * s : 0));

@@ -93,13 +93,18 @@ def prefill(args):
     e1.record()
     torch.cuda.synchronize()
     gemm_ms = e0.elapsed_time(e1)
+    # the quantizer alone, reading the token-major projection output in place
+    def quant_only(pool):
+        kitty.kitty_quantize_pages(layout, kbuf, vbuf, 0, D, hkv * D, ids, n_pages, pool, n_pages, src_page_offsets=tok_off * (hkv * D))
+    quant_ms = timed(quant_only, pools["two_step"], reps=5)
     flops = 2.0 * T * Hd * (2 * hkv * D)
     same_chunked = bool(torch.equal(pools["two_step"], pools["chunked"]))
     same_fused = float((pools["two_step"] == pools["fused"]).float().mean())
     print(json.dumps({
         "study": "prefill", "tokens": T, "hidden": Hd, "kv_heads": hkv, "pages": n_pages * hkv, "chunk_tokens": chunk,
         "projection_flop": flops, "ms": {k: round(v, 3) for k, v in ms.items()},
-        "two_step_parts_ms": {"projection_gemms": round(gemm_ms, 3), "quantize_pages": round(ms["two_step"] - gemm_ms, 3)},
+        "two_step_parts_ms": {"projection_gemms": round(gemm_ms, 3), "quantize_pages": round(quant_ms, 3)},
+        "quantize_pages_traffic_gbps": round(n_pages * hkv * (65536 + rb) / (quant_ms * 1e-3) / 1e9, 1),
         "tflops": {k: round(flops / (v * 1e-3) / 1e12, 1) for k, v in ms.items()},
         "bf16_kv_round_trip_bytes_saved_by_fusion": int(2 * 2 * T * hkv * D * 2),
         "records_equal_two_step_vs_chunked": same_chunked, "fraction_of_equal_record_bytes_fused_vs_two_step": round(same_fused, 5),
