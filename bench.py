@@ -245,6 +245,13 @@ def run_c5(args):
     kern_ms = ev0.elapsed_time(ev1) / (reps * layers)
     kern_gbps = kbytes / (kern_ms * 1e-3) / 1e9
 
+    if args.calib_copy_mib:      # scale reference for the FETCH_SIZE / WRITE_SIZE counters
+        src_c = torch.ones(args.calib_copy_mib << 20, dtype=torch.uint8, device=dev)
+        dst_c = torch.empty_like(src_c)
+        dst_c.copy_(src_c)
+        torch.cuda.synchronize()
+        del src_c, dst_c
+
     # ---- CPU oracle on a sample of layer 0: rebuilt from the inputs, appended tokens replayed ----------
     cpu, max_err = None, None
     if not args.no_cpu_baseline:
