@@ -470,8 +470,10 @@ struct PageWorker {
       wave_lds_fence();
     }
     // ================= C: logits for 128 tokens x heads on the int8 matrix cores =================
-    // Two halves of four token tiles each (dense plane, then the boost plane's contribution to the same tiles,
-    // then the join of the byte terms), so that at most four tiles' accumulators are alive at a time.
+    // Dense plane, then the boost plane's contribution to the same tiles, then the join of the byte terms.  Eight-head
+    // groups (two MFMA passes, twice the accumulators) do this in two halves of four token tiles each, so that at
+    // most four tiles' accumulators are alive at a time; four-head groups take all eight tiles at once and read
+    // each boost operand once.
     const v4i a0 = *reinterpret_cast<const v4i*>(a_ptr);
     const v4i a1 = *reinterpret_cast<const v4i*>(a_ptr + 64);
     v4i a0x = {0, 0, 0, 0}, a1x = {0, 0, 0, 0};
@@ -479,22 +481,14 @@ struct PageWorker {
       a0x = *reinterpret_cast<const v4i*>(a_ptr + A_PASS);
       a1x = *reinterpret_cast<const v4i*>(a_ptr + A_PASS + 64);
     }
-    // boost operands: read once for both halves where the registers allow it (four-head groups, 16 boosted
-    // channels), else once per half
-    constexpr bool AB_ONCE = HPL == 1 && NB16 == 1;
-    v4i ab_all[AB_ONCE ? NB16 : 1][4];
-    if constexpr (AB_ONCE) {
+    constexpr int NU = HPL == 2 ? 2 : 1;       // passes over the token tiles
+    constexpr int TP = 8 / NU;                 // tiles per pass
 #pragma unroll
-      for (int s = 0; s < NB16; ++s)
+    for (int uu = 0; uu < NU; ++uu) {
+      v4i dq[TP], dqx[TWO_PASS_K ? TP : 1];
 #pragma unroll
-        for (int kb = 0; kb < 4; ++kb) ab_all[s][kb] = *reinterpret_cast<const v4i*>(b_ptr[kb] + (gi == kb ? 16 * s : 0));
-    }
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      v4i dq[4], dqx[TWO_PASS_K ? 4 : 1];
-#pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        const int T = 4 * u + t;
+      for (int t = 0; t < TP; ++t) {
+        const int T = TP * uu + t;
         const uint4 ld = pg.kd[T >> 1];
         const uint32_t w0 = (T & 1) ? ld.z : ld.x, w1 = (T & 1) ? ld.w : ld.y;
         const v4i b0 = unpack_k(w0), b1 = unpack_k(w1);
@@ -513,24 +507,29 @@ struct PageWorker {
 #pragma unroll
         for (int s = 0; s < NB16; ++s) {
           // tile 4u+kb of the boost plane lives in the lanes of k-block kb: feed A only to that block
-          const v4i bb = unpack16_x4(u ? pg.kb[s].y : pg.kb[s].x);
+          v4i ab[4], abx[TWO_PASS_K ? 4 : 1];
 #pragma unroll
           for (int kb = 0; kb < 4; ++kb) {
-            v4i ab;
-            if constexpr (AB_ONCE) ab = ab_all[s][kb];
-            else ab = *reinterpret_cast<const v4i*>(b_ptr[kb] + (gi == kb ? 16 * s : 0));
-            dq[kb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ab, bb, dq[kb], 0, 0, 0);
-            if constexpr (TWO_PASS_K) {
-              const v4i abx = *reinterpret_cast<const v4i*>(b_ptr[kb] + (gi == kb ? B_PASS + 16 * s : 0));
-              dqx[kb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(abx, bb, dqx[kb], 0, 0, 0);
+            ab[kb] = *reinterpret_cast<const v4i*>(b_ptr[kb] + (gi == kb ? 16 * s : 0));
+            if constexpr (TWO_PASS_K) abx[kb] = *reinterpret_cast<const v4i*>(b_ptr[kb] + (gi == kb ? B_PASS + 16 * s : 0));
+          }
+#pragma unroll
+          for (int u = (NU == 2 ? uu : 0); u < (NU == 2 ? uu + 1 : 2); ++u) {
+            const v4i bb = unpack16_x4(u ? pg.kb[s].y : pg.kb[s].x);
+            const int base = NU == 2 ? 0 : 4 * u;
+#pragma unroll
+            for (int kb = 0; kb < 4; ++kb) {
+              dq[base + kb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ab[kb], bb, dq[base + kb], 0, 0, 0);
+              if constexpr (TWO_PASS_K)
+                dqx[base + kb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(abx[kb], bb, dqx[base + kb], 0, 0, 0);
             }
           }
         }
       }
 #pragma unroll
-      for (int t = 0; t < 4; ++t)
+      for (int t = 0; t < TP; ++t)
 #pragma unroll
-        for (int e = 0; e < HPL; ++e) nl[e][4 * u + t] = joined_k(dq[t], dqx[TWO_PASS_K ? t : 0], e);
+        for (int e = 0; e < HPL; ++e) nl[e][TP * uu + t] = joined_k(dq[t], dqx[TWO_PASS_K ? t : 0], e);
     }
   }
 
