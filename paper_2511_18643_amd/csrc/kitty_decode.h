@@ -5,7 +5,7 @@
 //     q . K_t      = sum_c (q_c s_c) X[t][c] + sum_c q_c z_c
 //     sum_t p_t V_t = sum_t (p_t s_t) X[t][:] + sum_t p_t z_t
 // so the 2-bit codes X go to the int8 matrix cores unchanged (mask/shift into bytes), while the
-// small vectors q*s and p*s are turned into 2 or 3 signed-byte terms (n = t0 + 256 t1 + 65536 t2)
+// small vectors q*s and p*s are turned into three signed-byte terms (n = t0 + 256 t1 + 65536 t2)
 // occupying separate matrix rows; the integer dot products are exact and are recombined by shifts.
 // The high bits of boosted channels are one more short contraction against the same q*s values
 // gathered through the channel list (the only gather, and it is of q, never of cache bytes).
@@ -657,8 +657,8 @@ struct PageWorker {
   }
 };
 
-// HPL = query heads per lane: 1 for GQA groups of 1, 2, 4 (three byte terms), 2 for groups of 8
-// (two byte terms).  Grid: x = page range (see active_splits), y = kv-head, z = sequence.
+// HPL = query heads per lane: 1 for GQA groups of 1, 2, 4 (three byte terms in one matrix), 2 for groups of 8
+// (three byte terms in two matrix passes).  Grid: x = page range (see active_splits), y = kv-head, z = sequence.
 // Block = NW wavefronts (4 or 8); wavefront w takes pages p0+w, p0+w+NW, ... of the range and a slice of
 // the range's share of the rows held in full precision (Sink, window).
 // wavefronts per SIMD the kernel is compiled for (register budget 512 / n)

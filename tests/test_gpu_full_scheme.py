@@ -206,10 +206,10 @@ def test_randomized_configurations():
         layout, gc = H.gpu_full_cache(w, lengths, k, v, max_pages, sink, v_local, v_bits=v_bits)
         if trial % 2:
             gc.seq_order = torch.from_numpy(rng.permutation(B).astype(np.int32)).cuda()
-        # short, peaky sequences are the worst case of the fixed-point images: up to 3.2e-4 with 20-bit images
-        # (groups of up to four query heads) and up to 1.4e-3 with the 16-bit images of eight-head groups when
-        # the outlier channels are not boosted (measured over all variants); the stated bar is 2e-3
-        tol = 5e-4 if g <= 4 else 1.6e-3
+        # short, peaky sequences are the worst case of the fixed-point images: up to 3.2e-4 with the 20-bit images
+        # (measured over all variants); eight-head groups with 4-bit Values keep a two-term image of p*scale (up to
+        # 1.4e-3); the stated bar is 2e-3
+        tol = 1.6e-3 if (g == 8 and v_bits == 4) else 5e-4
         tag = dict(trial=trial, hkv=hkv, g=g, v_bits=v_bits, nb=nb, sink=sink, v_local=v_local, metric=metric, B=B,
                    n_splits=n_splits, max_pages=max_pages, lengths=lengths)
         q = synth.query(w)

@@ -29,8 +29,9 @@ def check_pool(w, lengths, oc, gc):
 
 
 def run_case(w, lengths, n_splits_list=(0,), max_pages=None, v_bits=2):
-    # groups of 8 query heads carry two byte terms per value instead of three (coarser fixed point)
-    tol32 = TOL_FP32 if w.gqa <= 4 else 1e-3
+    # fp32 output: 3e-4 for groups of up to four query heads, 5e-4 for eight; eight-head groups with 4-bit Values
+    # (a variant of the design-space sweep) keep a two-term image of p*scale: 1e-3
+    tol32 = TOL_FP32 if w.gqa <= 4 else (1e-3 if v_bits == 4 else 5e-4)
     k, v = H.gen_sequences(w, lengths)
     mp = max_pages or max(max((w.pages_and_resid(n)[0] if n else 0) for n in lengths), 1)
     oc = H.oracle_cache(w, lengths, k, v, mp, v_bits)
@@ -251,7 +252,7 @@ def test_c3_full_size_sampled():
 
 
 def test_c4_full_size_sampled():
-    _full_size_case("c4", 1, [(0, 0), (7, 5)], 1e-3)
+    _full_size_case("c4", 1, [(0, 0), (7, 5)], 5e-4)
 
 
 def test_wide_batch_long_ranges_in_four_wavefront_blocks_sampled():
