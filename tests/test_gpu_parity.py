@@ -525,3 +525,27 @@ def test_long_single_sequence_many_pages_per_wavefront():
         got = H.gpu_decode(layout, gc, q, w.sm_scale, ns, fp32=True)
         err = float(np.abs(got - want).max())
         assert err <= TOL_FP32, (ns, err)
+
+
+def test_quantize_pages_more_pages_than_a_grid_dimension_holds():
+    """70 000 pages in one call (the launch is one-dimensional, so the 65 535 limit of a grid's second dimension does
+    not apply): all source pages are the same two pages (per-page offsets), records sampled over the whole range."""
+    import torch
+    from paper_2511_18643_amd import kitty
+    w = synth.scaled(synth.WORKLOADS["c2"], batch=1, n_q_heads=4, n_kv_heads=1, context=0)
+    kb, vb = synth.kv_block(w, 0, 0, 256)
+    n = 70000
+    layout = kitty.make_layout(4, 1, 16, 128, 0)
+    rb = kitty.kitty_page_bytes(layout)
+    pool = torch.full((n, 1, rb), 0xA5, dtype=torch.uint8, device="cuda")
+    offs = (torch.arange(n, dtype=torch.int64, device="cuda") % 2) * (128 * 128)
+    ids = torch.arange(n, dtype=torch.int32, device="cuda")
+    kitty.kitty_quantize_pages(layout, H.bf16_tensor(kb), H.bf16_tensor(vb), 0, 0, 128, ids, n, pool, n, src_page_offsets=offs)
+    torch.cuda.synchronize()
+    want = []
+    for i in range(2):
+        kp = ko.quantize_k_page(ko.bf16_bits_to_f32(kb[128 * i:128 * (i + 1)]), 16, 0)
+        vp = ko.quantize_v_page(ko.bf16_bits_to_f32(vb[128 * i:128 * (i + 1)]))
+        want.append(torch.from_numpy(ko.pack_record(kp, vp)).cuda())
+    for parity in range(2):      # every record of the whole pool, compared on the device
+        assert bool((pool[parity::2, 0] == want[parity][None, :]).all()), parity
