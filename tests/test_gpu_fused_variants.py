@@ -194,3 +194,36 @@ def test_eight_head_groups_with_one_dominant_query_channel(nb, n_tokens):
         got = H.gpu_decode(layout, gc, q, w.sm_scale, ns, fp32=True)
         err = float(np.abs(got - want).max())
         assert err <= 2e-3, (ns, err)
+
+
+@pytest.mark.parametrize("n_splits", [0, 2])
+def test_decode_step_with_a_full_page_table_drops_the_token_and_attends_over_the_old_state(n_splits):
+    """A flush is due but the page table has no free entry (or the fresh id lies outside the pool): that sequence is
+    left unchanged, as kitty_append_token leaves it, and attention runs over its old state; the other sequence of
+    the batch appends normally.  One launch (n_splits 0) and two (n_splits 2)."""
+    import torch
+    from paper_2511_18643_amd import kitty
+    w = synth.scaled(synth.WORKLOADS["c2"], batch=3, n_q_heads=8, n_kv_heads=2, context=0)
+    max_pages = 2
+    start = [2 * 128 + 128, 128 + 5, 128 + 128]        # table full and window full; room left; window full, bad fresh id
+    k0, v0 = H.gen_sequences(w, start)
+    oc = H.oracle_cache(w, start, k0, v0, max_pages)
+    layout, gc = H.gpu_cache(w, start, k0, v0, max_pages)
+    before = {n: getattr(gc, n).clone() for n in ("n_pages", "n_resid", "page_table", "resid_k", "resid_v", "pool")}
+    kn, vn = synth.new_token(w, 1)
+    q = synth.query(w, 1)
+    fresh = np.array([0, 3, 99], np.int32)             # sequence 2's id is outside the pool of 6 pages
+    # the oracle's machine has no refusal: apply the append to sequence 1 only
+    oc.resid_k[1, :, 5] = kn[1]; oc.resid_v[1, :, 5] = vn[1]; oc.n_resid[1] = 6
+    want = oc.decode_attention(q, w.sm_scale)
+    ws = kitty.new_workspace(layout, 3, max_pages, n_splits)
+    out = torch.full((3, 8, 128), float("nan"), dtype=torch.float32, device="cuda")
+    kitty.kitty_decode_step(layout, gc, H.bf16_tensor(kn), H.bf16_tensor(vn), torch.from_numpy(fresh).cuda(),
+                            H.bf16_tensor(q), out, w.sm_scale, ws, n_splits)
+    torch.cuda.synchronize()
+    assert gc.n_pages.cpu().tolist() == [2, 1, 1] and gc.n_resid.cpu().tolist() == [128, 6, 128]
+    assert torch.equal(gc.page_table, before["page_table"]) and torch.equal(gc.pool, before["pool"])
+    for b in (0, 2):
+        assert torch.equal(gc.resid_k[b], before["resid_k"][b]) and torch.equal(gc.resid_v[b], before["resid_v"][b])
+    got = out.cpu().numpy()
+    assert np.isfinite(got).all() and float(np.abs(got - want).max()) <= TOL_G4
