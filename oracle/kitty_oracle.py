@@ -15,7 +15,8 @@ What it follows (arXiv 2511.18643):
   * Sec. 4.2, Alg. 1    X = X_low | (X_high << 2);  K = X * scale + zero_point
   * Sec. 3.2, Eq. (1)   attention = softmax(Q K^T / sqrt(d)) (then times V)
   * Sec. 4.3            insert new token -> attention -> quantize+pack when the buffer of G
-                        full-precision tokens is full (at most once every G steps)
+                        full-precision tokens is full (at most once every G steps); `project_bf16` is the
+                        plain linear projection that produces the tokens at prefill
   * Fig. 1, Sec. 3.1,   the full scheme (`KittyUnitOracle`): Sink of S initial tokens kept in full
     Sec. 4.3 step (1)   precision for K and V; Key Q-Buffer; Value Local window of the R newest tokens
                         whose evicted token enters the Value Q-Buffer, so Value pages form R tokens
@@ -183,6 +184,15 @@ def quantize_v_page(x: np.ndarray, bits: int = 2) -> VPage:
     qmax = np.full((x.shape[0], 1), float(2 ** bits - 1), dtype=np.float32)
     codes, scale_h, zero_h = _asym_quant(x, mn[:, None], mx[:, None], qmax)
     return VPage(codes=codes, scale=scale_h[:, 0], zero=zero_h[:, 0], bits=bits)
+
+
+def project_bf16(x: np.ndarray, w: np.ndarray) -> np.ndarray:
+    """Linear projection of tokens x[T][H] with a weight w[C][H] (one output channel per row, the layout of a linear
+    layer), as the producer of the Keys or Values that a page is quantized from (Sec. 4.3: tokens are quantized as
+    the engine produces them): y[t][c] = sum_j x[t][j] * w[c][j] in fp64, rounded once to fp32 and once more to bf16
+    (nearest even).  Returns bf16 bit patterns (uint16) [T][C].  Inputs are float arrays holding bf16 values."""
+    y = np.asarray(x, dtype=np.float64) @ np.asarray(w, dtype=np.float64).T
+    return f32_to_bf16_bits(y.astype(np.float32))
 
 
 def dequant_k(kp: KPage) -> np.ndarray:

@@ -24,8 +24,7 @@ def _exact_inputs(n_tokens, hidden, hkv, seed):
 
 
 def _oracle_records(x, wk, wv, offsets, hkv, n_boost, metric):
-    k = ko.f32_to_bf16_bits((x.astype(np.float64) @ wk.astype(np.float64).T).astype(np.float32))   # [tokens][hkv*128]
-    v = ko.f32_to_bf16_bits((x.astype(np.float64) @ wv.astype(np.float64).T).astype(np.float32))
+    k, v = ko.project_bf16(x, wk), ko.project_bf16(x, wv)                                     # [tokens][hkv*128]
     recs = []
     for o in offsets:
         for h in range(hkv):

@@ -792,3 +792,25 @@ def test_channel_score_refuses_pages_whose_sum_may_be_inexact():
     s = ko.channel_scores(z, 0)
     from fractions import Fraction
     assert Fraction(float(s[3])) == sum(Fraction(abs(float(v))) for v in z[:, 3])
+
+
+# ------------------------------------------------------------------ projection that produces the tokens at prefill
+def test_projection_by_hand_and_bf16_rounding():
+    from fractions import Fraction
+    r = np.random.default_rng(3)
+    x = ko.bf16_bits_to_f32(ko.f32_to_bf16_bits(r.standard_normal((5, 7)).astype(np.float32)))
+    w = ko.bf16_bits_to_f32(ko.f32_to_bf16_bits(r.standard_normal((3, 7)).astype(np.float32)))
+    got = ko.bf16_bits_to_f32(ko.project_bf16(x, w))
+    assert got.shape == (5, 3)
+    for t in range(5):
+        for c in range(3):
+            exact = sum(Fraction(float(x[t, j])) * Fraction(float(w[c, j])) for j in range(7))
+            # within half a bf16 unit in the last place of the exact sum (8 significant bits)
+            assert abs(Fraction(float(got[t, c])) - exact) <= abs(exact) * Fraction(1, 256) + Fraction(1, 10 ** 30)
+    # rows of w are output channels (not columns): a weight with a single one picks an input feature
+    e = np.zeros((2, 7), np.float32); e[0, 4] = 1.0; e[1, 0] = -2.0
+    assert np.array_equal(ko.bf16_bits_to_f32(ko.project_bf16(x, e)), np.stack([x[:, 4], -2.0 * x[:, 0]], axis=1))
+    # rounding to nearest even at the bf16 step: 1 + 2^-8 is a tie and goes to 1.0, 1 + 3 * 2^-8 to 1 + 2^-6
+    one = np.array([[1.0, 2.0 ** -8]], np.float32)
+    assert ko.project_bf16(one, np.array([[1.0, 1.0]], np.float32))[0, 0] == 0x3F80
+    assert ko.project_bf16(one, np.array([[1.0, 3.0]], np.float32))[0, 0] == 0x3F82
