@@ -17,6 +17,14 @@
 #include "kitty_common.h"
 #include "kitty_quant.h"
 
+// Byte terms of the fixed-point images in the kernels for eight-head groups (2 or 3; see PageWorker).
+#ifndef KITTY_G8_KEY_TERMS
+#define KITTY_G8_KEY_TERMS 3
+#endif
+#ifndef KITTY_G8_VALUE_TERMS
+#define KITTY_G8_VALUE_TERMS 3
+#endif
+
 namespace kitty {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
@@ -327,13 +335,8 @@ struct PageWorker {
   // the same code operand.  On the Key side the 16-bit image is not enough: its step is set by the largest
   // |q*scale| of a head, and one dominant query element on an outlier channel coarsens the other 127 channels
   // until the logits are off by 1e-2 (measured: output error up to 1.4e-2 on short contexts, 8e-4 to 1.8e-3 on
-  // ordinary data).  KEY_TERMS_G8 / VALUE_TERMS_G8 choose the terms of the eight-head kernels.
-#ifndef KITTY_G8_KEY_TERMS
-#define KITTY_G8_KEY_TERMS 3
-#endif
-#ifndef KITTY_G8_VALUE_TERMS
-#define KITTY_G8_VALUE_TERMS 3
-#endif
+  // ordinary data), so both sides carry three terms; KITTY_G8_KEY_TERMS / KITTY_G8_VALUE_TERMS are the compile-time
+  // switches the alternatives were measured with.
   static constexpr int TRK = HPL == 1 ? 3 : KITTY_G8_KEY_TERMS;     // byte terms of q*scale
   static constexpr int TRV = HPL == 1 ? 3 : (V4 ? 2 : KITTY_G8_VALUE_TERMS);   // byte terms of p*scale (4-bit Values: no second pass)
   // cheap unpack (one shift, four masks; elements 4..7 and 12..15 of a word come out times 4): relies on the
