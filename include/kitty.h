@@ -39,7 +39,7 @@ typedef struct kitty_layout {
   int32_t n_boost;         /* boosted Key channels per page = boost fraction * D (Sec. 3.2): 0,16,32,64,128 */
   int32_t residual_window; /* R: full-precision tokens kept before a page forms (Sec. 4.3): 128, or 0    */
   int32_t n_q_heads;       /* query heads                                                                */
-  int32_t n_kv_heads;      /* KV heads; n_q_heads / n_kv_heads must be 1, 2, 4 or 8                      */
+  int32_t n_kv_heads;      /* KV heads; n_q_heads / n_kv_heads must be an integer from 1 to 8           */
   int32_t rank_metric;     /* channel ranking: 0 = mean |x| over the page (Eq. 2), 1 = max - min         */
   int32_t sink_tokens;     /* S: initial tokens kept in full precision for K and V (Fig. 1, Sec. 3.1): 0..128.  The
                               paper leaves S free (default 32); this library stops at one page's worth and answers

@@ -21,7 +21,7 @@ int check_layout(const kitty_layout* L) {
   const int nb16 = L->n_boost / 16;
   if (nb16 != 0 && nb16 != 1 && nb16 != 2 && nb16 != 4 && nb16 != 8) return KITTY_ERR_UNSUPPORTED;
   const int g = L->n_q_heads / L->n_kv_heads;
-  if (g != 1 && g != 2 && g != 4 && g != 8) return KITTY_ERR_UNSUPPORTED;
+  if (g > 8) return KITTY_ERR_UNSUPPORTED;   // a block holds the heads of a group in 4 or 8 slots; unused slots carry a zero query
   if (L->sink_tokens < 0 || L->v_local < 0) return KITTY_ERR_INVALID_ARG;
   if (L->sink_tokens > G) return KITTY_ERR_UNSUPPORTED;
   if (L->v_local != 0 && (L->v_local != G || L->residual_window != G)) return KITTY_ERR_UNSUPPORTED;
@@ -378,7 +378,7 @@ int launch_split(const kitty_layout* L, const kitty_cache* C, const void* q, flo
   }
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   const dim3 grid(P.n_splits, L->n_kv_heads, C->batch);
-  const bool wide = P.gqa == 8;
+  const bool wide = P.gqa > 4;   // more than four query heads per kv-head: eight head slots per block
   const bool big = waves_per_block(C->max_pages, P.n_splits, (int64_t)P.n_splits * L->n_kv_heads * C->batch) == 8;
   const bool fused = step != nullptr;
   return dispatch_variant(L, [&](auto nb, auto v4) {

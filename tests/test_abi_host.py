@@ -43,7 +43,9 @@ def test_unsupported_layouts_are_rejected():
     assert kitty.kitty_page_bytes(kitty.make_layout(32, 8, 48)) == 0           # unsupported count
     assert kitty.kitty_page_bytes(kitty.make_layout(32, 8, 16, residual_window=64)) == 0
     assert kitty.kitty_page_bytes(kitty.make_layout(30, 8, 16)) == 0           # heads do not divide
-    assert kitty.kitty_page_bytes(kitty.make_layout(48, 8, 16)) == 0           # GQA group of 6
+    assert kitty.kitty_page_bytes(kitty.make_layout(48, 8, 16)) == 9856        # any group of up to eight query heads
+    assert kitty.kitty_page_bytes(kitty.make_layout(40, 8, 16)) == 9856
+    assert kitty.kitty_page_bytes(kitty.make_layout(72, 8, 16)) == 0           # group of 9
     assert kitty.kitty_page_bytes(kitty.make_layout(32, 8, 16, rank_metric=2)) == 0
     # 4-bit Values: one more 4 KB plane; only with 0 or 16 boosted channels
     assert kitty.kitty_page_bytes(kitty.make_layout(32, 8, 16, v_bits=4)) == 9856 + 4096

@@ -70,10 +70,17 @@ def test_boost_counts(nb):
     run_case(w, [5 * 128 + 60, 3 * 128 + 128], n_splits_list=(0, 2))
 
 
-@pytest.mark.parametrize("g", [1, 2, 4, 8])
+@pytest.mark.parametrize("g", [1, 2, 3, 4, 5, 6, 7, 8])
 def test_gqa_groups(g):
+    # groups that do not fill the block's 4 or 8 head slots (3; 5, 6, 7) leave the rest with a zero query
     w = synth.scaled(synth.WORKLOADS["c2"], batch=2, n_q_heads=2 * g, n_kv_heads=2)
     run_case(w, [9 * 128 + 1, 2 * 128 + 77], n_splits_list=(0, 3))
+
+
+def test_forty_query_heads_on_eight_kv_heads():
+    """The head shape of the 14B model of the paper's accuracy table (Sec. 5.1): 40 query heads, 8 kv-heads."""
+    w = synth.scaled(synth.WORKLOADS["c2"], batch=2, n_q_heads=40, n_kv_heads=8, n_boost=32)
+    run_case(w, [17 * 128 + 33, 4 * 128 + 128], n_splits_list=(0, 2))
 
 
 def test_ragged_lengths_and_empty():
