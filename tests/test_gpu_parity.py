@@ -556,3 +556,43 @@ def test_quantize_pages_more_pages_than_a_grid_dimension_holds():
         want.append(torch.from_numpy(ko.pack_record(kp, vp)).cuda())
     for parity in range(2):      # every record of the whole pool, compared on the device
         assert bool((pool[parity::2, 0] == want[parity][None, :]).all()), parity
+
+
+def test_largest_batch_a_launch_holds_and_one_past_it():
+    """65 535 sequences (the most the launch grid's third dimension holds), each with 0 to 5 tokens in its window
+    and no page: sampled sequences against plain softmax attention, empty sequences give zeros; 65 536 sequences
+    are refused with an error code and nothing is launched (the output keeps its fill)."""
+    import torch
+    from paper_2511_18643_amd import kitty
+    B, hq, rows = 65535, 2, 8
+    layout = kitty.make_layout(hq, 1, 16)
+    rng = np.random.default_rng(77)
+    kw = ko.f32_to_bf16_bits(rng.standard_normal((B, 1, rows, 128)).astype(np.float32))
+    vw = ko.f32_to_bf16_bits(rng.standard_normal((B, 1, rows, 128)).astype(np.float32))
+    qb = ko.f32_to_bf16_bits((rng.standard_normal((B, hq, 128)) * 0.3).astype(np.float32))
+    nres = (np.arange(B) % 6).astype(np.int32)
+    c = kitty.Cache(layout, B, 1, 1)
+    c.resid_k[:, :, :rows] = H.bf16_tensor(kw)
+    c.resid_v[:, :, :rows] = H.bf16_tensor(vw)
+    c.n_resid.copy_(torch.from_numpy(nres))
+    sm = 0.25
+    got = H.gpu_decode(layout, c, qb, sm, 0, fp32=True)
+    assert np.isfinite(got).all()
+    assert not got[nres == 0].any()
+    for b in (1, 2, 5, 4099, 32767, 65533, 65534):
+        n = int(nres[b])
+        kf, vf = ko.bf16_bits_to_f32(kw[b, 0, :n]), ko.bf16_bits_to_f32(vw[b, 0, :n])
+        for hd in range(hq):
+            want = ko.softmax_attention(ko.bf16_bits_to_f32(qb[b, hd]), kf, vf, sm)
+            assert np.abs(got[b, hd] - want).max() <= TOL_FP32, (b, hd)
+    # one sequence more: an error, and no kernel ran
+    c2 = kitty.Cache(layout, B + 1, 1, 1)
+    c2.n_resid.fill_(1)
+    q2 = torch.zeros((B + 1, hq, 128), dtype=torch.bfloat16, device="cuda")
+    out2 = torch.full((B + 1, hq, 128), 7.0, dtype=torch.float32, device="cuda")
+    ws = kitty.new_workspace(layout, B + 1, 1, 1)
+    with pytest.raises(kitty.KittyError) as e:
+        kitty.kitty_decode_attention(layout, c2, q2, out2, sm, ws, 1)
+    assert e.value.code == kitty.ERR_UNSUPPORTED
+    torch.cuda.synchronize()
+    assert bool((out2 == 7.0).all())
