@@ -1,6 +1,8 @@
 """GPU parity of the paper's full cache organisation (Fig. 1, Sec. 4.3): Sink tokens in full precision, and the
 Value Local window that keeps the Values of the newest page in full precision one page longer than its Keys.
 The oracle side is the buffer-by-buffer state machine (KittyUnitOracle); the GPU side goes through the C ABI."""
+import os
+
 import numpy as np
 import pytest
 
@@ -183,10 +185,11 @@ def test_randomized_configurations():
     every output is compared with the unit oracles."""
     import torch
     from paper_2511_18643_amd import kitty
-    rng = np.random.default_rng(20251127)
-    for trial in range(14):
+    # KITTY_RANDOM_SEED / KITTY_RANDOM_DRAWS widen the search by hand; the defaults are what the suite runs
+    rng = np.random.default_rng(int(os.environ.get("KITTY_RANDOM_SEED", "20251127")))
+    for trial in range(int(os.environ.get("KITTY_RANDOM_DRAWS", "14"))):
         hkv = int(rng.choice([1, 2, 4]))
-        g = int(rng.choice([1, 2, 4, 8]))
+        g = int(rng.choice([1, 2, 3, 4, 5, 6, 7, 8]))
         v_bits = int(rng.choice([2, 2, 4]))
         nb = int(rng.choice([0, 16] if v_bits == 4 else [0, 16, 32, 64, 128]))
         sink = int(rng.choice([0, 0, 7, 32, 128]))
@@ -209,7 +212,7 @@ def test_randomized_configurations():
         # short, peaky sequences are the worst case of the fixed-point images: up to 3.2e-4 with the 20-bit images
         # (measured over all variants); eight-head groups with 4-bit Values keep a two-term image of p*scale (up to
         # 1.4e-3); the stated bar is 2e-3
-        tol = 1.6e-3 if (g == 8 and v_bits == 4) else 5e-4
+        tol = 1.6e-3 if (g > 4 and v_bits == 4) else 5e-4
         tag = dict(trial=trial, hkv=hkv, g=g, v_bits=v_bits, nb=nb, sink=sink, v_local=v_local, metric=metric, B=B,
                    n_splits=n_splits, max_pages=max_pages, lengths=lengths)
         q = synth.query(w)
