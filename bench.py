@@ -48,7 +48,7 @@ def parse():
     ap.add_argument("--two-calls", action="store_true",
                     help="step = kitty_append_token + kitty_decode_attention instead of the single kitty_decode_step call")
     ap.add_argument("--n-boost", type=int, default=-1,
-                    help="override the workload's boosted-channel count (0, 16, 32, 64 or 128): the variant sweep")
+                    help="override the workload's boosted-channel count (a multiple of 16 up to 128): the variant sweep")
     ap.add_argument("--v-bits", type=int, default=2, choices=[2, 4],
                     help="4: Values quantized to 4 bits (the K2V4-like variants; n_boost 0 or 16)")
     ap.add_argument("--sink-tokens", type=int, default=0,

@@ -36,7 +36,7 @@ typedef struct kitty_layout {
   int32_t head_dim;        /* D: channels per head; must be 128                                          */
   int32_t page_size;       /* G: Key quantization group = tokens per page (Sec. 4.1); must be 128        */
   int32_t v_group;         /* Value quantization group along D (per-token, Sec. 2.1); must equal D       */
-  int32_t n_boost;         /* boosted Key channels per page = boost fraction * D (Sec. 3.2): 0,16,32,64,128 */
+  int32_t n_boost;         /* boosted Key channels per page = boost fraction * D (Sec. 3.2): 0,16,..,128 */
   int32_t residual_window; /* R: full-precision tokens kept before a page forms (Sec. 4.3): 128, or 0    */
   int32_t n_q_heads;       /* query heads                                                                */
   int32_t n_kv_heads;      /* KV heads; n_q_heads / n_kv_heads must be an integer from 1 to 8           */

@@ -19,7 +19,6 @@ int check_layout(const kitty_layout* L) {
   if (L->head_dim != D || L->page_size != G || L->v_group != D) return KITTY_ERR_UNSUPPORTED;
   if (L->residual_window != 0 && L->residual_window != G) return KITTY_ERR_UNSUPPORTED;
   const int nb16 = L->n_boost / 16;
-  if (nb16 != 0 && nb16 != 1 && nb16 != 2 && nb16 != 4 && nb16 != 8) return KITTY_ERR_UNSUPPORTED;
   const int g = L->n_q_heads / L->n_kv_heads;
   if (g > 8) return KITTY_ERR_UNSUPPORTED;   // a block holds the heads of a group in 4 or 8 slots; unused slots carry a zero query
   if (L->sink_tokens < 0 || L->v_local < 0) return KITTY_ERR_INVALID_ARG;
@@ -112,7 +111,11 @@ int dispatch_variant(const kitty_layout* L, F&& f) {
     case 0: return f(std::integral_constant<int, 0>{}, std::false_type{});
     case 1: return f(std::integral_constant<int, 1>{}, std::false_type{});
     case 2: return f(std::integral_constant<int, 2>{}, std::false_type{});
+    case 3: return f(std::integral_constant<int, 3>{}, std::false_type{});
     case 4: return f(std::integral_constant<int, 4>{}, std::false_type{});
+    case 5: return f(std::integral_constant<int, 5>{}, std::false_type{});
+    case 6: return f(std::integral_constant<int, 6>{}, std::false_type{});
+    case 7: return f(std::integral_constant<int, 7>{}, std::false_type{});
     case 8: return f(std::integral_constant<int, 8>{}, std::false_type{});
   }
   return KITTY_ERR_UNSUPPORTED;
@@ -411,9 +414,9 @@ int launch_split(const kitty_layout* L, const kitty_cache* C, const void* q, flo
     using F2 = std::integral_constant<int, 2>;   // fused step, several ranges: the merge launch does that
     auto pick = [&](auto fu) {
       if (wide) {
-        // (eight-head groups with every channel boosted: 4-wavefront blocks only, one wavefront per SIMD, because
+        // (eight-head groups with more than 64 boosted channels: 4-wavefront blocks only, one wavefront per SIMD, because
         // their two-pass contractions need more than 256 registers)
-        if constexpr (NB == 8) go(I2{}, I4{}, fu);
+        if constexpr (NB > 4) go(I2{}, I4{}, fu);
         else if (big) go(I2{}, I8{}, fu);
         else go(I2{}, I4{}, fu);
       } else {

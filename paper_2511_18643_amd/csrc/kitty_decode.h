@@ -665,10 +665,10 @@ struct PageWorker {
 // Block = NW wavefronts (4 or 8); wavefront w takes pages p0+w, p0+w+NW, ... of the range and a slice of
 // the range's share of the rows held in full precision (Sink, window).
 // wavefronts per SIMD the kernel is compiled for (register budget 512 / n)
-// (eight-head groups with every channel boosted need more than 256 registers for their two-pass contractions:
+// (eight-head groups with more than 64 boosted channels need more than 256 registers for their two-pass contractions:
 // they run in 4-wavefront blocks with one wavefront per SIMD)
 template <int NB16, int HPL>
-constexpr int decode_waves_per_simd() { return (HPL == 2 && NB16 == 8) ? 1 : 2; }
+constexpr int decode_waves_per_simd() { return (HPL == 2 && NB16 > 4) ? 1 : 2; }
 
 // FUSED: the block first performs this (sequence, kv-head)'s share of kitty_append_token (flush a full window
 // into the fresh page, store the new token), then attends over the result; needs one range per (sequence,

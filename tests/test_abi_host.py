@@ -40,7 +40,8 @@ def test_unsupported_layouts_are_rejected():
     assert kitty.kitty_page_bytes(kitty.make_layout(32, 8, 16, page_size=64)) == 0
     assert kitty.kitty_page_bytes(kitty.make_layout(32, 8, 16, v_group=32)) == 0
     assert kitty.kitty_page_bytes(kitty.make_layout(32, 8, 24)) == 0           # not a multiple of 16
-    assert kitty.kitty_page_bytes(kitty.make_layout(32, 8, 48)) == 0           # unsupported count
+    assert kitty.kitty_page_bytes(kitty.make_layout(32, 8, 48)) == 9344 + 3 * 512   # every multiple of 16 up to D
+    assert kitty.kitty_page_bytes(kitty.make_layout(32, 8, 144)) == 0          # more than D
     assert kitty.kitty_page_bytes(kitty.make_layout(32, 8, 16, residual_window=64)) == 0
     assert kitty.kitty_page_bytes(kitty.make_layout(30, 8, 16)) == 0           # heads do not divide
     assert kitty.kitty_page_bytes(kitty.make_layout(48, 8, 16)) == 9856        # any group of up to eight query heads

@@ -121,6 +121,7 @@ FUSED_CASES = [
     (8, 0, 0, 4), (8, 16, 1, 40), (8, 32, 0, 4), (8, 32, 1, 40), (8, 32, 2, 80), (8, 32, 2, 4), (8, 32, 12, 24),
     (8, 64, 0, 4), (8, 64, 1, 40), (8, 64, 2, 80), (8, 64, 12, 24), (8, 128, 0, 4), (8, 128, 1, 40), (8, 128, 2, 80),
     (8, 128, 12, 24),
+    (4, 48, 0, 4), (4, 96, 2, 80), (8, 48, 0, 4), (8, 48, 2, 80), (8, 80, 1, 40), (8, 96, 12, 24), (8, 112, 0, 4),
     (3, 16, 0, 4), (3, 16, 2, 80), (5, 16, 0, 4), (5, 32, 2, 80), (6, 32, 1, 40), (7, 64, 12, 24),
 ]
 

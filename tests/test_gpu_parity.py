@@ -64,7 +64,7 @@ def test_c1_both_metrics():
         run_case(synth.scaled(w, rank_metric=metric), [1024], n_splits_list=(0, 1, 2, 8))
 
 
-@pytest.mark.parametrize("nb", [0, 16, 32, 64, 128])
+@pytest.mark.parametrize("nb", [0, 16, 32, 48, 64, 80, 96, 112, 128])
 def test_boost_counts(nb):
     w = synth.scaled(synth.WORKLOADS["c2"], batch=2, n_q_heads=8, n_kv_heads=2, n_boost=nb)
     run_case(w, [5 * 128 + 60, 3 * 128 + 128], n_splits_list=(0, 2))
