@@ -66,7 +66,7 @@ def test_non_boosted_channels_have_no_high_bits():
 def test_boost_count_follows_fraction():
     # Sec. 3.2 footnote: boosting 25 % of a 128-wide head means K = 32
     assert int(0.25 * 128) == 32 and int(0.125 * 128) == 16
-    for nb in (0, 16, 32, 128):
+    for nb in range(0, 129, 16):
         assert len(ko.quantize_k_page(page(3), nb, 0).ch) == nb
 
 
@@ -209,6 +209,9 @@ def test_golden_words_and_sizes():
     # payload closed form: K page D*G/4 + Db*G/4 + 4D + Db, V page D*G/4 + 4G
     assert ko.RecordLayout(16).payload_bytes == 5136 + 4608
     assert ko.RecordLayout(32).payload_bytes == 5664 + 4608
+    for nb in range(0, 129, 16):   # every boost count: 32 plane bytes and one list byte per boosted channel
+        assert ko.RecordLayout(nb).record_bytes == 9344 + 32 * nb
+        assert ko.RecordLayout(nb).payload_bytes == 4096 + 32 * nb + 512 + nb + 4608
 
 
 def test_paper_byte_packing_example():
@@ -230,7 +233,7 @@ def test_paper_byte_packing_example():
     assert np.array_equal(ko.dequant_paper_tensors(t2, th, idx, kp2.scale, kp2.zero, 16), ko.dequant_k(kp2))
 
 
-@pytest.mark.parametrize("nb", [0, 16, 32, 128])
+@pytest.mark.parametrize("nb", list(range(0, 129, 16)))
 def test_pack_unpack_roundtrip(nb):
     x = page(13 + nb)
     kp = ko.quantize_k_page(x, nb, 0)
