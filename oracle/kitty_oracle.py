@@ -220,7 +220,9 @@ class RecordLayout:
       K dense  (low 2 bits of every channel), word (t, cb) = channels 16cb..16cb+15 of token t
                at  1024*(t//32) + 16*((t%16) + 16*(cb%4)) + 4*(2*((t//16)%2) + cb//4)
       K boost  (high 2 bits of boosted channels), word (t, s) = slots 16s..16s+15 of token t
-               at  kb_off + 512*s + 8*((t%16) + 16*((t//16)%4)) + 4*(t//64)
+               with T = t//16, j = t%16: n_boost = 16 at  kb_off + 8*(16*(T%4) + j) + 4*(T//4), otherwise
+               at  kb_off + 512*s + 16*(16*(T//4) + j) + 4*(T%4)  (pieces of 2 or 4 words: the words a lane of
+               the decode kernel reads together)
       k_scale, k_zero   fp16[128], channel order
       ch       uint8[n_boost] ascending boosted channels, zero-padded to 128 bytes
       V codes, word (d, wv) = positions 16wv..16wv+15 of channel d, where the token at
@@ -260,7 +262,10 @@ class RecordLayout:
         return 1024 * (t // 32) + 16 * ((t % 16) + 16 * (cb % 4)) + 4 * (2 * ((t // 16) % 2) + cb // 4)
 
     def kb_word_off(self, t, s):
-        return self.kb_off + 512 * s + 8 * ((t % 16) + 16 * ((t // 16) % 4)) + 4 * (t // 64)
+        T, j = t // 16, t % 16
+        if self.n_boost == 16:
+            return self.kb_off + 8 * (16 * (T % 4) + j) + 4 * (T // 4) + 0 * s
+        return self.kb_off + 512 * s + 16 * (16 * (T // 4) + j) + 4 * (T % 4)
 
     def vd_word_off(self, d, wv):
         return self.vd_off + 1024 * (d // 32) + 16 * ((d % 16) + 16 * (wv % 4)) + 4 * (2 * ((d // 16) % 2) + wv // 4)

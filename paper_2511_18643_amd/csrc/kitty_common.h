@@ -10,7 +10,8 @@ constexpr int G = 128;   // page_size
 
 // Byte offsets inside one (page, kv-head) record; NB16 = n_boost / 16.
 //   K dense plane   4096 B   word (t, cb) at 1024*(t/32) + 16*((t%16) + 16*(cb%4)) + 4*(2*((t/16)%2) + cb/4)
-//   K boost plane   512*NB16 word (t, s)  at 512*s + 8*((t%16) + 16*((t/16)%4)) + 4*(t/64)
+//   K boost plane   512*NB16 word (t, s), T = t/16, j = t%16: NB16 == 1 at 8*(16*(T%4) + j) + 4*(T/4); otherwise at
+//                   512*s + 16*(16*(T/4) + j) + 4*(T%4): the words a decode lane reads together are contiguous
 //   k_scale, k_zero fp16[128] each, channel order
 //   ch              uint8[n_boost] ascending, zero-padded to 128 B
 //   V plane         4096 B   word (d, wv) at 1024*(d/32) + 16*((d%16) + 16*(wv%4)) + 4*(2*((d/16)%2) + wv/4)

@@ -86,10 +86,28 @@ __device__ __forceinline__ int active_splits(int np, int r, int n_splits, int mi
 // One page's code planes as they sit in a lane's registers.  The four fp16 arrays travel separately: lane
 // group 0 fetches k_scale, 1 k_zero, 2 v_scale, 3 v_zero (entries 8j..8j+7 each) and the groups exchange
 // them through LDS.
+// How the boost plane (16*NB16 slots per token) meets the 64-deep contraction of a matrix instruction.  P slot
+// blocks of 16 sit side by side in an operand's four k-blocks; with P < 4 the other k-blocks carry the same slot
+// blocks of F - 1 further token tiles, and the tile is chosen by zeroing the query-side operand in the k-blocks of
+// the others.  More than 64 slots take KG operands per tile.  Lane (j, k-block kb) holds, per operand, slot block
+// kb % P (+ 4 per further operand) of the WPG token tiles WPG * (kb / P) + v (P = 1: tiles kb and 4 + kb): words
+// that are contiguous in the record.
+template <int NB16>
+struct BoostShape {
+  static constexpr int P = NB16 <= 1 ? 1 : (NB16 == 2 ? 2 : 4);
+  static constexpr int F = 4 / P;
+  static constexpr int KG = NB16 > 4 ? 2 : 1;
+  static constexpr int WPG = 2 * P;                      // words per lane and operand (8 token tiles / F)
+  static constexpr int WORDS = NB16 ? WPG * KG : 1;
+  static constexpr int COLS = NB16 == 0 ? 16 : (NB16 <= 2 ? 16 * NB16 : 64 * KG);   // slot columns of the query-side operand
+  // token tile of word v of a lane whose k-block belongs to tile class f
+  static constexpr int tile(int f, int v) { return P == 1 ? 4 * v + f : WPG * f + v; }
+};
+
 template <int NB16, bool V4 = false>
 struct PageRegs {
   uint4 kd[4];
-  uint2 kb[NB16 ? NB16 : 1];
+  uint32_t kbw[BoostShape<NB16>::WORDS];   // boost plane, see BoostShape
   uint32_t chv[NB16 ? NB16 : 1];
   uint4 vd[4];
   uint4 vh[V4 ? 4 : 1];   // high Value plane (4-bit Values)
@@ -97,14 +115,26 @@ struct PageRegs {
 
 // Byte offsets of a lane into a record (32-bit, so loads take the scalar record base + one VGPR offset).
 struct LaneOffsets {
-  uint32_t o16, o8, j, meta;
+  uint32_t o16, j, meta;
+  uint32_t ob[2];   // the lane's words of the boost plane, per operand; beyond the record (reads as zeros) if it has none
 };
 template <int NB16, bool V4>
 __device__ __forceinline__ LaneOffsets lane_offsets(int l) {
   using R = Rec<NB16, V4>;
+  using BS = BoostShape<NB16>;
   const uint32_t j = l & 15, gi = l >> 4;
   const uint32_t base = gi == 0 ? R::ks : (gi == 1 ? R::kz : (gi == 2 ? R::vs : R::vz));
-  return LaneOffsets{(uint32_t)l * 16u, (uint32_t)l * 8u, j, base + 16u * j};
+  LaneOffsets o{(uint32_t)l * 16u, j, base + 16u * j, {0u, 0u}};
+  constexpr uint32_t NONE = 0x40000000u;
+  if constexpr (BS::P == 1) {          // tiles kb and 4 + kb: 8 bytes, lanes in order
+    o.ob[0] = R::kb + 8u * (uint32_t)l;
+  } else if constexpr (BS::P == 2) {   // slot block kb % 2, tiles 4*(kb/2) .. +3: 16 bytes
+    o.ob[0] = R::kb + 512u * (gi & 1u) + 256u * (gi >> 1) + 16u * j;
+  } else {                             // slot block 4q + kb, all eight tiles: two pieces of 16 bytes, 256 apart
+#pragma unroll
+    for (int q = 0; q < BS::KG; ++q) o.ob[q] = (4 * q + (int)gi < NB16) ? R::kb + 512u * (4u * q + gi) + 16u * j : NONE;
+  }
+  return o;
 }
 
 // A page is fetched in three pieces: the lane's 16 bytes of fp16 arrays, the Key planes (+ channel list), the
@@ -139,12 +169,25 @@ __device__ __forceinline__ void load_k(PageRegs<NB16, V4>& r, RecRef rec, const 
   using R = Rec<NB16, V4>;
 #pragma unroll
   for (int i = 0; i < 4; ++i) r.kd[i] = buf_load16(rec, o.o16, R::kd + 1024 * i);
+  using BS = BoostShape<NB16>;
+  if constexpr (NB16 > 0) {
+    if constexpr (BS::P == 1) {
+      const v2u v = __builtin_amdgcn_raw_buffer_load_b64(rec, o.ob[0], 0, REC_LOAD_POLICY);
+      r.kbw[0] = v.x; r.kbw[1] = v.y;
+    } else if constexpr (BS::P == 2) {
+      const uint4 v = buf_load16(rec, o.ob[0], 0);
+      r.kbw[0] = v.x; r.kbw[1] = v.y; r.kbw[2] = v.z; r.kbw[3] = v.w;
+    } else {
 #pragma unroll
-  for (int s = 0; s < NB16; ++s) {
-    const v2u v = __builtin_amdgcn_raw_buffer_load_b64(rec, o.o8, R::kb + 512 * s, REC_LOAD_POLICY);
-    r.kb[s] = make_uint2(v.x, v.y);
-    r.chv[s] = __builtin_amdgcn_raw_buffer_load_b8(rec, o.j, R::ch + 16 * s, 0);
+      for (int q = 0; q < BS::KG; ++q) {
+        const uint4 v0 = buf_load16(rec, o.ob[q], 0), v1 = buf_load16(rec, o.ob[q], 256);
+        r.kbw[8 * q + 0] = v0.x; r.kbw[8 * q + 1] = v0.y; r.kbw[8 * q + 2] = v0.z; r.kbw[8 * q + 3] = v0.w;
+        r.kbw[8 * q + 4] = v1.x; r.kbw[8 * q + 5] = v1.y; r.kbw[8 * q + 6] = v1.z; r.kbw[8 * q + 7] = v1.w;
+      }
+    }
   }
+#pragma unroll
+  for (int s = 0; s < NB16; ++s) r.chv[s] = __builtin_amdgcn_raw_buffer_load_b8(rec, o.j, R::ch + 16 * s, 0);
 }
 template <int NB16, bool V4>
 __device__ __forceinline__ void load_v(PageRegs<NB16, V4>& r, RecRef rec, const LaneOffsets& o) {
@@ -294,7 +337,7 @@ struct WaveScratch {
   static constexpr int NPITCH = D + (HPL == 1 ? 8 : 4);
   uint32_t nbuf[4 * HPL][NPITCH];
   uint8_t abuf[16 * HPL][144];                         // rows (head, term) x channel; one 16-row matrix per pass
-  uint8_t bbuf[16 * HPL][16 * (NB16 ? NB16 : 1) + 16];  // rows (head, term) x boost slot
+  uint8_t bbuf[16 * HPL][BoostShape<NB16>::COLS + 16];  // rows (head, term) x boost slot (columns of absent slots stay zero)
   uint8_t pbuf[16 * HPL][144];                         // rows (head, term) x position
   float pw[32][8];                               // full-precision rows: softmax weights [row][head]
   float pcorr[8];                                // same path: rescale factor of the running sums per head
@@ -363,7 +406,7 @@ struct PageWorker {
   const int j, gi;
   const uint8_t* a_ptr;      // A operand of the logits: row j, k-block gi (second matrix 16 rows further)
   const uint8_t* p_ptr;      // A operand of the Value sum
-  const uint8_t* b_ptr[4];   // boost rows for tile kb (zeros unless gi == kb)
+  const uint8_t* b_own;      // boost operand: row j, the columns of this lane's slot block (k-block gi % P)
   LaneOffsets lo;            // byte offsets of the lane into a record
   float qv[HPL][8];          // q * sm_scale * log2(e) divided by the weight, compact layout
   float m_run[HPL], l_run[HPL], z_run[HPL];
@@ -371,14 +414,14 @@ struct PageWorker {
   float acc_unit[HPL];
 
   static constexpr int A_PASS = 16 * 144;                           // bytes between the two matrices
-  static constexpr int B_PASS = 16 * (16 * (NB16 ? NB16 : 1) + 16);
+  using BS = BoostShape<NB16>;
+  static constexpr int B_PASS = 16 * (BS::COLS + 16);
 
   __device__ __forceinline__ PageWorker(WaveScratch<NB16, HPL>& ws_, int l)
       : ws(ws_), j(l & 15), gi(l >> 4), lo(lane_offsets<NB16, V4>(l)) {
     a_ptr = &ws.abuf[j][16 * gi];
     p_ptr = &ws.pbuf[j][16 * gi];
-#pragma unroll
-    for (int kb = 0; kb < 4; ++kb) b_ptr[kb] = (gi == kb) ? &ws.bbuf[j][0] : ws.zero;
+    b_own = &ws.bbuf[j][16 * (gi % BS::P)];
 #pragma unroll
     for (int e = 0; e < HPL; ++e) {
       m_run[e] = -INFINITY; l_run[e] = 0.f; z_run[e] = 0.f; acc_unit[e] = 1.f;
@@ -507,24 +550,35 @@ struct PageWorker {
         }
       }
       if constexpr (NB16 > 0) {
+        // Boost plane: per operand q (64 slots) and tile class f the query-side operand is read with the k-blocks
+        // of the other classes zeroed (an LDS address select), then one matrix instruction per tile.
 #pragma unroll
-        for (int s = 0; s < NB16; ++s) {
-          // tile 4u+kb of the boost plane lives in the lanes of k-block kb: feed A only to that block
-          v4i ab[4], abx[TWO_PASS_K ? 4 : 1];
+        for (int q = 0; q < BS::KG; ++q) {
+          v4i ab[BS::F], abx[TWO_PASS_K ? BS::F : 1];
 #pragma unroll
-          for (int kb = 0; kb < 4; ++kb) {
-            ab[kb] = *reinterpret_cast<const v4i*>(b_ptr[kb] + (gi == kb ? 16 * s : 0));
-            if constexpr (TWO_PASS_K) abx[kb] = *reinterpret_cast<const v4i*>(b_ptr[kb] + (gi == kb ? B_PASS + 16 * s : 0));
+          for (int f = 0; f < BS::F; ++f) {
+            bool used = false;
+#pragma unroll
+            for (int v = 0; v < BS::WPG; ++v) used |= (BS::tile(f, v) / TP == uu);
+            if (!used) continue;
+            const bool mine = (gi / BS::P) == f;
+            ab[f] = *reinterpret_cast<const v4i*>(mine ? b_own + 64 * q : ws.zero);
+            if constexpr (TWO_PASS_K) abx[f] = *reinterpret_cast<const v4i*>(mine ? b_own + B_PASS + 64 * q : ws.zero);
           }
 #pragma unroll
-          for (int u = (NU == 2 ? uu : 0); u < (NU == 2 ? uu + 1 : 2); ++u) {
-            const v4i bb = unpack16_x4(u ? pg.kb[s].y : pg.kb[s].x);
-            const int base = NU == 2 ? 0 : 4 * u;
+          for (int v = 0; v < BS::WPG; ++v) {
+            bool used = false;
 #pragma unroll
-            for (int kb = 0; kb < 4; ++kb) {
-              dq[base + kb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ab[kb], bb, dq[base + kb], 0, 0, 0);
+            for (int f = 0; f < BS::F; ++f) used |= (BS::tile(f, v) / TP == uu);
+            if (!used) continue;
+            const v4i bb = unpack16_x4(pg.kbw[BS::WPG * q + v]);
+#pragma unroll
+            for (int f = 0; f < BS::F; ++f) {
+              const int T = BS::tile(f, v);
+              if (T / TP != uu) continue;
+              dq[T % TP] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ab[f], bb, dq[T % TP], 0, 0, 0);
               if constexpr (TWO_PASS_K)
-                dqx[base + kb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(abx[kb], bb, dqx[base + kb], 0, 0, 0);
+                dqx[T % TP] = __builtin_amdgcn_mfma_i32_16x16x64_i8(abx[f], bb, dqx[T % TP], 0, 0, 0);
             }
           }
         }
@@ -1043,7 +1097,14 @@ __global__ __launch_bounds__(64 * (NW + (ROWW ? 1 : 0)), (ROWW ? 3 : decode_wave
       // simply alternate.
       int turn = 0;
       int k = 0;
-      for (; idx < p1q; idx += NW) {
+      // PEEL: every page but the wavefront's last requests the next one; those run in a loop whose loads are
+      // unconditional, so that the compiler's waits for them are exact, and the last page follows the loop.
+      // Otherwise one loop with the next page's loads behind a branch: the compiler then drains the load queue in
+      // the middle of every page, which happens to pace the requests of the 8-wavefront blocks of four-head groups
+      // well (32k workload: 97.6 us against 101.5 us peeled); eight-head groups and 4-wavefront blocks stream
+      // better peeled (128k workload 137 against 141 us; the 36-layer loop 7.94 against 8.17 ms per step).
+      constexpr bool PEEL = HPL == 2 || NW == 4;
+      for (; PEEL ? idx + NW < p1 : idx < p1q; idx += NW) {
         const bool has_nx = idx + NW < p1;
         const bool high = NW == 4 ? (turn & 1) != 0 : (w >= 4 ? (turn & 3) != 0 : (turn & 3) == 0);
         if (high) __builtin_amdgcn_s_setprio(1); else __builtin_amdgcn_s_setprio(0);
@@ -1054,7 +1115,14 @@ __global__ __launch_bounds__(64 * (NW + (ROWW ? 1 : 0)), (ROWW ? 3 : decode_wave
         // the whole load queue, the current page's Value plane included, before every page (+5 % on the 32k
         // workload).
         if ((k & 63) == 0) ids = max(load_ids(k), 0);
-        pw.process(pg, rec_ref<NB16, V4>(has_nx ? rec_at(k, idx + NW) : pool_h), has_nx);
+        if constexpr (PEEL) pw.process(pg, rec_ref<NB16, V4>(rec_at(k, idx + NW)), true);   // (a constant: no branches around the loads)
+        else pw.process(pg, rec_ref<NB16, V4>(has_nx ? rec_at(k, idx + NW) : pool_h), has_nx);
+      }
+      if constexpr (PEEL) {
+        if (idx < p1q) {
+          pw.process(pg, rec_ref<NB16, V4>(pool_h), false);
+          idx += NW;
+        }
       }
       __builtin_amdgcn_s_setprio(0);
       if (lag_here && idx == p1q) pw.logits_to(pg, lagx);   // this wavefront holds the newest page

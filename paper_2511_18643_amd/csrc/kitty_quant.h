@@ -286,15 +286,18 @@ __device__ __forceinline__ void quantize_page(QuantSmem& s, const uint16_t* __re
     plane_store16<STREAM>(rec + R::kd + 16 * tid, *reinterpret_cast<const uint4*>(&s.pk.kout[4 * tid]));
     if constexpr (NB16 > 0) {   // boost plane: high two bits of the boosted channels, slot order
       for (int idx = tid; idx < 128 * NB16; idx += 256) {
-        const int sblk = idx >> 7, u = (idx >> 6) & 1, lane = idx & 63;
-        const int t = 16 * (4 * u + (lane >> 4)) + (lane & 15);
+        // word idx % 128 of slot block idx / 128: the inverse of the plane's placement formula (pieces of W words,
+        // W = 2 with one slot block, else 4); a wavefront stores 256 consecutive bytes and reads 64 different tokens
+        const int sblk = idx >> 7, wi = idx & 127;
+        const int t = NB16 == 1 ? 16 * (4 * (wi & 1) + (wi >> 5)) + ((wi >> 1) & 15)
+                                : 16 * (4 * (wi >> 6) + (wi & 3)) + ((wi >> 2) & 15);
         uint32_t word = 0;
 #pragma unroll
         for (int a = 0; a < 16; ++a) {
           const uint32_t code = s.pk.codes[t][s.chl[16 * sblk + a]];
           word |= (code >> 2) << (8 * (a & 3) + 2 * (a >> 2));
         }
-        plane_store4<STREAM>(rec + R::kb + 512 * sblk + 8 * lane + 4 * u, word);
+        plane_store4<STREAM>(rec + R::kb + 512 * sblk + 4 * wi, word);
       }
     }
     // ---------------- Value codes: half a word per channel and thread ----------------

@@ -248,9 +248,9 @@ def test_pack_unpack_roundtrip(nb):
     assert np.all(rec[lay.ch_off + nb:lay.vd_off] == 0)          # pad bytes are zero
 
 
-def test_record_bits_brute_force_from_formulas():
+@pytest.mark.parametrize("nb", [32, 16, 96])
+def test_record_bits_brute_force_from_formulas(nb):
     """Read single elements out of a record with scalar code written from the layout text."""
-    nb = 32
     x = page(15)
     kp = ko.quantize_k_page(x, nb, 0)
     vp = ko.quantize_v_page(page(16, outliers=()))
@@ -277,7 +277,10 @@ def test_record_bits_brute_force_from_formulas():
         if c in ch:
             slot = ch.index(c)
             s, a2 = slot // 16, slot % 16
-            off = kb_off + 512 * s + 8 * ((t % 16) + 16 * ((t // 16) % 4)) + 4 * (t // 64)
+            if nb == 16:    # pieces of two words: token tiles T % 4 and 4 + T % 4 of token column t % 16 side by side
+                off = kb_off + 8 * ((t % 16) + 16 * ((t // 16) % 4)) + 4 * (t // 64)
+            else:           # pieces of four words: tiles 4*(T//4)..+3
+                off = kb_off + 512 * s + 256 * (t // 64) + 16 * (t % 16) + 4 * ((t // 16) % 4)
             hi = field(off, a2)
         assert lo | (hi << 2) == kp.codes[t, c]
         # V: token t sits at position p = 8*(t%16) + t//16 of channel c's row
