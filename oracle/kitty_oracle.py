@@ -264,7 +264,7 @@ class RecordLayout:
     def kb_word_off(self, t, s):
         T, j = t // 16, t % 16
         if self.n_boost == 16:
-            return self.kb_off + 8 * (16 * (T % 4) + j) + 4 * (T // 4) + 0 * s
+            return self.kb_off + 512 * s + 8 * (16 * (T % 4) + j) + 4 * (T // 4)      # (s is 0: one slot block)
         return self.kb_off + 512 * s + 16 * (16 * (T // 4) + j) + 4 * (T % 4)
 
     def vd_word_off(self, d, wv):
