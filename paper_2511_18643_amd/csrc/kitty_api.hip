@@ -4,8 +4,8 @@
 #include <mutex>
 #include <type_traits>
 
-#include "kitty_decode.h"
-#include "kitty_prefill.h"
+#include "kitty_launch.h"
+#include "kitty_merge.h"
 
 namespace {
 
@@ -261,7 +261,7 @@ int kitty_quantize_pages(const kitty_layout* L, const void* k_src, const void* v
   return dispatch_variant(L, [&](auto nb, auto v4) {
     constexpr int NB = decltype(nb)::value;
     constexpr bool V4 = decltype(v4)::value;
-    hipLaunchKernelGGL((quantize_pages_kernel<NB, V4>), dim3((unsigned)((int64_t)n_pages * L->n_kv_heads)), dim3(256), 0, st, P);
+    launch_quantize_pages<NB, V4>(P, (unsigned)((int64_t)n_pages * L->n_kv_heads), st);
     return launch_status();
   });
 }
@@ -297,7 +297,7 @@ int kitty_project_quantize_pages(const kitty_layout* L, const void* x, int64_t x
   return dispatch_variant(L, [&](auto nb, auto v4) {
     constexpr int NB = decltype(nb)::value;
     constexpr bool V4 = decltype(v4)::value;
-    hipLaunchKernelGGL((project_quantize_pages_kernel<NB, V4>), dim3(n_pages, L->n_kv_heads), dim3(256), 0, st, P);
+    launch_project_quantize_pages<NB, V4>(P, dim3(n_pages, L->n_kv_heads), st);
     return launch_status();
   });
 }
@@ -336,7 +336,7 @@ int kitty_append_token(const kitty_layout* L, const kitty_cache* C, const void* 
   return dispatch_variant(L, [&](auto nb, auto v4) {
     constexpr int NB = decltype(nb)::value;
     constexpr bool V4 = decltype(v4)::value;
-    hipLaunchKernelGGL((append_token_kernel<NB, V4>), dim3(L->n_kv_heads, C->batch), dim3(256), 0, st, P);
+    launch_append_token<NB, V4>(P, dim3(L->n_kv_heads, C->batch), st);
     return launch_status();
   });
 }
@@ -380,52 +380,14 @@ int launch_split(const kitty_layout* L, const kitty_cache* C, const void* q, flo
     P.n_sink_w = C->n_sink;
   }
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  const dim3 grid(P.n_splits, L->n_kv_heads, C->batch);
-  const bool wide = P.gqa > 4;   // more than four query heads per kv-head: eight head slots per block
-  const bool big = waves_per_block(C->max_pages, P.n_splits, (int64_t)P.n_splits * L->n_kv_heads * C->batch) == 8;
-  const bool fused = step != nullptr;
+  SplitLaunch sl;
+  sl.grid = dim3(P.n_splits, L->n_kv_heads, C->batch);
+  sl.wide = P.gqa > 4;   // more than four query heads per kv-head: eight head slots per block
+  sl.big = waves_per_block(C->max_pages, P.n_splits, (int64_t)P.n_splits * L->n_kv_heads * C->batch) == 8;
+  sl.row_wave = !L->v_local;
+  sl.fused = step == nullptr ? 0 : (P.direct_out ? 1 : 2);
   return dispatch_variant(L, [&](auto nb, auto v4) {
-    constexpr int NB = decltype(nb)::value;
-    constexpr bool V4 = decltype(v4)::value;
-    auto go = [&](auto hpl, auto nw, auto fu) {
-      constexpr int HPL = decltype(hpl)::value, NW = decltype(nw)::value;
-      constexpr int FU = decltype(fu)::value;
-      hipLaunchKernelGGL((decode_split_kernel<NB, HPL, NW, FU, V4>), grid, dim3(64 * NW), 0, st, P);
-    };
-    using I1 = std::integral_constant<int, 1>; using I2 = std::integral_constant<int, 2>;
-    using I4 = std::integral_constant<int, 4>; using I8 = std::integral_constant<int, 8>;
-    // 8-wavefront blocks of the variants that fit 168 registers get a ninth wavefront for the full-precision rows
-    // (32k workload -1 %, 8k workload -12 %); not with the Value Local window, whose rows can only follow the
-    // pages (+2 % there)
-    constexpr bool ROWW_OK = V4 ? NB == 0 : NB <= 2;
-    const bool row_wave = !L->v_local;
-    auto go_rows = [&](auto fu) {
-      constexpr int FU = decltype(fu)::value;
-      if constexpr (ROWW_OK) {
-        if (row_wave) {
-          hipLaunchKernelGGL((decode_split_kernel<NB, 1, 8, FU, V4, true>), grid, dim3(64 * 9), 0, st, P);
-          return;
-        }
-      }
-      go(I1{}, I8{}, fu);
-    };
-    using F0 = std::integral_constant<int, 0>;   // attention only
-    using F1 = std::integral_constant<int, 1>;   // fused step, one range: the kernel also stores the token and advances the state
-    using F2 = std::integral_constant<int, 2>;   // fused step, several ranges: the merge launch does that
-    auto pick = [&](auto fu) {
-      if (wide) {
-        // (eight-head groups with more than 64 boosted channels: 4-wavefront blocks only, one wavefront per SIMD, because
-        // their two-pass contractions need more than 256 registers)
-        if constexpr (NB > 4) go(I2{}, I4{}, fu);
-        else if (big) go(I2{}, I8{}, fu);
-        else go(I2{}, I4{}, fu);
-      } else {
-        if (big) go_rows(fu); else go(I1{}, I4{}, fu);
-      }
-    };
-    if (!fused) pick(F0{});
-    else if (P.direct_out) pick(F1{});
-    else pick(F2{});
+    launch_decode_split<decltype(nb)::value, decltype(v4)::value>(P, sl, st);
     return launch_status();
   });
 }

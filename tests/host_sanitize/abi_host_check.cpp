@@ -116,8 +116,6 @@ int main() {
   return 0;
 }
 
-// The library's host code is built here without its device code (host pass only, -fuse-cuid=none): this empty
-// stand-in satisfies the reference to the device image, which is never looked at because nothing is launched.
-extern "C" {
-__attribute__((section(".hip_fatbin"), used)) unsigned long long __hip_fatbin[8] = {0};
-}
+// The library's host code is built here without its device code (host pass only).  The references of its translation
+// units to their device images are satisfied by empty stand-ins that the test generates (one per unit, named after
+// the unit's compilation id); they are never looked at because nothing is launched.
