@@ -33,10 +33,10 @@ void launch_decode_split(const DecodeParams& P, const SplitLaunch& s, hipStream_
   };
   using I1 = std::integral_constant<int, 1>; using I2 = std::integral_constant<int, 2>;
   using I4 = std::integral_constant<int, 4>; using I8 = std::integral_constant<int, 8>;
-  // 8-wavefront blocks of the variants that fit 168 registers get a ninth wavefront for the full-precision rows
-  // (32k workload -1 %, 8k workload -12 %); not with the Value Local window, whose rows can only follow the
-  // pages (+2 % there)
-  constexpr bool ROWW_OK = V4 ? NB == 0 : NB <= 2;
+  // 8-wavefront blocks of the variants that fit 168 registers (2-bit Values with any boost count; 4-bit Values
+  // without boosted channels) get a ninth wavefront for the full-precision rows (32k workload -1 to -3 %, 8k
+  // workload -12 %); not with the Value Local window, whose rows can only follow the pages (+2 % there)
+  constexpr bool ROWW_OK = V4 ? NB == 0 : true;
   auto go_rows = [&](auto fu) {
     constexpr int FU = decltype(fu)::value;
     if constexpr (ROWW_OK) {
