@@ -50,7 +50,7 @@ def parse():
     ap.add_argument("--n-boost", type=int, default=-1,
                     help="override the workload's boosted-channel count (a multiple of 16 up to 128): the variant sweep")
     ap.add_argument("--v-bits", type=int, default=2, choices=[2, 4],
-                    help="4: Values quantized to 4 bits (the K2V4-like variants; n_boost 0 or 16)")
+                    help="4: Values quantized to 4 bits (the K2V4- and K4V4-like variants)")
     ap.add_argument("--sink-tokens", type=int, default=0,
                     help="keep this many initial tokens in full precision (the paper's Sink; parity covered by the tests, "
                          "the CPU baseline leg is skipped)")

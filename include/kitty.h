@@ -47,8 +47,7 @@ typedef struct kitty_layout {
   int32_t v_local;         /* Value Local window (Fig. 1, Sec. 4.3 step 1): 0 = off, 128 = the Values of the newest
                               page are read in full precision until the next page forms; needs R = 128       */
   int32_t v_bits;          /* bits per Value code: 2 (the method; 0 means 2) or 4 (the K2V4 / K4V4-like points of the
-                              design-space study, Table 2: a second Value plane holds the high bits); 4 needs
-                              n_boost 0 or 16                                                                  */
+                              design-space study, Table 2: a second Value plane holds the high bits)          */
 } kitty_layout;
 
 /* One batch's cache.  All pointers are device pointers.

@@ -20,7 +20,7 @@ FLAGS = [
 
 # record variants (16-channel boost blocks, 4-bit Values): one translation unit each (csrc/kitty_variant.hip), the
 # same set kitty_api.hip dispatches to
-VARIANTS = [(nb, 0) for nb in range(9)] + [(0, 1), (1, 1)]
+VARIANTS = [(nb, 0) for nb in range(9)] + [(nb, 1) for nb in range(9)]
 
 
 def translation_units(extra: list[str] | None = None) -> list[tuple[str, str, list[str]]]:

@@ -25,7 +25,6 @@ int check_layout(const kitty_layout* L) {
   if (L->sink_tokens > G) return KITTY_ERR_UNSUPPORTED;
   if (L->v_local != 0 && (L->v_local != G || L->residual_window != G)) return KITTY_ERR_UNSUPPORTED;
   if (L->v_bits != 0 && L->v_bits != 2 && L->v_bits != 4) return KITTY_ERR_INVALID_ARG;
-  if (L->v_bits == 4 && nb16 > 1) return KITTY_ERR_UNSUPPORTED;   // 4-bit Values: with n_boost 0 or 16 only
   return KITTY_OK;
 }
 
@@ -104,6 +103,13 @@ int dispatch_variant(const kitty_layout* L, F&& f) {
     switch (nb16) {
       case 0: return f(std::integral_constant<int, 0>{}, std::true_type{});
       case 1: return f(std::integral_constant<int, 1>{}, std::true_type{});
+      case 2: return f(std::integral_constant<int, 2>{}, std::true_type{});
+      case 3: return f(std::integral_constant<int, 3>{}, std::true_type{});
+      case 4: return f(std::integral_constant<int, 4>{}, std::true_type{});
+      case 5: return f(std::integral_constant<int, 5>{}, std::true_type{});
+      case 6: return f(std::integral_constant<int, 6>{}, std::true_type{});
+      case 7: return f(std::integral_constant<int, 7>{}, std::true_type{});
+      case 8: return f(std::integral_constant<int, 8>{}, std::true_type{});
     }
     return KITTY_ERR_UNSUPPORTED;
   }

@@ -48,11 +48,12 @@ def test_unsupported_layouts_are_rejected():
     assert kitty.kitty_page_bytes(kitty.make_layout(40, 8, 16)) == 9856
     assert kitty.kitty_page_bytes(kitty.make_layout(72, 8, 16)) == 0           # group of 9
     assert kitty.kitty_page_bytes(kitty.make_layout(32, 8, 16, rank_metric=2)) == 0
-    # 4-bit Values: one more 4 KB plane; only with 0 or 16 boosted channels
+    # 4-bit Values: one more 4 KB plane, with any boost count
     assert kitty.kitty_page_bytes(kitty.make_layout(32, 8, 16, v_bits=4)) == 9856 + 4096
     assert kitty.kitty_page_payload_bytes(kitty.make_layout(32, 8, 0, v_bits=4)) == 9216 + 4096
     assert kitty.kitty_page_bytes(kitty.make_layout(32, 8, 16, v_bits=0)) == 9856
-    assert kitty.kitty_page_bytes(kitty.make_layout(32, 8, 32, v_bits=4)) == 0
+    assert kitty.kitty_page_bytes(kitty.make_layout(32, 8, 32, v_bits=4)) == 10368 + 4096
+    assert kitty.kitty_page_bytes(kitty.make_layout(32, 8, 128, v_bits=4)) == 13440 + 4096     # 4-bit Keys and Values
     assert kitty.kitty_page_bytes(kitty.make_layout(32, 8, 16, v_bits=3)) == 0
     # Sink up to one page; the Value Local window is one page long and needs the residual window
     assert kitty.kitty_page_bytes(kitty.make_layout(32, 8, 16, sink_tokens=32, v_local=128)) == 9856

@@ -191,7 +191,7 @@ def test_randomized_configurations():
         hkv = int(rng.choice([1, 2, 4]))
         g = int(rng.choice([1, 2, 3, 4, 5, 6, 7, 8]))
         v_bits = int(rng.choice([2, 2, 4]))
-        nb = int(rng.choice([0, 16] if v_bits == 4 else [0, 16, 32, 48, 64, 80, 96, 112, 128]))
+        nb = int(rng.choice([0, 16, 32, 48, 64, 80, 96, 112, 128]))
         sink = int(rng.choice([0, 0, 7, 32, 128]))
         v_local = int(rng.choice([0, 128]))
         metric = int(rng.choice([0, 1]))

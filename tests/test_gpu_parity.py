@@ -476,7 +476,7 @@ def test_quantize_pages_reads_projection_layout_in_place():
 
 
 # ------------------------------------------------------------------ 4-bit Values (the K2V4 point of Table 2)
-@pytest.mark.parametrize("nb,hq", [(0, 8), (16, 8), (16, 16), (0, 2)])
+@pytest.mark.parametrize("nb,hq", [(0, 8), (16, 8), (16, 16), (0, 2), (32, 8), (32, 16), (64, 8), (96, 10), (128, 8), (128, 16)])
 def test_v4_values(nb, hq):
     """Second Value plane with the high bits: records bit-exact, attention within the same bounds; ragged
     lengths, several split plans."""
