@@ -414,7 +414,8 @@ int kitty_decode_merge(const kitty_layout* L, const kitty_cache* C, void* out, i
   P.out = out;
   P.out_dtype = out_dtype;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  hipLaunchKernelGGL(decode_merge_kernel, dim3(L->n_q_heads, C->batch), dim3(128), 0, st, P);
+  if (P.n_splits > 8) hipLaunchKernelGGL(decode_merge_kernel<true>, dim3(L->n_q_heads, C->batch), dim3(128), 0, st, P);
+  else hipLaunchKernelGGL(decode_merge_kernel<false>, dim3(L->n_q_heads, C->batch), dim3(128), 0, st, P);
   return launch_status();
 }
 
@@ -465,7 +466,9 @@ int kitty_decode_step(const kitty_layout* L, const kitty_cache* C, const void* k
   P.sink_k_w = static_cast<uint16_t*>(C->sink_k);
   P.sink_v_w = static_cast<uint16_t*>(C->sink_v);
   P.n_sink_w = C->n_sink;
-  hipLaunchKernelGGL(decode_merge_step_kernel, dim3(L->n_q_heads, C->batch), dim3(128), 0, static_cast<hipStream_t>(hip_stream), P);
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (P.n_splits > 8) hipLaunchKernelGGL(decode_merge_step_kernel<true>, dim3(L->n_q_heads, C->batch), dim3(128), 0, st, P);
+  else hipLaunchKernelGGL(decode_merge_step_kernel<false>, dim3(L->n_q_heads, C->batch), dim3(128), 0, st, P);
   return launch_status();
 }
 
