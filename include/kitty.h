@@ -66,7 +66,8 @@ typedef struct kitty_cache {
   const int32_t* seq_order; /* optional [batch] permutation of 0..batch-1, or NULL (identity): the decode kernels
                             dispatch their workgroups sequence by sequence in this order, so listing the longest
                             sequences first shortens the tail of a variable-length batch.  Results do not depend on
-                            it; entries outside [0, batch) are skipped, repeated entries are the caller's error   */
+                            it; entries outside [0, batch) are skipped, repeated entries are the caller's error,
+                            and the output of a sequence the order does not name is unspecified                   */
   int32_t  batch;
   int32_t  max_pages;    /* row length of page_table                                                     */
   int32_t  n_pool_pages;
