@@ -49,6 +49,7 @@ def parse():
                     help="step = kitty_append_token + kitty_decode_attention instead of the single kitty_decode_step call")
     ap.add_argument("--n-boost", type=int, default=-1,
                     help="override the workload's boosted-channel count (a multiple of 16 up to 128): the variant sweep")
+    ap.add_argument("--batch", type=int, default=0, help="c2-c4: override the workload's batch size (1 = one sequence: latency)")
     ap.add_argument("--v-bits", type=int, default=2, choices=[2, 4],
                     help="4: Values quantized to 4 bits (the K2V4- and K4V4-like variants)")
     ap.add_argument("--sink-tokens", type=int, default=0,
@@ -359,10 +360,11 @@ def other_workloads(args):
     import copy
     import torch
     out = {}
-    for name, pairs in (("c2", 16), ("c4", 2)):
+    for key, name, pairs, batch in (("c2", "c2", 16, 0), ("c4", "c4", 2, 0), ("c4_one_sequence", "c4", 1, 1)):
         a = copy.copy(args)
         a.steps, a.warmup, a.cpu_pairs, a.prewarm_ms = min(args.steps or 200, 100), min(args.warmup, 10), pairs, 150.0
-        out[name] = compact(run_layer(a, name, headline=False))
+        a.batch = batch      # (c4_one_sequence: one 128k-token sequence, the latency case; 32 ranges and a merge)
+        out[key] = compact(run_layer(a, name, headline=False))
         torch.cuda.empty_cache()
     a = copy.copy(args)
     a.steps, a.warmup, a.layers, a.prewarm_ms, a.cpu_pairs = min(args.steps or 16, 16), 2, 0, 150.0, 6
@@ -380,6 +382,8 @@ def run_layer(args, wname, headline):
     w = synth.WORKLOADS[wname]
     if args.n_boost >= 0:
         w = synth.scaled(w, n_boost=args.n_boost)
+    if getattr(args, "batch", 0):
+        w = synth.scaled(w, batch=args.batch)
     S, VL = args.sink_tokens, args.v_local
     full_scheme = bool(S or VL)
     if full_scheme:
